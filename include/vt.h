@@ -1,0 +1,167 @@
+/*
+ * vt.h - C ABI of the virtual-tensor library for MI355X (gfx950).
+ *
+ * A virtual tensor (paper, Sec. 4.1, Def. 3) is a pair (F, {P_1..P_n}): a mapping function
+ * from the index of a tensor that is never stored to (physical tensor, physical index).
+ * A chain of data-movement operators (Sec. 2.2, Def. 2) between a producer and a consumer
+ * is composed on the host into one such map (Sec. 4.1, "mapping function composition")
+ * and the consumer kernels apply it in their load stage (Sec. 4.2, virtual tensor I/O),
+ * so the intermediates of the chain are never written to memory.
+ *
+ * Conventions
+ *   - Every function returns a vt_status; vt_last_error() gives a thread-local message.
+ *   - "device pointer": memory of the current HIP device, owned by the caller, which must
+ *     stay valid until the work queued on `stream` has finished.  "host pointer": ordinary
+ *     process memory, read during the call only, unless stated otherwise.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Kernels are
+ *     queued asynchronously; the library never synchronises and allocates no device memory.
+ *     A launch that the runtime rejects returns VT_ERR_DEVICE; a fault while a kernel runs
+ *     surfaces at the caller's next synchronisation.
+ *   - Tensors are row-major; strides are in elements; dense outputs are contiguous.
+ *   - Invalid chains fail in vt_build and never reach a kernel.
+ */
+#ifndef VT_H_
+#define VT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VT_MAX_DIMS 8
+
+typedef enum {
+  VT_OK = 0,
+  VT_ERR_INVALID_ARG = 1,   /* null pointer, bad enum, bad value id */
+  VT_ERR_SHAPE = 2,         /* shapes do not fit the operator or the consumer */
+  VT_ERR_RANGE = 3,         /* slice / split / index out of range */
+  VT_ERR_NOT_ONE_TO_ONE = 4,/* a map used as a store target sends two indices to one element (Sec. 4.1) */
+  VT_ERR_UNSUPPORTED = 5,   /* valid, but outside what the descriptor or the kernel can express */
+  VT_ERR_DEVICE = 6         /* the HIP runtime refused a launch */
+} vt_status;
+
+typedef enum { VT_F32 = 0, VT_F16 = 1, VT_BF16 = 2 } vt_dtype;
+
+/* Data-movement operators that a chain may contain (Sec. 2.2; ONNX semantics). */
+typedef enum {
+  VT_OP_RESHAPE = 0,      /* a[0..ndim) = new shape; row-major order of elements is kept */
+  VT_OP_PERMUTE = 1,      /* a[0..ndim) = perm; out.shape[i] = in.shape[perm[i]] */
+  VT_OP_SLICE = 2,        /* a[0]=dim, a[1]=start, a[2]=stop, a[3]=step (>=1) */
+  VT_OP_SPLIT = 3,        /* a[0]=dim, b[0..ndim) = sizes (ndim = number of outputs), out_index = which output */
+  VT_OP_CONCAT = 4,       /* a[0]=dim; inputs in[0..n_in) */
+  VT_OP_EXPAND = 5,       /* a[0..ndim) = new shape, same rank; size-1 dims broadcast */
+  VT_OP_UNSQUEEZE = 6,    /* a[0]=dim of the inserted size-1 axis */
+  VT_OP_INDEX_SELECT = 7  /* a[0]=dim; index/index_host/n_index */
+} vt_op_kind;
+
+/* A physical tensor: the producer's buffer (Def. 3's P_j).  Graph inputs and outputs
+ * stay physical (Alg. 1), so the leaves of every chain are sources. */
+typedef struct {
+  void* ptr;                       /* device pointer to element (0,..,0); may be NULL for host-only use of the descriptor */
+  int32_t dtype;                   /* vt_dtype */
+  int32_t ndim;                    /* 1..VT_MAX_DIMS */
+  int64_t shape[VT_MAX_DIMS];
+  int64_t stride[VT_MAX_DIMS];     /* elements; all zero = dense row-major */
+} vt_source;
+
+#define VT_MAX_OP_INPUTS 8
+
+/* One statement of a chain.  Value ids: v < 0 names source number (-1 - v); v >= 0 names the
+ * result of statement v (which must come earlier). */
+typedef struct {
+  int32_t kind;                    /* vt_op_kind */
+  int32_t n_in;                    /* 1, or the number of concat inputs (<= VT_MAX_OP_INPUTS) */
+  int32_t in[VT_MAX_OP_INPUTS];
+  int32_t out_index;               /* SPLIT: which output this statement denotes */
+  int32_t ndim;                    /* number of valid entries of a (RESHAPE/PERMUTE/EXPAND) or b (SPLIT) */
+  int64_t a[VT_MAX_DIMS];
+  int64_t b[VT_MAX_DIMS];
+  const int32_t* index;            /* INDEX_SELECT: device pointer to n_index int32 entries; read by kernels,
+                                      must outlive every launch that uses the descriptor; may be NULL if the
+                                      descriptor is only evaluated on the host */
+  const int32_t* index_host;       /* INDEX_SELECT: host copy of the same table (required; validated and
+                                      copied into the descriptor during vt_build) */
+  int64_t n_index;
+} vt_op;
+
+typedef struct vt_desc vt_desc;    /* opaque; host memory owned by the library; immutable; reusable */
+
+/* ---- descriptor builder (Sec. 4.1 composition, Sec. 4.3 Eq. 1 form, Def. 4/5 contiguity) ----
+ * Composes statements ops[0..n_ops) over src[0..n_src) and returns the map of value
+ * `result_value` as a descriptor: per piece (one per region served by one source, arising
+ * from CONCAT) a stack of mixed-radix strided stages plus optional index tables, i.e.
+ * f(I) = S.I + b(I) of Eq. 1 with b piecewise / table driven.  src and ops are host
+ * pointers, copied.  Errors: INVALID_ARG, SHAPE, RANGE, UNSUPPORTED (more pieces, stages
+ * or digits than the descriptor holds; index_select along a concatenated dim). */
+int vt_build(const vt_source* src, int n_src, const vt_op* ops, int n_ops, int result_value,
+             vt_desc** out);
+int vt_free(vt_desc* d);
+
+/* Shape, dtype, number of pieces and the contiguous run in elements (Def. 4/5 evaluated on
+ * the refined index space: the number of consecutive virtual elements, counted from any
+ * index whose trailing refined digits are zero, that are consecutive in one source;
+ * minimum over pieces).  Any output pointer may be NULL.  shape must hold VT_MAX_DIMS. */
+int vt_desc_info(const vt_desc* d, int* ndim, int64_t* shape, int* dtype,
+                 int64_t* contiguous_run, int* n_pieces);
+/* Piece p: its box [lo,hi) in virtual index space, its source number and its own run. */
+int vt_desc_piece(const vt_desc* d, int p, int64_t* lo, int64_t* hi, int* src_id, int64_t* run);
+/* CPU evaluation of the map at one virtual index (host logic; used by tests).  vindex holds
+ * ndim entries.  Returns the source number and the element offset from its ptr. */
+int vt_eval_host(const vt_desc* d, const int64_t* vindex, int* src_id, int64_t* elem_offset);
+/* The same, evaluated by the kernels' own routine over the device form of the descriptor
+ * (run on the CPU): a pre-launch check of what the generic kernels will walk.  Returns the
+ * piece number instead of the source number. */
+int vt_eval_device_form(const vt_desc* d, const int64_t* vindex, int* piece, int64_t* elem_offset);
+/* Human-readable dump (pieces, stages, digits) into buf (NUL-terminated, truncated to cap). */
+int vt_desc_dump(const vt_desc* d, char* buf, size_t cap);
+
+/* ---- pure data movement --------------------------------------------------------------
+ * vt_materialize: gather-copy of the whole virtual tensor into dense row-major dst (device
+ * pointer, same dtype).  Bit-exact.  vt_copy_op: ONE operator executed as an explicit copy
+ * kernel from dense/strided inputs into dense dst: the building block of the materialized
+ * comparison path (Sec. 3.1 counts six such kernels between the two compute kernels). */
+int vt_materialize(const vt_desc* d, void* dst, void* stream);
+int vt_copy_op(const vt_source* in, int n_in, const vt_op* op, void* dst, void* stream);
+
+/* ---- consumers (stage 1 reads through the map; stage 2 and 3 are ordinary, Sec. 4.2) ----
+ * VT_EW_ADD_ROWSUM: x, y virtual [R,C] f32; out[r] = sum_c (x[r,c] + y[r,c]), out = R floats
+ *   (device).  Summation order is fixed: column c goes to partial sum c mod 64 in ascending
+ *   c, the 64 partial sums are combined by the butterfly p[l] += p[l xor s], s = 32..1.
+ * VT_EW_LAYERNORM: x virtual [..., C] (f16/bf16/f32), y must be NULL; per-row LayerNorm over
+ *   the last dim with gamma = 1, beta = 0, biased variance, fp32 arithmetic, out dense, same
+ *   dtype and shape as x. */
+typedef enum { VT_EW_ADD_ROWSUM = 0, VT_EW_LAYERNORM = 1 } vt_ew_kind;
+int vt_elementwise(int kind, const vt_desc* x, const vt_desc* y, float eps, void* out, void* stream);
+
+/* GEMM consumer on the matrix cores (Sec. 2.3 Listing 1's three stages with a virtual stage
+ * 1): C[g] = A[g] . B[g] for g in [0, n_groups).  A[g] virtual [M_g, K] (trailing dims may be
+ * folded: [.., K] counts as rows x K), B[g] virtual [K, N]; f16 or bf16 operands, fp32
+ * accumulation, C[g] dense [M_g, N] row-major device pointers of dtype c_dtype (same as the
+ * operands, or VT_F32).  One launch covers all groups.
+ * prologue = VT_GEMM_LAYERNORM applies per-row LayerNorm (gamma 1, beta 0, eps) over K to A,
+ * rounded to the operand dtype, before the product; it needs K <= 256.
+ * A, B, C are host arrays of n_groups pointers. */
+typedef enum { VT_GEMM_PLAIN = 0, VT_GEMM_LAYERNORM = 1 } vt_gemm_prologue;
+int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* const* C, int n_groups,
+            int c_dtype, int prologue, float eps, void* stream);
+
+/* Split-K flash-decoding attention with grouped queries (Sec. 3.1: the attention kernel
+ * reads the un-expanded cache).  Q virtual [B,Hq,1,D], K and V virtual [B,Hq,S,D]
+ * (f16/bf16, D = 128).  out dense [B,Hq,D], same dtype.  softmax(scale * q.k) in fp32.
+ * Query heads whose K/V rows coincide (a broadcast digit in the map) share one read.
+ * workspace: device pointer of at least vt_decode_attn_workspace(...) bytes, holding the
+ * per-split partial results; n_splits = 0 lets the library choose.  lse (device, B*Hq floats,
+ * may be NULL) receives the log-sum-exp of the scaled scores. */
+size_t vt_decode_attn_workspace(int B, int Hq, int D, int S, int n_splits);
+int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float scale, void* out,
+                   float* lse, void* workspace, size_t workspace_bytes, int n_splits, void* stream);
+
+const char* vt_last_error(void);
+const char* vt_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VT_H_ */

@@ -1,0 +1,133 @@
+// Device-side form of a descriptor (a POD passed to kernels by value) and its evaluator.
+//
+// The generic evaluator applies the whole map to one index: it is the fallback every
+// consumer can use on any descriptor.  The fast paths of the consumers do not call it per
+// element: they resolve a tile origin once and walk the tile with a few strides (the
+// paper's block-wise virtual tensor I/O, Sec. 4.2).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "vt_desc.h"
+
+namespace vt {
+
+constexpr int kDevPieces = 8;
+constexpr int kDevStages = 10;   // pool shared by all pieces
+constexpr int kDevDigits = 24;   // pool shared by all stages
+constexpr int kDevTables = 4;
+
+// n / d for n < 2^31 as (n * magic) >> (31 + shift), magic = ceil(2^(31+shift) / d),
+// shift = ceil(log2 d): exact for every n < 2^31 (Granlund-Montgomery with N = 31).
+struct FastDiv {
+  uint32_t d, magic, shift;
+};
+
+struct DevDigit {
+  int64_t stride;
+  FastDiv radix;
+  uint32_t table_off;
+  int32_t table;     // index into DevDesc::tables or -1
+};
+
+struct DevStage {
+  int64_t base;
+  uint8_t first, count;   // digits [first, first+count) of the pool, outer -> inner
+};
+
+struct DevPiece {
+  const void* ptr;
+  int32_t lo[VT_MAX_DIMS], hi[VT_MAX_DIMS];
+  uint8_t group_begin[VT_MAX_DIMS + 1];   // top stage: dim i owns digits [gb[i], gb[i+1]) (absolute pool indices)
+  uint8_t stage_first, n_stages;          // stage_first = top stage; the lower ones follow it
+};
+
+struct DevDesc {
+  int32_t ndim, n_pieces, elem_size, outer_dims;   // dims [0,outer_dims) are indexed by the launch's outer index
+  FastDiv shape[VT_MAX_DIMS];
+  DevPiece pieces[kDevPieces];
+  DevStage stages[kDevStages];
+  DevDigit digits[kDevDigits];
+  const int32_t* tables[kDevTables];
+};
+
+FastDiv make_fastdiv(uint32_t d);
+// Fills `out` from a host descriptor.  VT_ERR_UNSUPPORTED if it exceeds the device pools or a
+// 31-bit index range.  `inner_elems` receives the product of the dims that are addressed by
+// the 32-bit inner index (all dims unless the tensor has 2^31 elements or more).
+// `host_tables` makes the table pointers name the host copies (for evaluation on the CPU) and
+// tolerates sources without device pointers.
+int to_device(const vt_desc& d, DevDesc* out, int64_t* outer_count, int64_t* inner_elems, bool host_tables = false);
+
+__host__ __device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv& f) {
+  return (uint32_t)(((uint64_t)n * f.magic) >> (31u + f.shift));
+}
+
+// Element offset and source pointer of the element at (outer index o, inner linear index L).
+// Returns the piece index (always found for a well-formed descriptor).
+__host__ __device__ __forceinline__ int vtd_eval(const DevDesc& D, uint32_t o, uint32_t L, int64_t* off_out,
+                                                 const void** ptr_out) {
+  uint32_t x[VT_MAX_DIMS];
+  for (int i = D.ndim - 1; i >= D.outer_dims; --i) {
+    uint32_t q = fdiv(L, D.shape[i]);
+    x[i] = L - q * D.shape[i].d;
+    L = q;
+  }
+  for (int i = D.outer_dims - 1; i >= 0; --i) {
+    uint32_t q = o / D.shape[i].d;
+    x[i] = o - q * D.shape[i].d;
+    o = q;
+  }
+  int found = -1;
+  int64_t off = 0;
+  const void* ptr = nullptr;
+  for (int p = 0; p < D.n_pieces; ++p) {
+    const DevPiece& pc = D.pieces[p];
+    bool in = true;
+    for (int i = 0; i < D.ndim; ++i) in = in && (int32_t)x[i] >= pc.lo[i] && (int32_t)x[i] < pc.hi[i];
+    if (!in) continue;
+    found = p;
+    ptr = pc.ptr;
+    int64_t acc = D.stages[pc.stage_first].base;
+    for (int i = 0; i < D.ndim; ++i) {
+      uint32_t v = x[i] - (uint32_t)pc.lo[i];
+      for (int k = (int)pc.group_begin[i + 1] - 1; k >= (int)pc.group_begin[i]; --k) {
+        const DevDigit& dg = D.digits[k];
+        uint32_t q = fdiv(v, dg.radix);
+        uint32_t r = v - q * dg.radix.d;
+        v = q;
+        int64_t val = dg.table >= 0 ? (int64_t)D.tables[dg.table][dg.table_off + r] : (int64_t)r;
+        acc += val * dg.stride;
+      }
+    }
+    for (int s = 1; s < pc.n_stages; ++s) {
+      const DevStage& st = D.stages[pc.stage_first + s];
+      uint32_t v = (uint32_t)acc;
+      acc = st.base;
+      for (int k = (int)st.first + st.count - 1; k >= (int)st.first; --k) {
+        const DevDigit& dg = D.digits[k];
+        uint32_t q = fdiv(v, dg.radix);
+        uint32_t r = v - q * dg.radix.d;
+        v = q;
+        int64_t val = dg.table >= 0 ? (int64_t)D.tables[dg.table][dg.table_off + r] : (int64_t)r;
+        acc += val * dg.stride;
+      }
+    }
+    off = acc;
+  }
+  *off_out = off;
+  *ptr_out = ptr;
+  return found;
+}
+
+// Largest vector width (elements, a power of two, at most 16 bytes) with which aligned groups
+// of consecutive virtual elements can be moved as one access: it divides every piece's run,
+// every piece boundary and every offset at which a run can start, and the source pointers are
+// 16-byte aligned.  Always >= 1.
+int vector_width(const vt_desc& d);
+
+// launch bookkeeping shared by the kernels' host wrappers
+int check_launch(const char* what);
+
+}  // namespace vt

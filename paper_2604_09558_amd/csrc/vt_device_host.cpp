@@ -1,0 +1,148 @@
+// Host helpers: conversion of a descriptor to its device form, vector-width analysis.
+#include <cstring>
+
+#include "vt_device.h"
+
+namespace vt {
+
+FastDiv make_fastdiv(uint32_t d) {
+  FastDiv f;
+  f.d = d;
+  uint32_t l = 0;
+  while ((1ull << l) < d) ++l;
+  f.shift = l;
+  unsigned __int128 num = (unsigned __int128)1 << (31 + l);
+  f.magic = (uint32_t)((num + d - 1) / d);
+  return f;
+}
+
+static bool fits31(int64_t v) { return v >= 0 && v < (1ll << 31); }
+
+int to_device(const vt_desc& d, DevDesc* out, int64_t* outer_count, int64_t* inner_elems, bool host_tables) {
+  memset(out, 0, sizeof(*out));
+  int n = (int)d.shape.size();
+  out->ndim = n;
+  out->elem_size = dtype_size(d.dtype);
+  if ((int)d.pieces.size() > kDevPieces) return fail(VT_ERR_UNSUPPORTED, "descriptor has more pieces than the generic kernels take (8)");
+  if ((int)d.tables.size() > kDevTables) return fail(VT_ERR_UNSUPPORTED, "descriptor has more index tables than the generic kernels take (4)");
+  out->n_pieces = (int)d.pieces.size();
+  int64_t inner = 1;
+  int k = n;
+  while (k > 0 && inner * d.shape[k - 1] < (1ll << 31)) inner *= d.shape[--k];
+  int64_t outer = 1;
+  for (int i = 0; i < k; ++i) outer *= d.shape[i];
+  if (!fits31(outer)) return fail(VT_ERR_UNSUPPORTED, "tensor too large for the generic kernels");
+  out->outer_dims = k;
+  if (outer_count) *outer_count = outer;
+  if (inner_elems) *inner_elems = inner;
+  for (int i = 0; i < n; ++i) {
+    if (!fits31(d.shape[i])) return fail(VT_ERR_UNSUPPORTED, "extent >= 2^31");
+    out->shape[i] = make_fastdiv((uint32_t)d.shape[i]);
+  }
+  for (size_t t = 0; t < d.tables.size(); ++t) {
+    if (host_tables) {
+      out->tables[t] = d.tables[t].host.data();
+      continue;
+    }
+    if (!d.tables[t].dev) return fail(VT_ERR_INVALID_ARG, "descriptor was built without the device pointer of an index table");
+    out->tables[t] = d.tables[t].dev;
+  }
+  int ns = 0, nd = 0;
+  auto put_digit = [&](const Digit& g) -> bool {
+    if (nd >= kDevDigits || !fits31(g.radix)) return false;
+    DevDigit& o = out->digits[nd++];
+    o.stride = g.stride;
+    o.radix = make_fastdiv((uint32_t)g.radix);
+    o.table = g.table;
+    o.table_off = (uint32_t)g.table_off;
+    return true;
+  };
+  for (size_t p = 0; p < d.pieces.size(); ++p) {
+    const Piece& pc = d.pieces[p];
+    DevPiece& o = out->pieces[p];
+    o.ptr = d.sources[pc.src].ptr;
+    if (!o.ptr && !host_tables) return fail(VT_ERR_INVALID_ARG, "descriptor was built from a source without a device pointer");
+    for (int i = 0; i < n; ++i) {
+      o.lo[i] = (int32_t)pc.lo[i];
+      o.hi[i] = (int32_t)pc.hi[i];
+    }
+    if (ns + 1 + (int)pc.v.lower.size() > kDevStages) return fail(VT_ERR_UNSUPPORTED, "descriptor has more stages than the generic kernels take");
+    o.stage_first = (uint8_t)ns;
+    o.n_stages = (uint8_t)(1 + pc.v.lower.size());
+    DevStage& top = out->stages[ns++];
+    top.base = pc.v.base;
+    top.first = (uint8_t)nd;
+    for (int i = 0; i < n; ++i) {
+      o.group_begin[i] = (uint8_t)nd;
+      for (const Digit& g : pc.v.groups[i])
+        if (!put_digit(g)) return fail(VT_ERR_UNSUPPORTED, "descriptor has more digits than the generic kernels take");
+    }
+    o.group_begin[n] = (uint8_t)nd;
+    top.count = (uint8_t)(nd - top.first);
+    for (const Stage& s : pc.v.lower) {
+      DevStage& st = out->stages[ns++];
+      st.base = s.base;
+      st.first = (uint8_t)nd;
+      int64_t span = 1;
+      for (const Digit& g : s.digits) {
+        span *= g.radix;
+        if (!fits31(span)) return fail(VT_ERR_UNSUPPORTED, "stacked stage spans 2^31 elements or more");
+        if (!put_digit(g)) return fail(VT_ERR_UNSUPPORTED, "descriptor has more digits than the generic kernels take");
+      }
+      st.count = (uint8_t)(nd - st.first);
+    }
+  }
+  return VT_OK;
+}
+
+int vector_width(const vt_desc& d) {
+  int n = (int)d.shape.size();
+  int esz = dtype_size(d.dtype);
+  int vec = 16 / esz;
+  auto ok = [&](int v) {
+    if (d.shape[n - 1] % v) return false;
+    for (const Piece& p : d.pieces) {
+      if (p.run % v) return false;
+      if (p.align % v) return false;
+      if (p.lo[n - 1] % v || p.hi[n - 1] % v) return false;
+      if ((uintptr_t)d.sources[p.src].ptr % 16) return false;
+    }
+    return true;
+  };
+  while (vec > 1 && !ok(vec)) vec >>= 1;
+  return vec;
+}
+
+}  // namespace vt
+
+// The kernels' own evaluator, run on the CPU over the device form of the descriptor: lets the
+// host tests check the structure the kernels will walk before anything is launched.
+extern "C" int vt_eval_device_form(const vt_desc* d, const int64_t* vindex, int* piece, int64_t* elem_offset) {
+  using namespace vt;
+  if (!d || !vindex) return fail(VT_ERR_INVALID_ARG, "vt_eval_device_form: NULL argument");
+  DevDesc D;
+  int64_t outer, inner;
+  int rc = to_device(*d, &D, &outer, &inner, true);
+  if (rc != VT_OK) return rc;
+  int n = (int)d->shape.size();
+  uint64_t o = 0, L = 0;
+  for (int i = 0; i < D.outer_dims; ++i) o = o * d->shape[i] + vindex[i];
+  for (int i = D.outer_dims; i < n; ++i) L = L * d->shape[i] + vindex[i];
+  int64_t off;
+  const void* ptr;
+  int p = vtd_eval(D, (uint32_t)o, (uint32_t)L, &off, &ptr);
+  if (p < 0) return fail(VT_ERR_RANGE, "vt_eval_device_form: no piece holds the index");
+  if (piece) *piece = p;
+  if (elem_offset) *elem_offset = off;
+  return VT_OK;
+}
+
+namespace vt {
+
+int check_launch(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(VT_ERR_DEVICE, std::string(what) + ": " + hipGetErrorString(e));
+  return VT_OK;
+}
+
+}  // namespace vt

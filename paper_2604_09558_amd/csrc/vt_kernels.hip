@@ -1,0 +1,229 @@
+// Pure data movement through a descriptor (vt_materialize, vt_copy_op) and the
+// elementwise / reduction consumer (vt_elementwise).  gfx950, wave64.
+#include <hip/hip_runtime.h>
+
+#include "vt_device.h"
+#include "vt_numeric.h"
+
+using namespace vt;
+
+// ------------------------------------------------------------------------------------------
+// Gather-copy: thread t moves one vector of VB bytes.  The host guarantees that aligned
+// vectors never straddle a piece, a run or a row of the virtual tensor.
+// ------------------------------------------------------------------------------------------
+template <typename V>
+__global__ void __launch_bounds__(256) k_materialize(const DevDesc D, V* __restrict__ dst, uint32_t inner_vecs,
+                                                     uint32_t vec_elems, uint32_t outer) {
+  uint32_t vi = blockIdx.x * 256u + threadIdx.x;
+  if (vi >= inner_vecs) return;
+  for (uint32_t o = blockIdx.y; o < outer; o += gridDim.y) {
+    int64_t off;
+    const void* ptr;
+    vtd_eval(D, o, vi * vec_elems, &off, &ptr);
+    const V* src = reinterpret_cast<const V*>(static_cast<const char*>(ptr) + off * D.elem_size);
+    dst[(size_t)o * inner_vecs + vi] = *src;
+  }
+}
+
+static int launch_materialize(const vt_desc& d, void* dst, hipStream_t stream) {
+  DevDesc D;
+  int64_t outer, inner;
+  int rc = to_device(d, &D, &outer, &inner);
+  if (rc != VT_OK) return rc;
+  int vec = vector_width(d);
+  if ((uintptr_t)dst % 16) vec = 1;
+  int esz = dtype_size(d.dtype);
+  uint32_t inner_vecs = (uint32_t)(inner / vec);
+  dim3 grid((inner_vecs + 255) / 256, (unsigned)std::min<int64_t>(outer, 65535));
+  int bytes = vec * esz;
+  switch (bytes) {
+    case 16:
+      hipLaunchKernelGGL(k_materialize<uint4>, grid, dim3(256), 0, stream, D, (uint4*)dst, inner_vecs, (uint32_t)vec, (uint32_t)outer);
+      break;
+    case 8:
+      hipLaunchKernelGGL(k_materialize<uint2>, grid, dim3(256), 0, stream, D, (uint2*)dst, inner_vecs, (uint32_t)vec, (uint32_t)outer);
+      break;
+    case 4:
+      hipLaunchKernelGGL(k_materialize<uint32_t>, grid, dim3(256), 0, stream, D, (uint32_t*)dst, inner_vecs, (uint32_t)vec, (uint32_t)outer);
+      break;
+    default:
+      hipLaunchKernelGGL(k_materialize<uint16_t>, grid, dim3(256), 0, stream, D, (uint16_t*)dst, inner_vecs, (uint32_t)vec, (uint32_t)outer);
+      break;
+  }
+  return check_launch("vt_materialize");
+}
+
+// ------------------------------------------------------------------------------------------
+// out[r] = sum_c (x[r,c] + y[r,c]), fp32.  One wave per row.  Lane l owns the columns
+// c = l, l+64, ... in ascending order starting from +0; the 64 partial sums are combined by
+// the butterfly p[l] += p[l xor s], s = 32..1, and lane 0 stores.  This order is part of the
+// contract (it is what makes the result reproducible bit for bit).
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_add_rowsum(const DevDesc X, const DevDesc Y, float* __restrict__ out,
+                                                    uint32_t R, uint32_t C) {
+  uint32_t lane = threadIdx.x & 63u;
+  uint32_t row = blockIdx.x * 4u + (threadIdx.x >> 6);
+  if (row >= R) return;
+  float p = 0.0f;
+  for (uint32_t c = lane; c < C; c += 64u) {
+    int64_t ox, oy;
+    const void *px, *py;
+    vtd_eval(X, 0, row * C + c, &ox, &px);
+    vtd_eval(Y, 0, row * C + c, &oy, &py);
+    float t = static_cast<const float*>(px)[ox] + static_cast<const float*>(py)[oy];
+    p = p + t;
+  }
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) p = p + __shfl_xor(p, s, 64);
+  if (lane == 0) out[row] = p;
+}
+
+// ------------------------------------------------------------------------------------------
+// Per-row LayerNorm over the last dim (gamma = 1, beta = 0, biased variance), fp32 math.
+// LPR lanes share a row; each lane keeps up to 4 vectors of VEC elements in registers.
+// ------------------------------------------------------------------------------------------
+template <typename T, int VEC>
+__global__ void __launch_bounds__(256) k_layernorm(const DevDesc X, T* __restrict__ out, uint32_t rows, uint32_t C,
+                                                   uint32_t lpr_log2, float eps, uint32_t outer, uint32_t rows_inner) {
+  const uint32_t lpr = 1u << lpr_log2;
+  const uint32_t rpw = 64u >> lpr_log2;                 // rows per wave
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t sub = lane & (lpr - 1u);
+  const uint32_t row = (blockIdx.x * 4u + (threadIdx.x >> 6)) * rpw + (lane >> lpr_log2);
+  const uint32_t nvec = C / VEC;
+  const bool live = row < rows;
+  float v[4][VEC];
+  float sum = 0.0f;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    uint32_t j = sub + it * lpr;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) v[it][e] = 0.0f;
+    if (live && j < nvec) {
+      uint32_t o = row / rows_inner, ri = row - o * rows_inner;
+      int64_t off;
+      const void* ptr;
+      vtd_eval(X, o, ri * C + j * VEC, &off, &ptr);
+      Vec<T, VEC> raw = *reinterpret_cast<const Vec<T, VEC>*>(static_cast<const T*>(ptr) + off);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        v[it][e] = to_float(raw.v[e]);
+        sum += v[it][e];
+      }
+    }
+  }
+  for (uint32_t s = lpr >> 1; s >= 1; s >>= 1) sum += __shfl_xor(sum, (int)s, 64);
+  const float mean = sum / (float)C;
+  float sq = 0.0f;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    uint32_t j = sub + it * lpr;
+    if (j < nvec) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        float dlt = v[it][e] - mean;
+        sq += dlt * dlt;
+      }
+    }
+  }
+  for (uint32_t s = lpr >> 1; s >= 1; s >>= 1) sq += __shfl_xor(sq, (int)s, 64);
+  const float rstd = 1.0f / sqrtf(sq / (float)C + eps);
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    uint32_t j = sub + it * lpr;
+    if (live && j < nvec) {
+      Vec<T, VEC> o;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) o.v[e] = from_float<T>((v[it][e] - mean) * rstd);
+      *reinterpret_cast<Vec<T, VEC>*>(out + (size_t)row * C + (size_t)j * VEC) = o;
+    }
+  }
+  (void)outer;
+}
+
+template <typename T>
+static int launch_layernorm_t(const vt_desc& d, const DevDesc& D, void* out, float eps, int64_t outer, int64_t inner,
+                              hipStream_t stream) {
+  int n = (int)d.shape.size();
+  int64_t C = d.shape[n - 1];
+  int vec = vector_width(d);
+  if ((uintptr_t)out % 16) vec = 1;
+  int64_t nvec = C / vec;
+  uint32_t lpr_log2 = 0;
+  while ((1 << lpr_log2) < nvec && lpr_log2 < 6) ++lpr_log2;
+  if (nvec > (int64_t)(4 << lpr_log2)) return fail(VT_ERR_UNSUPPORTED, "layernorm: row too long for the register-resident kernel");
+  int64_t rows = outer * inner / C;
+  if (rows >= (1ll << 31)) return fail(VT_ERR_UNSUPPORTED, "layernorm: too many rows");
+  uint32_t rows_inner = (uint32_t)(inner / C);
+  uint32_t rpw = 64u >> lpr_log2;
+  dim3 grid((unsigned)((rows + 4 * rpw - 1) / (4 * rpw)));
+#define LN_LAUNCH(V)                                                                                          \
+  hipLaunchKernelGGL((k_layernorm<T, V>), grid, dim3(256), 0, stream, D, (T*)out, (uint32_t)rows, (uint32_t)C, \
+                     lpr_log2, eps, (uint32_t)outer, rows_inner)
+  switch (vec) {
+    case 8:
+      if constexpr (sizeof(T) == 2) { LN_LAUNCH(8); break; }
+      [[fallthrough]];
+    case 4: LN_LAUNCH(4); break;
+    case 2: LN_LAUNCH(2); break;
+    default: LN_LAUNCH(1); break;
+  }
+#undef LN_LAUNCH
+  return check_launch("vt_elementwise(layernorm)");
+}
+
+extern "C" {
+
+int vt_materialize(const vt_desc* d, void* dst, void* stream) {
+  if (!d || !dst) return fail(VT_ERR_INVALID_ARG, "vt_materialize: NULL argument");
+  return launch_materialize(*d, dst, (hipStream_t)stream);
+}
+
+int vt_copy_op(const vt_source* in, int n_in, const vt_op* op, void* dst, void* stream) {
+  if (!in || !op || !dst || n_in < 1) return fail(VT_ERR_INVALID_ARG, "vt_copy_op: NULL argument");
+  vt_op local = *op;
+  if (local.n_in != n_in) return fail(VT_ERR_INVALID_ARG, "vt_copy_op: n_in differs from the statement's");
+  for (int i = 0; i < n_in; ++i) local.in[i] = -1 - i;
+  vt_desc* d = nullptr;
+  int rc = vt_build(in, n_in, &local, 1, 0, &d);
+  if (rc != VT_OK) return rc;
+  rc = launch_materialize(*d, dst, (hipStream_t)stream);
+  vt_free(d);
+  return rc;
+}
+
+int vt_elementwise(int kind, const vt_desc* x, const vt_desc* y, float eps, void* out, void* stream) {
+  if (!x || !out) return fail(VT_ERR_INVALID_ARG, "vt_elementwise: NULL argument");
+  hipStream_t st = (hipStream_t)stream;
+  if (kind == VT_EW_ADD_ROWSUM) {
+    if (!y) return fail(VT_ERR_INVALID_ARG, "vt_elementwise(add_rowsum): y is NULL");
+    if (x->dtype != VT_F32 || y->dtype != VT_F32) return fail(VT_ERR_INVALID_ARG, "vt_elementwise(add_rowsum): fp32 only");
+    if (x->shape.size() != 2 || x->shape != y->shape) return fail(VT_ERR_SHAPE, "vt_elementwise(add_rowsum): x and y must be [R,C] of equal shape");
+    DevDesc X, Y;
+    int64_t ox, ix, oy, iy;
+    int rc = to_device(*x, &X, &ox, &ix);
+    if (rc != VT_OK) return rc;
+    rc = to_device(*y, &Y, &oy, &iy);
+    if (rc != VT_OK) return rc;
+    if (ox != 1 || oy != 1) return fail(VT_ERR_UNSUPPORTED, "vt_elementwise(add_rowsum): 2^31 elements or more");
+    uint32_t R = (uint32_t)x->shape[0], C = (uint32_t)x->shape[1];
+    hipLaunchKernelGGL(k_add_rowsum, dim3((R + 3) / 4), dim3(256), 0, st, X, Y, (float*)out, R, C);
+    return check_launch("vt_elementwise(add_rowsum)");
+  }
+  if (kind == VT_EW_LAYERNORM) {
+    if (y) return fail(VT_ERR_INVALID_ARG, "vt_elementwise(layernorm): y must be NULL");
+    DevDesc X;
+    int64_t outer, inner;
+    int rc = to_device(*x, &X, &outer, &inner);
+    if (rc != VT_OK) return rc;
+    if (inner % x->shape.back()) return fail(VT_ERR_UNSUPPORTED, "vt_elementwise(layernorm): row of 2^31 elements or more");
+    switch (x->dtype) {
+      case VT_F32: return launch_layernorm_t<float>(*x, X, out, eps, outer, inner, st);
+      case VT_F16: return launch_layernorm_t<f16_t>(*x, X, out, eps, outer, inner, st);
+      default: return launch_layernorm_t<bf16_t>(*x, X, out, eps, outer, inner, st);
+    }
+  }
+  return fail(VT_ERR_INVALID_ARG, "vt_elementwise: unknown kind");
+}
+
+}  // extern "C"

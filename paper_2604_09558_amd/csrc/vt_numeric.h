@@ -1,0 +1,48 @@
+// Storage types and conversions used by the kernels (device only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace vt {
+
+struct bf16_t {
+  uint16_t bits;
+};
+typedef _Float16 f16_t;
+
+template <typename T, int N>
+struct __attribute__((aligned(sizeof(T) * N))) Vec {
+  T v[N];
+};
+
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(f16_t x) { return (float)x; }
+__device__ __forceinline__ float to_float(bf16_t x) { return __uint_as_float((uint32_t)x.bits << 16); }
+
+// float -> bf16, round to nearest even; NaN stays NaN
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <typename T>
+__device__ __forceinline__ T from_float(float x);
+template <>
+__device__ __forceinline__ float from_float<float>(float x) {
+  return x;
+}
+template <>
+__device__ __forceinline__ f16_t from_float<f16_t>(float x) {
+  return (f16_t)x;
+}
+template <>
+__device__ __forceinline__ bf16_t from_float<bf16_t>(float x) {
+  bf16_t r;
+  r.bits = f32_to_bf16_bits(x);
+  return r;
+}
+
+}  // namespace vt

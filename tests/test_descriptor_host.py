@@ -1,0 +1,273 @@
+"""Host logic of the library (no GPU): the descriptor builder evaluated on the CPU through
+vt_eval_host against the oracle's dense, op-by-op result; contiguity analysis (Def. 4/5);
+error paths; exported symbols."""
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2604_09558_amd as vt
+import workloads
+from oracle import dm_ops
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def specs_of(wl, ptrs=None):
+    return {k: (v.shape, wl.dtype) for k, v in wl.sources.items()}
+
+
+def check_desc_against_dense(desc, dense, wl):
+    """Every virtual index: descriptor -> (source, offset) must name the value the oracle put there."""
+    info = desc.info()
+    assert info["shape"] == dense.shape
+    flat = {n: wl.sources[n].ravel() for n in desc.source_names}
+    for x in itertools.product(*[range(n) for n in dense.shape]):
+        src, off = desc.eval_host(x)
+        name = desc.source_names[src]
+        assert 0 <= off < flat[name].size, (x, src, off)
+        got = flat[name][off]
+        assert got == dense[x] or (got != got and dense[x] != dense[x]), (x, name, off, desc.dump())
+        # the kernels' evaluator over the device form must agree with the host evaluator
+        try:
+            pc, off2 = desc.eval_device_form(x)
+        except vt.VtError as e:
+            assert e.code == vt.ERR_UNSUPPORTED
+            continue
+        assert off2 == off and desc.piece(pc)["src"] == src, (x, desc.dump())
+
+
+def test_exported_symbols_match_header():
+    hdr = open(os.path.join(ROOT, "include", "vt.h")).read()
+    names = set(re.findall(r"\b(vt_[a-z_]+)\s*\(", hdr))
+    assert {"vt_build", "vt_elementwise", "vt_gemm", "vt_decode_attn", "vt_materialize", "vt_copy_op"} <= names
+    L = vt.lib()
+    for n in sorted(names):
+        assert hasattr(L, n), n
+
+
+@pytest.mark.parametrize("seed", range(150))
+def test_random_chain_descriptor_equals_oracle(seed):
+    wl = workloads.random_chain(seed, n_ops=6)
+    dense = dm_ops.run_chain(wl.chain, wl.sources, wl.index_tables)["R"]
+    try:
+        d = vt.build_chain(wl.chain, specs_of(wl), "R", wl.index_tables)
+    except vt.VtError as e:
+        assert e.code == vt.ERR_UNSUPPORTED, str(e)
+        pytest.skip("outside the descriptor's reach: " + str(e))
+    check_desc_against_dense(d, dense, wl)
+    check_runs(d)
+
+
+def test_most_random_chains_are_supported():
+    ok = 0
+    for seed in range(150):
+        wl = workloads.random_chain(seed, n_ops=6)
+        try:
+            vt.build_chain(wl.chain, specs_of(wl), "R", wl.index_tables)
+            ok += 1
+        except vt.VtError as e:
+            assert e.code == vt.ERR_UNSUPPORTED
+    assert ok >= 110, ok
+
+
+def local_linear(local, shape):
+    lin = 0
+    for a, n in zip(local, shape):
+        lin = lin * n + a
+    return lin
+
+
+def check_runs(d):
+    """Soundness and maximality of each piece's contiguous run, by scanning the piece."""
+    info = d.info()
+    shape = info["shape"]
+    runs = []
+    for p in range(info["n_pieces"]):
+        pc = d.piece(p)
+        lshape = tuple(h - l for l, h in zip(pc["lo"], pc["hi"]))
+        run = pc["run"]
+        runs.append(run)
+        size = int(np.prod(lshape))
+        assert run >= 1 and size % run == 0
+        offs = {}
+        glin = {}
+        for loc in itertools.product(*[range(n) for n in lshape]):
+            x = tuple(a + l for a, l in zip(loc, pc["lo"]))
+            src, off = d.eval_host(x)
+            assert src == pc["src"]
+            ll = local_linear(loc, lshape)
+            offs[ll] = off
+            glin[ll] = local_linear(x, shape)
+        broke = False
+        for ll in range(size - 1):
+            same_block = (ll + 1) % run != 0
+            consecutive = offs[ll + 1] == offs[ll] + 1 and glin[ll + 1] == glin[ll] + 1
+            if same_block:
+                assert consecutive, (p, ll, run, d.dump())
+            elif not consecutive:
+                broke = True
+        # maximal among runs that are products of trailing refined digits: some block
+        # boundary must really break, unless the run already covers the piece
+        # (an index table may be consecutive by accident: the analysis never looks at its entries)
+        assert broke or run == size or ",T" in d.dump(), (p, run, d.dump())
+    assert info["run"] == min(runs)
+
+
+# ------------------------------------------------------------------ benchmark chains
+def test_c1_descriptor():
+    wl = workloads.c1_tiny_chain()
+    dense = dm_ops.run_chain(wl.chain, wl.sources)["V"]
+    d = vt.build_chain(wl.chain, specs_of(wl), "V")
+    check_desc_against_dense(d, dense, wl)
+    info = d.info()
+    assert info["n_pieces"] == 2 and info["run"] == 1
+    assert d.piece(0)["hi"] == (8, 16) and d.piece(1)["lo"] == (0, 16) and d.piece(1)["run"] == 5
+    # hand closed form: c < 16 -> X offset 8*(c+4) + r ; c >= 16 -> Y offset 5*r + c - 16
+    for r in range(8):
+        for c in range(21):
+            src, off = d.eval_host((r, c))
+            if c < 16:
+                assert (d.source_names[src], off) == ("X", 8 * (c + 4) + r)
+            else:
+                assert (d.source_names[src], off) == ("Y", 5 * r + c - 16)
+
+
+def test_c2_descriptor_small_and_full_size_structure():
+    wl = workloads.c2_decode_attention(B=2, Hkv=2, G=4, S=5, D=128)
+    env = dm_ops.run_chain(wl.chain, wl.sources)
+    for name in ("Q", "K", "V"):
+        d = vt.build_chain(wl.chain, specs_of(wl), name)
+        check_desc_against_dense(d, env[name], wl)
+    # full size: build from shapes only (no data needed) and check the closed form on samples
+    B, Hkv, G, S, D = 8, 8, 4, 4096, 128
+    E = (Hkv * G + 2 * Hkv) * D
+    specs = {"QKV": ((B, 1, E), "bf16"), "Kcache": ((B, Hkv, S, D), "bf16"), "Vcache": ((B, Hkv, S, D), "bf16")}
+    chain = workloads.c2_chain(B, Hkv, G, S, D)
+    k = vt.build_chain(chain, specs, "K")
+    info = k.info()
+    assert info["shape"] == (B, Hkv * G, S, D) and info["n_pieces"] == 2
+    assert k.piece(0)["hi"][2] == S - 1 and k.piece(1)["lo"][2] == S - 1
+    assert k.piece(0)["run"] == (S - 1) * D and k.piece(1)["run"] == D and info["run"] == D
+    rng = np.random.default_rng(0)
+    for _ in range(500):
+        b, h, t, dd = (int(rng.integers(0, n)) for n in (B, Hkv * G, S, D))
+        if rng.integers(0, 4) == 0:
+            t = S - 1
+        src, off = k.eval_host((b, h, t, dd))
+        if t < S - 1:
+            assert (k.source_names[src], off) == ("Kcache", ((b * Hkv + h // G) * S + t) * D + dd)
+        else:
+            assert (k.source_names[src], off) == ("QKV", b * E + Hkv * G * D + (h // G) * D + dd)
+    q = vt.build_chain(chain, specs, "Q")
+    assert q.info()["run"] == Hkv * G * D     # the whole Q block of a batch row is contiguous
+
+
+def test_c3_c4_c5_descriptors_full_size_closed_forms():
+    rng = np.random.default_rng(1)
+    # C3
+    B, H, S, D = 16, 32, 512, 128
+    chain = [("o1", "permute", ("O",), {"perm": (0, 2, 1, 3)}), ("A", "reshape", ("o1",), {"shape": (B * S, H * D)})]
+    a = vt.build_chain(chain, {"O": ((B, H, S, D), "bf16")}, "A")
+    assert a.info()["run"] == D and a.info()["n_pieces"] == 1
+    for _ in range(300):
+        m, k = int(rng.integers(0, B * S)), int(rng.integers(0, H * D))
+        assert a.eval_host((m, k))[1] == (m // S) * 2097152 + (k // D) * 65536 + (m % S) * D + k % D
+    # C4
+    Bc, R, win, Cc = 32, 56, 7, 128
+    nw = R // win
+    chain = [("x1", "reshape", ("X",), {"shape": (Bc, nw, win, nw, win, Cc)}),
+             ("x2", "permute", ("x1",), {"perm": (0, 1, 3, 2, 4, 5)}),
+             ("T", "reshape", ("x2",), {"shape": (Bc * nw * nw, win * win, Cc)})]
+    t = vt.build_chain(chain, {"X": ((Bc, R, R, Cc), "f16")}, "T")
+    assert t.info()["run"] == win * Cc              # 7 tokens of 128 channels = 896 elements
+    for _ in range(300):
+        w, p, c = int(rng.integers(0, 2048)), int(rng.integers(0, 49)), int(rng.integers(0, 128))
+        b, wh, ww, ih, iw = w // 64, (w // 8) % 8, w % 8, p // 7, p % 7
+        assert t.eval_host((w, p, c))[1] == ((b * 56 + wh * 7 + ih) * 56 + ww * 7 + iw) * 128 + c
+    # C5 (small T, real hidden size): row r of expert e is token idx_e[r]
+    wl = workloads.c5_moe_dispatch(T=64, Hd=4096, E=8, N=16)
+    for e in (0, 5):
+        d = vt.build_chain(wl.chain, specs_of(wl), "A%d" % e, wl.index_tables)
+        idx = wl.index_tables["idx%d" % e]
+        assert d.info()["run"] == 4096 and d.info()["shape"] == (len(idx), 4096)
+        for r in range(len(idx)):
+            assert d.eval_host((r, 17))[1] == int(idx[r]) * 4096 + 17
+        bdesc = vt.build_chain(wl.chain, specs_of(wl), "B%d" % e, wl.index_tables)
+        assert bdesc.eval_host((3, 5))[1] == e * 4096 * 16 + 3 * 16 + 5
+        assert bdesc.info()["run"] == 4096 * 16
+
+
+def test_paper_contiguity_cases():
+    # split along axis 0 keeps full contiguity (Sec. 4.4, Split: Type I); along axis 1 it does not
+    src = {"X": ((6, 10), "f32")}
+    d0 = vt.build_chain([("a", "split", ("X",), {"dim": 0, "sizes": (2, 4), "output": 1})], src, "a")
+    assert d0.info()["run"] == 4 * 10                 # minimal contiguous dimension = 1: whole tensor
+    d1 = vt.build_chain([("a", "split", ("X",), {"dim": 1, "sizes": (4, 6), "output": 1})], src, "a")
+    assert d1.info()["run"] == 6                      # partial contiguity: chunk of a row
+    # Eq. 2's expand: (a,b,c) -> (a,3b,c): run is b*c (one replica), bias jumps at each replica
+    a, b, c = 2, 3, 4
+    chain = [("u", "unsqueeze", ("X",), {"dim": 1}), ("e", "expand", ("u",), {"shape": (a, 3, b, c)}),
+             ("y", "reshape", ("e",), {"shape": (a, 3 * b, c)})]
+    d = vt.build_chain(chain, {"X": ((a, b, c), "f32")}, "y")
+    assert d.info()["run"] == b * c
+    for i, j, k in itertools.product(range(a), range(3 * b), range(c)):
+        assert d.eval_host((i, j, k))[1] == i * b * c + j * c + k - (j // b) * b * c
+    # transposed matrix: no contiguity
+    dt = vt.build_chain([("t", "permute", ("X",), {"perm": (1, 0)})], src, "t")
+    assert dt.info()["run"] == 1
+    # strided source (Sec. 2.1 stride vector given explicitly)
+    ds = vt.build_chain([], {"X": ((3, 4), "f32", 0, (8, 2))}, "X")
+    assert ds.eval_host((2, 3))[1] == 2 * 8 + 3 * 2 and ds.info()["run"] == 1
+
+
+def test_stacked_stage_case():
+    # a reshape that straddles a slice boundary needs a second stage
+    chain = [("a", "slice", ("X",), {"dim": 1, "start": 0, "stop": 3, "step": 1}),
+             ("b", "reshape", ("a",), {"shape": (2, 9)}),
+             ("c", "slice", ("b",), {"dim": 1, "start": 0, "stop": 8, "step": 1}),
+             ("R", "reshape", ("c",), {"shape": (16,)})]
+    wl = workloads.Workload("stack", "f32", {"X": np.arange(24, dtype=np.float32).reshape(6, 4)}, chain,
+                            {"kind": "materialize", "x": "R"})
+    dense = dm_ops.run_chain(chain, wl.sources)["R"]
+    d = vt.build_chain(chain, specs_of(wl), "R")
+    assert "|" in d.dump()                            # more than one stage
+    check_desc_against_dense(d, dense, wl)
+
+
+def test_error_paths():
+    src = {"X": ((4, 6), "f32"), "Y": ((4, 5), "f32"), "H": ((4, 6), "f16")}
+
+    def code(chain, result, tables=None, s=src):
+        with pytest.raises(vt.VtError) as ei:
+            vt.build_chain(chain, s, result, tables)
+        return ei.value.code
+
+    assert code([("a", "reshape", ("X",), {"shape": (5, 5)})], "a") == vt.ERR_SHAPE
+    assert code([("a", "slice", ("X",), {"dim": 1, "start": 2, "stop": 9, "step": 1})], "a") == vt.ERR_RANGE
+    assert code([("a", "slice", ("X",), {"dim": 2, "start": 0, "stop": 1, "step": 1})], "a") == vt.ERR_RANGE
+    assert code([("a", "split", ("X",), {"dim": 1, "sizes": (2, 2), "output": 0})], "a") == vt.ERR_RANGE
+    assert code([("a", "permute", ("X",), {"perm": (0, 0)})], "a") == vt.ERR_INVALID_ARG
+    assert code([("a", "concat", ("X", "Y"), {"dim": 0})], "a") == vt.ERR_SHAPE
+    assert code([("a", "concat", ("X", "H"), {"dim": 0})], "a") == vt.ERR_INVALID_ARG
+    assert code([("a", "expand", ("X",), {"shape": (4, 12)})], "a") == vt.ERR_SHAPE
+    t = {"i": np.array([0, 7], np.int32)}
+    assert code([("a", "index_select", ("X",), {"dim": 0, "index": "i"})], "a", t) == vt.ERR_RANGE
+    # index_select along a concatenated dim is outside the representation
+    t = {"i": np.array([0, 7], np.int32)}
+    chain = [("c", "concat", ("X", "Y"), {"dim": 1}), ("a", "index_select", ("c",), {"dim": 1, "index": "i"})]
+    assert code(chain, "a", t) == vt.ERR_UNSUPPORTED
+    # NULL arguments
+    assert vt.lib().vt_build(None, 0, None, 0, 0, None) == vt.ERR_INVALID_ARG
+    assert vt.lib().vt_desc_info(None, None, None, None, None, None) == vt.ERR_INVALID_ARG
+    assert b"NULL" in vt.lib().vt_last_error()
+    d = vt.build_chain([], src, "X")
+    with pytest.raises(vt.VtError) as ei:
+        d.eval_host((4, 0))
+    assert ei.value.code == vt.ERR_RANGE
+    # kernels refuse a descriptor without device pointers (no GPU call is made)
+    with pytest.raises(vt.VtError) as ei:
+        vt.vt_materialize(d, 16, stream=0)
+    assert ei.value.code == vt.ERR_INVALID_ARG

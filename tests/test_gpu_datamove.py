@@ -1,0 +1,195 @@
+"""GPU parity, pure data movement and the elementwise consumer (bit-exact bar)."""
+import numpy as np
+import pytest
+
+import workloads
+from oracle import consumers, dm_ops, index_maps
+from oracle.run import run_workload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2604_09558_amd as vt
+    from paper_2604_09558_amd import torch_io
+    vt.lib()
+    return vt, torch_io, torch
+
+
+def bits(a):
+    a = np.ascontiguousarray(a)
+    return a.view({2: np.uint16, 4: np.uint32}[a.dtype.itemsize])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_materialize_random_chains_bit_exact(gpu, dtype):
+    vt, tio, torch = gpu
+    done = 0
+    for seed in range(120):
+        wl = workloads.random_chain(seed, n_ops=6, dtype=dtype)
+        dense = dm_ops.run_chain(wl.chain, wl.sources, wl.index_tables)["R"]
+        dw = tio.DeviceWorkload(wl)
+        try:
+            d = dw.build("R")
+        except vt.VtError as e:
+            assert e.code == vt.ERR_UNSUPPORTED
+            continue
+        out = dw.empty(dense.shape)
+        out.fill_(-7.0)
+        try:
+            vt.vt_materialize(d, out)
+        except vt.VtError as e:
+            assert e.code == vt.ERR_UNSUPPORTED, str(e)
+            continue
+        torch.cuda.synchronize()
+        got = tio.to_host_bits(out)
+        assert np.array_equal(bits(got), bits(dense)), (seed, d.dump())
+        done += 1
+    assert done >= 80
+
+
+def test_materialize_vector_paths_and_ragged(gpu):
+    """Larger tensors that take the 16/8/4/2-byte vector paths, several blocks and a ragged tail."""
+    vt, tio, torch = gpu
+    rng = np.random.default_rng(0)
+    cases = [
+        # (source shape, chain, result)
+        ((6, 40, 8, 64), [("p", "permute", ("X",), {"perm": (0, 2, 1, 3)}), ("R", "reshape", ("p",), {"shape": (48, 2560)})]),
+        ((37, 1000), [("R", "slice", ("X",), {"dim": 1, "start": 8, "stop": 1000, "step": 1})]),       # run 992
+        ((37, 1001), [("R", "slice", ("X",), {"dim": 1, "start": 3, "stop": 1001, "step": 1})]),       # odd base: scalar path
+        ((5, 3, 130), [("u", "unsqueeze", ("X",), {"dim": 1}), ("e", "expand", ("u",), {"shape": (5, 4, 3, 130)}),
+                       ("R", "reshape", ("e",), {"shape": (20, 390)})]),
+        ((300, 257), [("R", "permute", ("X",), {"perm": (1, 0)})]),
+        ((64, 4, 36), [("R", "slice", ("X",), {"dim": 2, "start": 4, "stop": 36, "step": 2})]),
+    ]
+    for dtype in ("f32", "bf16"):
+        for shape, chain in cases:
+            x = workloads.encode(rng.normal(size=shape).astype(np.float32), dtype)
+            wl = workloads.Workload("case", dtype, {"X": x}, chain, {"kind": "materialize", "x": "R"})
+            dense = dm_ops.run_chain(chain, wl.sources)["R"]
+            dw = tio.DeviceWorkload(wl)
+            d = dw.build("R")
+            out = dw.empty(dense.shape)
+            vt.vt_materialize(d, out)
+            torch.cuda.synchronize()
+            assert np.array_equal(bits(tio.to_host_bits(out)), bits(dense)), (dtype, shape, d.dump())
+
+
+def test_copy_op_each_operator(gpu):
+    vt, tio, torch = gpu
+    rng = np.random.default_rng(1)
+    tables = {"t": np.array([3, 0, 0, 2, 1, 3, 2], np.int32)}
+    cases = [
+        ("permute", [(6, 5, 16)], {"perm": (2, 0, 1)}),
+        ("reshape", [(6, 5, 16)], {"shape": (30, 16)}),
+        ("slice", [(9, 64)], {"dim": 1, "start": 8, "stop": 40, "step": 1}),
+        ("split", [(9, 64)], {"dim": 1, "sizes": (16, 40, 8), "output": 1}),
+        ("concat", [(4, 8), (4, 24), (4, 3)], {"dim": 1}),
+        ("unsqueeze", [(4, 8)], {"dim": 1}),
+        ("expand", [(4, 1, 8)], {"shape": (4, 5, 8)}),
+        ("index_select", [(4, 32)], {"dim": 0, "index": "t"}),
+    ]
+    for dtype in ("f32", "f16"):
+        for op, shapes, p in cases:
+            ins = [workloads.encode(rng.normal(size=s).astype(np.float32), dtype) for s in shapes]
+            dense = dm_ops.run_statement(op, ins, p, tables)
+            brute = index_maps.materialize_bruteforce(op, ins, p, tables)
+            assert np.array_equal(bits(dense), bits(brute))
+            dev = [tio.to_device(a, dtype) for a in ins]
+            tdev = {k: torch.from_numpy(v).cuda() for k, v in tables.items()}
+            out = torch.empty(dense.shape, dtype=tio.TORCH_DTYPE[dtype], device="cuda:0")
+            vt.vt_copy_op(op, [(a.shape, dtype, t.data_ptr()) for a, t in zip(ins, dev)], p, out,
+                          tables=tables, table_ptrs={k: v.data_ptr() for k, v in tdev.items()})
+            torch.cuda.synchronize()
+            assert np.array_equal(bits(tio.to_host_bits(out)), bits(dense)), (dtype, op)
+
+
+def run_c1(vt, tio, torch, wl):
+    dw = tio.DeviceWorkload(wl)
+    v = dw.build("V")
+    z = dw.build("Z")
+    rows = v.shape[0]
+    out = torch.full((rows,), -1.0, dtype=torch.float32, device="cuda:0")
+    vt.vt_elementwise(vt.EW_ADD_ROWSUM, v, z, 0.0, out)
+    torch.cuda.synchronize()
+    return dw, v, z, out
+
+
+def test_c1_tiny_chain_bit_exact_and_equals_materialized(gpu):
+    vt, tio, torch = gpu
+    wl = workloads.c1_tiny_chain()
+    ref = run_workload(wl, keep_intermediates=True)
+    dw, v, z, out = run_c1(vt, tio, torch, wl)
+    got = out.cpu().numpy()
+    assert np.array_equal(bits(got), bits(ref["out"])), (got, ref["out"])
+    assert np.max(np.abs(got.astype(np.float64) - ref["out_f64"])) <= 1e-5
+    # materialized path on the GPU: every operator as an explicit copy kernel, then the same consumer
+    cur = {k: t for k, t in dw.tensors.items()}
+    shapes = {k: tuple(t.shape) for k, t in dw.tensors.items()}
+    for name, op, ins, p in wl.chain:
+        dense = ref["env"][name]
+        o = torch.empty(dense.shape, dtype=torch.float32, device="cuda:0")
+        vt.vt_copy_op(op, [(shapes[i], "f32", cur[i].data_ptr()) for i in ins], p, o)
+        cur[name], shapes[name] = o, dense.shape
+        torch.cuda.synchronize()
+        assert np.array_equal(bits(o.cpu().numpy()), bits(dense)), name
+    vm = vt.build_chain([], {"V": (shapes["V"], "f32", cur["V"].data_ptr())}, "V")
+    out2 = torch.empty(8, dtype=torch.float32, device="cuda:0")
+    vt.vt_elementwise(vt.EW_ADD_ROWSUM, vm, z, 0.0, out2)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(out2.cpu().numpy()), bits(got))
+
+
+@pytest.mark.parametrize("sizes", [(3, 5, 7, 1, 12, 4), (30, 50, 130, 7, 1400, 77), (2, 3, 64, 0, 6, 1)])
+def test_c1_other_sizes_and_order_pin(gpu, sizes):
+    """Rows longer than one wave pass (several columns per lane), ragged widths."""
+    vt, tio, torch = gpu
+    a, b, c, lo, hi, ny = sizes
+    wl = workloads.c1_tiny_chain(seed=3, a=a, b=b, c=c, lo=lo, hi=hi, ny=ny)
+    ref = run_workload(wl)
+    _, _, _, out = run_c1(vt, tio, torch, wl)
+    assert np.array_equal(bits(out.cpu().numpy()), bits(ref["out"]))
+
+
+def test_rowsum_order_pin_on_gpu(gpu):
+    """The cancellation example that separates the fixed order from a sequential sum."""
+    vt, tio, torch = gpu
+    v = np.zeros((2, 66), np.float32)
+    v[0, 0], v[0, 64], v[0, 1], v[0, 65] = 1e8, -1e8, 1.0, 1.0
+    v[1, 0], v[1, 1], v[1, 2] = 1e8, 1.0, -1e8
+    z = np.zeros_like(v)
+    ref = consumers.add_rowsum_f32(v, z)
+    assert list(ref) == [2.0, 1.0]
+    tv, tz = tio.to_device(v, "f32"), tio.to_device(z, "f32")
+    dv = vt.build_chain([], {"V": (v.shape, "f32", tv.data_ptr())}, "V")
+    dz = vt.build_chain([], {"Z": (z.shape, "f32", tz.data_ptr())}, "Z")
+    out = torch.empty(2, dtype=torch.float32, device="cuda:0")
+    vt.vt_elementwise(vt.EW_ADD_ROWSUM, dv, dz, 0.0, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), ref)
+
+
+@pytest.mark.parametrize("dtype,C", [("f16", 128), ("bf16", 96), ("f32", 200), ("f16", 1024), ("f16", 130)])
+def test_layernorm_virtual_rows(gpu, dtype, C):
+    vt, tio, torch = gpu
+    rng = np.random.default_rng(7)
+    B, R, win = 2, 6, 3
+    x = workloads.encode((rng.normal(size=(B, R, R, C)) * 2 + 0.5).astype(np.float32), dtype)
+    nw = R // win
+    chain = [("x1", "reshape", ("X",), {"shape": (B, nw, win, nw, win, C)}),
+             ("x2", "permute", ("x1",), {"perm": (0, 1, 3, 2, 4, 5)}),
+             ("T", "reshape", ("x2",), {"shape": (B * nw * nw, win * win, C)})]
+    wl = workloads.Workload("ln", dtype, {"X": x}, chain, {"kind": "materialize", "x": "T"})
+    dense = dm_ops.run_chain(chain, wl.sources)["T"]
+    ref = consumers.layernorm(consumers.decode(dense, dtype), 1e-5)
+    dw = tio.DeviceWorkload(wl)
+    d = dw.build("T")
+    out = dw.empty(dense.shape)
+    vt.vt_elementwise(vt.EW_LAYERNORM, d, None, 1e-5, out)
+    torch.cuda.synchronize()
+    got = tio.to_host_f64(out)
+    tol = {"f32": 2e-6, "f16": 2e-3, "bf16": 1.6e-2}[dtype]      # output rounding of values up to ~4
+    assert np.max(np.abs(got - ref)) <= tol * max(1.0, np.max(np.abs(ref)))

@@ -11,6 +11,7 @@ from .inputs import (  # noqa: F401
     Workload,
     encode,
     c1_tiny_chain,
+    c2_chain,
     c2_decode_attention,
     c3_oproj_gemm,
     c4_window_ln_linear,

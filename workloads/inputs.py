@@ -95,23 +95,9 @@ def c1_tiny_chain(seed: int = 0, a: int = 4, b: int = 6, c: int = 8, lo: int = 4
 # ----------------------------------------------------------------------------------------
 # C2: Llama-3-8B-shaped decode segment, bf16
 # ----------------------------------------------------------------------------------------
-def c2_decode_attention(seed: int = 0, B: int = 8, Hkv: int = 8, G: int = 4, S: int = 4096,
-                        D: int = 128, dtype: str = "bf16", poison_last_slot: bool = False) -> Workload:
-    """Fused QKV output [B,1,(Hq+2Hkv)*D] is cut into Q, K_new, V_new; K_new/V_new take the
-    last slot of a cache of capacity S (the first S-1 slots come from the cache); the Hkv
-    heads are broadcast G-fold to the Hq = Hkv*G query heads; decode attention over S keys.
-    ``poison_last_slot`` writes NaN into the cache slot the new token replaces: that slot
-    must never be read."""
+def c2_chain(B: int, Hkv: int, G: int, S: int, D: int) -> list:
+    """Statements of the decode segment (no data): Q, K, V as seen by the attention kernel."""
     Hq = Hkv * G
-    E = (Hq + 2 * Hkv) * D
-    qkv = _normal(seed, 0, (B, 1, E), 1.0, dtype)
-    kc32 = _rng(seed, 1).standard_normal(size=(B, Hkv, S, D), dtype=np.float32)
-    vc32 = _rng(seed, 2).standard_normal(size=(B, Hkv, S, D), dtype=np.float32)
-    if poison_last_slot:
-        kc32[:, :, S - 1, :] = np.nan
-        vc32[:, :, S - 1, :] = np.nan
-    src = {"QKV": qkv, "Kcache": encode(kc32, dtype), "Vcache": encode(vc32, dtype)}
-    del kc32, vc32
     sizes = (Hq * D, Hkv * D, Hkv * D)
     chain = [
         ("q0", "split", ("QKV",), {"dim": 2, "sizes": sizes, "output": 0}),
@@ -129,6 +115,27 @@ def c2_decode_attention(seed: int = 0, B: int = 8, Hkv: int = 8, G: int = 4, S: 
             (nm + "x", "expand", (nm + "u",), {"shape": (B, Hkv, G, S, D)}),
             (nm.upper(), "reshape", (nm + "x",), {"shape": (B, Hq, S, D)}),
         ]
+    return chain
+
+
+def c2_decode_attention(seed: int = 0, B: int = 8, Hkv: int = 8, G: int = 4, S: int = 4096,
+                        D: int = 128, dtype: str = "bf16", poison_last_slot: bool = False) -> Workload:
+    """Fused QKV output [B,1,(Hq+2Hkv)*D] is cut into Q, K_new, V_new; K_new/V_new take the
+    last slot of a cache of capacity S (the first S-1 slots come from the cache); the Hkv
+    heads are broadcast G-fold to the Hq = Hkv*G query heads; decode attention over S keys.
+    ``poison_last_slot`` writes NaN into the cache slot the new token replaces: that slot
+    must never be read."""
+    Hq = Hkv * G
+    E = (Hq + 2 * Hkv) * D
+    qkv = _normal(seed, 0, (B, 1, E), 1.0, dtype)
+    kc32 = _rng(seed, 1).standard_normal(size=(B, Hkv, S, D), dtype=np.float32)
+    vc32 = _rng(seed, 2).standard_normal(size=(B, Hkv, S, D), dtype=np.float32)
+    if poison_last_slot:
+        kc32[:, :, S - 1, :] = np.nan
+        vc32[:, :, S - 1, :] = np.nan
+    src = {"QKV": qkv, "Kcache": encode(kc32, dtype), "Vcache": encode(vc32, dtype)}
+    del kc32, vc32
+    chain = c2_chain(B, Hkv, G, S, D)
     return Workload("c2_decode_attention", dtype, src, chain,
                     {"kind": "decode_attn", "q": "Q", "k": "K", "v": "V",
                      "scale": 1.0 / float(np.sqrt(D))})
