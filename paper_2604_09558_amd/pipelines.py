@@ -1,0 +1,189 @@
+"""The two ways to run a workload on the GPU, as sequences of library calls.
+
+virtual:       build the descriptors of the consumer's inputs, launch the consumer.  No
+               intermediate of the chain exists in memory.
+materialized:  execute the chain's data-movement operators as explicit copy kernels into fresh
+               dense buffers (every operator, "full"), then launch the SAME consumer on
+               identity descriptors of the dense results.  This is the on-GPU comparison path.
+
+Only launches and buffer bookkeeping happen here; all arithmetic is in the library.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as vt
+from .torch_io import TORCH_DTYPE, DeviceWorkload
+
+
+class Materialized:
+    """Runs a chain op by op with vt_copy_op.  Buffers are allocated once (outside any timed
+    region) and reused by `run`."""
+
+    def __init__(self, dw: DeviceWorkload, wanted):
+        self.dw = dw
+        wl = dw.wl
+        defs = {out: (op, ins, p) for out, op, ins, p in wl.chain}
+        order, seen = [], set()
+
+        def visit(n):
+            if n in seen or n not in defs:
+                return
+            seen.add(n)
+            for i in defs[n][1]:
+                visit(i)
+            order.append(n)
+
+        for w in wanted:
+            visit(w)
+        self.order = order
+        self.defs = defs
+        self.shapes = {k: tuple(t.shape) for k, t in dw.tensors.items()}
+        self.bufs = dict(dw.tensors)
+        self.bytes_written = 0
+        for n in order:
+            op, ins, p = defs[n]
+            d = vt.build_chain([(n, op, ins, p)], {i: (self.shapes[i], wl.dtype) for i in ins}, n, wl.index_tables)
+            self.shapes[n] = d.shape
+            self.bufs[n] = torch.empty(d.shape, dtype=TORCH_DTYPE[wl.dtype], device=dw.device)
+            self.bytes_written += self.bufs[n].numel() * self.bufs[n].element_size()
+
+    def run(self, stream=None):
+        wl = self.dw.wl
+        tp = self.dw.table_ptrs()
+        for n in self.order:
+            op, ins, p = self.defs[n]
+            vt.vt_copy_op(op, [(self.shapes[i], wl.dtype, self.bufs[i].data_ptr()) for i in ins], p, self.bufs[n],
+                          stream=stream, tables=wl.index_tables, table_ptrs=tp)
+
+    def identity_desc(self, name):
+        return vt.build_chain([], {name: (self.shapes[name], self.dw.wl.dtype, self.bufs[name].data_ptr())}, name)
+
+
+# ------------------------------------------------------------------------------------------
+# C1: add + row-sum
+# ------------------------------------------------------------------------------------------
+class AddRowsum:
+    def __init__(self, dw: DeviceWorkload, materialized=False):
+        c = dw.wl.consumer
+        self.dw = dw
+        self.mat = Materialized(dw, [c["x"], c["y"]]) if materialized else None
+        if materialized:
+            self.x, self.y = self.mat.identity_desc(c["x"]), self.mat.identity_desc(c["y"])
+        else:
+            self.x, self.y = dw.build(c["x"]), dw.build(c["y"])
+        self.out = torch.empty(self.x.shape[0], dtype=torch.float32, device=dw.device)
+
+    def run(self, stream=None):
+        if self.mat:
+            self.mat.run(stream)
+        vt.vt_elementwise(vt.EW_ADD_ROWSUM, self.x, self.y, 0.0, self.out, stream=stream)
+        return self.out
+
+
+# ------------------------------------------------------------------------------------------
+# C2: decode attention
+# ------------------------------------------------------------------------------------------
+class DecodeAttention:
+    def __init__(self, dw: DeviceWorkload, materialized=False, n_splits=0, want_lse=True):
+        c = dw.wl.consumer
+        self.dw = dw
+        self.scale = float(c["scale"])
+        self.n_splits = n_splits
+        self.mat = Materialized(dw, [c["q"], c["k"], c["v"]]) if materialized else None
+        if materialized:
+            self.q, self.k, self.v = (self.mat.identity_desc(c[n]) for n in ("q", "k", "v"))
+        else:
+            self.q, self.k, self.v = (dw.build(c[n]) for n in ("q", "k", "v"))
+        B, Hq, S, D = self.k.shape
+        self.ws_bytes = vt.vt_decode_attn_workspace(B, Hq, D, S, n_splits)
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dw.device)
+        self.out = torch.empty((B, Hq, D), dtype=TORCH_DTYPE[dw.wl.dtype], device=dw.device)
+        self.lse = torch.empty((B, Hq), dtype=torch.float32, device=dw.device) if want_lse else None
+
+    def run(self, stream=None):
+        if self.mat:
+            self.mat.run(stream)
+        vt.vt_decode_attn(self.q, self.k, self.v, self.scale, self.out, self.ws, self.ws_bytes, self.n_splits,
+                          lse=self.lse, stream=stream)
+        return self.out
+
+
+def run_decode_attention(dw: DeviceWorkload, materialized=False, n_splits=0):
+    p = DecodeAttention(dw, materialized, n_splits)
+    p.run()
+    torch.cuda.synchronize()
+    return {"out": p.out, "lse": p.lse, "pipeline": p}
+
+
+# ------------------------------------------------------------------------------------------
+# C3 / C5: (grouped) GEMM;  C4: LayerNorm + linear
+# ------------------------------------------------------------------------------------------
+class Gemm:
+    """consumer kinds "gemm" (one group), "grouped_gemm" (one group per expert, outputs stacked
+    row-wise in one buffer) and "ln_linear" (LayerNorm prologue fused into the GEMM, or, with
+    fused=False, the LayerNorm kernel followed by the GEMM on its dense result)."""
+
+    def __init__(self, dw: DeviceWorkload, materialized=False, fused=True):
+        c = dw.wl.consumer
+        wl = dw.wl
+        self.dw = dw
+        kind = c["kind"]
+        if kind == "gemm":
+            a_names, b_names = [c["a"]], [c["b"]]
+        elif kind == "grouped_gemm":
+            a_names, b_names = list(c["a"]), list(c["b"])
+        elif kind == "ln_linear":
+            a_names, b_names = [c["x"]], [c["w"]]
+        else:
+            raise ValueError(kind)
+        self.kind = kind
+        self.eps = float(c.get("eps", 0.0))
+        self.fused = fused
+        self.mat = Materialized(dw, a_names + b_names) if materialized else None
+        get = self.mat.identity_desc if materialized else dw.build
+        self.A = [get(n) for n in a_names]
+        self.B = [get(n) for n in b_names]
+        rows = []
+        for a in self.A:
+            shp = a.shape
+            r = 1
+            for s in shp[:-1]:
+                r *= s
+            rows.append(r)
+        self.N = self.B[0].shape[-1]
+        self.rows = rows
+        self.out = torch.empty((sum(rows), self.N), dtype=TORCH_DTYPE[wl.dtype], device=dw.device)
+        self.C = []
+        off = 0
+        for r in rows:
+            self.C.append(self.out.data_ptr() + off * self.N * self.out.element_size())
+            off += r
+        self.ln_buf = None
+        if kind == "ln_linear" and not fused:
+            shp = self.A[0].shape
+            self.ln_buf = torch.empty(shp, dtype=TORCH_DTYPE[wl.dtype], device=dw.device)
+            self.ln_desc = vt.build_chain([], {"ln": (shp, wl.dtype, self.ln_buf.data_ptr())}, "ln")
+
+    def run(self, stream=None):
+        if self.mat:
+            self.mat.run(stream)
+        dt = self.dw.wl.dtype
+        if self.kind == "ln_linear":
+            if self.fused:
+                vt.vt_gemm(self.A, self.B, self.C, dt, vt.GEMM_LAYERNORM, self.eps, stream=stream)
+            else:
+                vt.vt_elementwise(vt.EW_LAYERNORM, self.A[0], None, self.eps, self.ln_buf, stream=stream)
+                vt.vt_gemm([self.ln_desc], self.B, self.C, dt, vt.GEMM_PLAIN, 0.0, stream=stream)
+        else:
+            vt.vt_gemm(self.A, self.B, self.C, dt, vt.GEMM_PLAIN, 0.0, stream=stream)
+        return self.out
+
+
+def make_pipeline(dw: DeviceWorkload, materialized=False, **kw):
+    kind = dw.wl.consumer["kind"]
+    if kind == "add_rowsum":
+        return AddRowsum(dw, materialized)
+    if kind == "decode_attn":
+        return DecodeAttention(dw, materialized, **kw)
+    return Gemm(dw, materialized, **kw)
