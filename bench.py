@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the virtual-tensor hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input: the consumer
+kernel reading its operands through the descriptors (virtual path).  The default workload is
+the Llama-3-8B-shaped decode segment (config 2 of the benchmark spec): fused QKV output + KV cache
+-> GQA flash-decoding, bf16, batch 8, context 4096.
+
+Inputs are resident in HBM before the timed region.  To keep the 256 MB Infinity Cache from
+serving the 134 MB working set, the steps rotate over several independent copies of the
+inputs (more than 1 GB in total), so every step streams its K/V from HBM.
+
+Prints one JSON line (see the fields at the bottom).  `--gpus N` with N > 1 is refused: this
+build is single-GPU.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X published dense bf16/fp16 matrix peak
+
+
+def algorithmic_bytes_c2(B, Hkv, G, S, D, n_splits, esz=2):
+    """Bytes the method itself must move for one decode-attention step (kernel
+    table): K and V once (un-expanded), the fused QKV row, the output, and the split-K partial
+    results written once and read once."""
+    Hq = Hkv * G
+    kv = 2 * B * Hkv * S * D * esz
+    qkv = B * (Hq + 2 * Hkv) * D * esz
+    out = B * Hq * D * esz
+    ws = 2 * B * Hq * n_splits * (D + 2) * 4
+    return kv + qkv + out + ws
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--copies", type=int, default=8, help="independent input copies the steps rotate over")
+    ap.add_argument("--no-graph", action="store_true", help="launch every step from Python instead of replaying a HIP graph")
+    ap.add_argument("--no-materialized", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--n-splits", type=int, default=0, help="context splits of the attention kernel (0 = library's choice)")
+    ap.add_argument("--context", type=int, default=4096, help="context length (the benchmark's is 4096; others are for tuning)")
+    ap.add_argument("--extra", default="", help="comma list of further chains to time (c1,c3,c4,c5)")
+    return ap.parse_args()
+
+
+def time_steps(torch, step_fns, steps, warmup, use_graph):
+    """Runs warmup + exactly `steps` calls of step_fns[k % R] on the current stream, bracketed by
+    synchronize on both sides, and by two HIP events on that stream.  With use_graph the R
+    step functions are captured once into one HIP graph (R launches per replay); steps that
+    do not fill a whole replay are launched eagerly.  Returns (wall ms per step, event ms per
+    step)."""
+    R = len(step_fns)
+    stream = torch.cuda.current_stream()
+    graph = None
+    if use_graph and steps >= R:
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            for fn in step_fns:
+                fn(side)            # warm the code path on the capture stream
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for fn in step_fns:
+                fn(side)
+        torch.cuda.synchronize()
+
+    def run(n):
+        k = 0
+        if graph is not None:
+            while k + R <= n:
+                graph.replay()
+                k += R
+        while k < n:
+            step_fns[k % R](stream)
+            k += 1
+
+    run(warmup)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    run(steps)
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+
+def cpu_baseline_c2(wl, alg_bytes):
+    """The oracle as it stands on the host cores: one full pass (materialize every op, then
+    fp64 attention) over the same workload."""
+    import psutil
+    from oracle.run import run_workload
+    proc = psutil.Process()
+    c0 = proc.cpu_times()
+    t0 = time.perf_counter()
+    run_workload(wl)
+    dt = time.perf_counter() - t0
+    c1 = proc.cpu_times()
+    cpu = (c1.user - c0.user) + (c1.system - c0.system)
+    return {"value": alg_bytes / dt / 1e9, "unit": "GB/s", "cores": max(1, int(round(cpu / dt))), "kind": "oracle",
+            "sample": "one full pass of config 2 (B=8, context 4096): %.2f s wall" % dt, "seconds": dt}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU (one MI355X); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2604_09558_amd as vt
+    import workloads
+    from paper_2604_09558_amd import pipelines
+    from paper_2604_09558_amd import torch_io as tio
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    vt.lib()
+    torch.cuda.set_device(0)
+    B, Hkv, G, S, D = 8, 8, 4, a.context, 128
+
+    # ---- inputs: R independent copies resident in HBM
+    wls = [workloads.c2_decode_attention(seed=s, B=B, Hkv=Hkv, G=G, S=S, D=D) for s in range(a.copies)]
+    dws = [tio.DeviceWorkload(w) for w in wls]
+    virt = [pipelines.DecodeAttention(dw, materialized=False, n_splits=a.n_splits, want_lse=False) for dw in dws]
+    torch.cuda.synchronize()
+
+    def mk(p):
+        return lambda stream: p.run(stream)
+
+    # the library's own choice of split count for this shape
+    n_splits = a.n_splits if a.n_splits > 0 else 512 // (B * Hkv)
+    alg = algorithmic_bytes_c2(B, Hkv, G, S, D, n_splits)
+    wall_ms, ev_mean = time_steps(torch, [mk(p) for p in virt], a.steps, a.warmup, not a.no_graph)
+    value = alg / (wall_ms * 1e-3) / 1e9
+    achieved = alg / (ev_mean * 1e-3) / 1e9
+
+    out = {
+        "metric": "virtual vs materialized latency (µs) and achieved HBM GB/s % of peak per chain",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "c2: Llama-3-8B decode segment, fused QKV [8,1,6144] + KV cache [8,8,4096,128] -> "
+                               "GQA 4:1 flash-decode, context 4096, Q/K/V read through descriptors",
+                   "batch": B, "context": S, "kv_heads": Hkv, "q_heads": Hkv * G, "head_dim": D,
+                   "input_copies_rotated": a.copies, "launch": "eager" if a.no_graph else "hip graph replay"},
+        "virtual_us": round(wall_ms * 1e3, 2),
+        "hbm_pct_of_peak": round(100.0 * value / HBM_PEAK_GBS, 1),
+        "algorithmic_bytes": alg,
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "k_decode_attn", "event_us_per_launch": round(ev_mean * 1e3, 2)},
+    }
+
+    if not a.no_materialized:
+        mat = pipelines.DecodeAttention(dws[0], materialized=True, want_lse=False)
+        torch.cuda.synchronize()
+        m_steps = max(5, min(50, a.steps // 8))
+        m_wall, m_ev = time_steps(torch, [mk(mat)], m_steps, 3, False)
+        out["materialized_us"] = {"full": round(m_wall * 1e3, 1)}
+        out["speedup_vs_materialized_full"] = round(m_wall / wall_ms, 2)
+        out["intermediate_bytes_saved"] = mat.mat.bytes_written
+        del mat
+        torch.cuda.empty_cache()
+
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_c2(wls[0], alg)
+    print(json.dumps(out, ensure_ascii=False))
+
+
+if __name__ == "__main__":
+    main()

@@ -151,10 +151,17 @@ int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* const* C, in
  * reads the un-expanded cache).  Q virtual [B,Hq,1,D], K and V virtual [B,Hq,S,D]
  * (f16/bf16, D = 128).  out dense [B,Hq,D], same dtype.  softmax(scale * q.k) in fp32.
  * Query heads whose K/V rows coincide (a broadcast digit in the map) share one read.
- * workspace: device pointer of at least vt_decode_attn_workspace(...) bytes, holding the
- * per-split partial results; n_splits = 0 lets the library choose.  lse (device, B*Hq floats,
+ * workspace: device pointer (16-byte aligned) of at least vt_decode_attn_workspace(...) bytes,
+ * holding arrival counters and the per-split partial results, prepared once with
+ * vt_decode_attn_workspace_init; the split that finishes last for a (batch, kv head) merges
+ * the partial results inside the same launch.  n_splits = 0 lets the library choose.  lse (device, B*Hq floats,
  * may be NULL) receives the log-sum-exp of the scaled scores. */
 size_t vt_decode_attn_workspace(int B, int Hq, int D, int S, int n_splits);
+/* Clears a freshly allocated workspace (its first bytes hold one arrival counter per (batch,
+ * kv head), which must be zero when vt_decode_attn starts and which vt_decode_attn leaves at
+ * zero).  Call once after allocating, on the stream of the first vt_decode_attn, or clear
+ * the buffer yourself.  Launches that share a workspace must not overlap in time. */
+int vt_decode_attn_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float scale, void* out,
                    float* lse, void* workspace, size_t workspace_bytes, int n_splits, void* stream);
 

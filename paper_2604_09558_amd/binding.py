@@ -70,6 +70,7 @@ def lib():
         L.vt_gemm.argtypes = [C.POINTER(P), C.POINTER(P), C.POINTER(P), C.c_int, C.c_int, C.c_int, C.c_float, P]
         L.vt_decode_attn_workspace.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
         L.vt_decode_attn_workspace.restype = C.c_size_t
+        L.vt_decode_attn_workspace_init.argtypes = [P, C.c_size_t, P]
         L.vt_decode_attn.argtypes = [P, P, P, C.c_float, P, P, P, C.c_size_t, C.c_int, P]
         L.vt_last_error.restype = C.c_char_p
         L.vt_version.restype = C.c_char_p
@@ -282,6 +283,10 @@ def vt_gemm(A, B, Cs, c_dtype, prologue=GEMM_PLAIN, eps=0.0, stream=None):
 
 def vt_decode_attn_workspace(B, Hq, D, S, n_splits=0) -> int:
     return int(lib().vt_decode_attn_workspace(B, Hq, D, S, n_splits))
+
+
+def vt_decode_attn_workspace_init(workspace, workspace_bytes: int, stream=None):
+    _check(lib().vt_decode_attn_workspace_init(_ptr(workspace), workspace_bytes, _stream(stream)))
 
 
 def vt_decode_attn(Q: Desc, K: Desc, V: Desc, scale: float, out, workspace, workspace_bytes: int, n_splits=0,

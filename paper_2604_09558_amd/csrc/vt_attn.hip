@@ -5,23 +5,31 @@
 // Work split: one workgroup per (batch b, kv head g, context split s); WAVES waves share the
 // split's rows in tiles of 32.  All G query heads of the group are served from one read of
 // K and V (the broadcast digit of the descriptor, i.e. the Expand that is never executed).
+// The context is cut into segments at the piece boundaries of the two descriptors (the
+// Concat that is never executed); a tile never straddles a segment, so inside a tile a row
+// address is one wave-uniform base plus a per-lane constant.
 //
 // Per tile of 32 context rows and per wave:
 //   S^T = K . Q^T   on v_mfma_f32_16x16x32 (rows = context, cols = the group's heads, padded
 //                   to 16).  K rows are fetched with fully coalesced 16-byte loads (16 lanes
 //                   per 256-byte row), staged through an XOR-swizzled LDS tile and read back in
 //                   the matrix-core operand layout without bank conflicts.
-//   online softmax  in the accumulator layout (lane = head, 4 rows per 16-row block).
+//   softmax         in the accumulator layout (lane = head, 4 rows per 16-row block) against a
+//                   reference maximum that is only moved (and the accumulators rescaled) when
+//                   a score exceeds it by more than a threshold: the common tile costs one
+//                   fma and one exp2 per score and no cross-lane traffic.
 //   O^T += V^T . P^T on the same instruction.  V never touches LDS: each lane loads 8 rows of
 //                   its own 8-column chunk (again whole rows per 16 lanes), transposes the 8x8
 //                   block inside its registers (v_perm_b32) and feeds it as the A operand;
 //                   the contraction index is permuted identically for P, which the softmax
 //                   already holds in exactly that layout.
-// A second, tiny kernel merges the per-split partial results.
+// The workgroup that finishes last for a (b, g) merges the splits' partial results (a ticket
+// counter per (b, g) in the workspace; no second launch, no spinning).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <numeric>
 
@@ -35,29 +43,36 @@ namespace {
 constexpr int kD = 128;          // head dim
 constexpr int kTile = 32;        // context rows per wave step
 constexpr int kMaxAttnPieces = 4;
+constexpr int kMaxSegs = 8;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-struct AttnPiece {
-  const char* ptr;       // element (b=0, g=0, t=t_lo, d=0)
-  int64_t sb, sh;        // bytes per batch / per kv head
-  uint32_t st;           // bytes per context row
+// A stretch of the context [t_lo, t_hi) in which K rows come from one source region and V
+// rows from one source region (the union of the piece boundaries of the two descriptors).
+struct AttnSeg {
+  const char* k;         // K element (b=0, g=0, t=t_lo, d=0)
+  const char* v;
+  int64_t k_sb, k_sh, v_sb, v_sh;   // bytes per batch / per kv head
+  uint32_t k_st, v_st;              // bytes per context row
   int32_t t_lo, t_hi;
 };
-struct AttnOperand {
-  AttnPiece pc[kMaxAttnPieces];
-  int32_t n;
-};
 struct AttnParams {
-  AttnOperand K, V;
+  AttnSeg seg[kMaxSegs];
+  int32_t n_seg;
   const char* q_ptr;
   int64_t q_sb, q_sh;    // bytes
   int32_t B, Hkv, G, S, n_splits, rows_per_split;
   float scale_log2;      // softmax scale * log2(e)
-  float* ws_o;           // [B, Hkv, n_splits, G, D]
+  uint32_t* tickets;     // [B, Hkv], zero between launches
   float* ws_ml;          // [B, Hkv, n_splits, G, 2]
+  float* ws_o;           // [B, Hkv, n_splits, G, D]
+  void* out;             // [B, Hq, D]
+  float* lse;            // [B, Hq] or NULL
 };
 
 template <typename T>
@@ -65,53 +80,87 @@ struct Mfma;
 template <>
 struct Mfma<bf16_t> {
   typedef bf16x8 vec;
+  static constexpr float kThreshold = 16.0f;   // p <= 2^16: far inside the bf16 exponent range
   static __device__ __forceinline__ f32x4 run(vec a, vec b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
   }
   static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
-    return (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
+    f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
   }
 };
 template <>
 struct Mfma<f16_t> {
   typedef f16x8 vec;
+  static constexpr float kThreshold = 0.0f;    // keep p <= 1 (f16 tops out at 65504)
   static __device__ __forceinline__ f32x4 run(vec a, vec b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
   }
   static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
-    _Float16 l = (_Float16)lo, h = (_Float16)hi;
-    return (uint32_t)__builtin_bit_cast(uint16_t, l) | ((uint32_t)__builtin_bit_cast(uint16_t, h) << 16);
+    f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
   }
 };
 
-// Address of context row t of operand X for (b, g); t is clamped by the caller to [0, S).
-__device__ __forceinline__ const char* row_address(const AttnOperand& X, int b, int g, int t) {
-  const char* base = X.pc[0].ptr + b * X.pc[0].sb + g * X.pc[0].sh;
-  uint32_t st = X.pc[0].st;
-  int lo = X.pc[0].t_lo;
-#pragma unroll
-  for (int i = 1; i < kMaxAttnPieces; ++i) {
-    if (i < X.n && t >= X.pc[i].t_lo) {
-      base = X.pc[i].ptr + b * X.pc[i].sb + g * X.pc[i].sh;
-      st = X.pc[i].st;
-      lo = X.pc[i].t_lo;
-    }
-  }
-  return base + (uint64_t)(uint32_t)(t - lo) * st;
+struct Regs16 {
+  uint32_t w[4];
+};
+
+__device__ __forceinline__ Regs16 load16(const char* base, uint32_t off) {
+  uint4 t = *reinterpret_cast<const uint4*>(base + off);
+  Regs16 r;
+  r.w[0] = t.x; r.w[1] = t.y; r.w[2] = t.z; r.w[3] = t.w;
+  return r;
 }
 
-template <typename T, int WAVES>
-__global__ void __launch_bounds__(WAVES * 64) k_decode_attn(const AttnParams P) {
+// Tiles never straddle a segment: the i-th tile of the split [t_begin, t_end) is found by
+// walking the segments; all values are wave-uniform.
+struct TilePos {
+  int seg, r0, end;      // rows [r0, min(r0+32, end)) of segment seg are valid
+};
+
+__device__ __forceinline__ int count_tiles(const AttnParams& P, int t_begin, int t_end) {
+  int n = 0;
+  for (int s = 0; s < P.n_seg; ++s) {
+    int a = max(P.seg[s].t_lo, t_begin), e = min(P.seg[s].t_hi, t_end);
+    if (e > a) n += (e - a + kTile - 1) / kTile;
+  }
+  return n;
+}
+
+__device__ __forceinline__ TilePos locate_tile(const AttnParams& P, int t_begin, int t_end, int i) {
+  TilePos tp{0, t_begin, t_begin};
+  for (int s = 0; s < P.n_seg; ++s) {
+    int a = max(P.seg[s].t_lo, t_begin), e = min(P.seg[s].t_hi, t_end);
+    if (e <= a) continue;
+    int nt = (e - a + kTile - 1) / kTile;
+    if (i < nt) {
+      tp.seg = s;
+      tp.r0 = a + i * kTile;
+      tp.end = e;
+      return tp;
+    }
+    i -= nt;
+  }
+  return tp;
+}
+
+template <typename T, int WAVES, int OCC>
+__global__ void __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
+k_decode_attn(const AttnParams P) {
   typedef Mfma<T> M;
   typedef typename M::vec opvec;
   __shared__ uint4 lds[WAVES][kTile * 16];   // per wave: 32 rows x 16 chunks of 16 bytes, swizzled
+  __shared__ float red_ml[WAVES * 16 * 2];   // [WAVES][16][2]
+  __shared__ uint32_t ticket_sh;
 
   const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int l16 = lane & 15, lg = lane >> 4;
   const int t_begin = split * P.rows_per_split;
   const int t_end = min(P.S, t_begin + P.rows_per_split);
-  const int n_tiles = (t_end - t_begin + kTile - 1) / kTile;
+  const int n_tiles = count_tiles(P, t_begin, t_end);
+  const float c = P.scale_log2;
 
   // Q^T operand: lane (head l16, k-group lg) holds 8 consecutive d for each of the 4 k-steps
   opvec qreg[4];
@@ -125,41 +174,67 @@ __global__ void __launch_bounds__(WAVES * 64) k_decode_attn(const AttnParams P) 
     }
   }
 
-  float m_run = -1.0e30f;   // running max (log2 domain) of head l16, identical in the 4 lane groups
-  float l_run = 0.0f;       // this lane's share of the running denominator
+  float m_ref = -1.0e30f;   // reference maximum (log2 domain) of head l16, identical in the 4 lane groups
+  float l_run = 0.0f;       // this lane's share of the denominator, relative to m_ref
   f32x4 acc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  uint4 kst[8], vst[8];
-  auto issue_loads = [&](int tile) {
-    const int r0 = t_begin + tile * kTile;
+  // Loads of one tile.  K: instruction j covers rows 4j..4j+3 (16 lanes per 256-byte row);
+  // V: instruction j is contraction slot j of the lane group, row (j>>2)*16 + lg*4 + (j&3).
+  // In a full tile the address is a wave-uniform base per instruction plus ONE per-lane
+  // offset; a partial tile (last of a segment) clamps its rows onto the last valid one.
+  Regs16 kst[8], vst[8];
+  auto issue_k = [&](const TilePos& tp) {
+    const AttnSeg& sg = P.seg[tp.seg];
+    const uint32_t st = sg.k_st;
+    const char* kb = sg.k + b * sg.k_sb + g * sg.k_sh + (int64_t)(tp.r0 - sg.t_lo) * st;
+    if (tp.r0 + kTile <= tp.end) {
+      const uint32_t off = lg * st + l16 * 16;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      int tk = min(r0 + 4 * j + lg, t_end - 1);                          // K: instruction j covers rows 4j..4j+3
-      kst[j] = *reinterpret_cast<const uint4*>(row_address(P.K, b, g, tk) + l16 * 16);
+      for (int j = 0; j < 8; ++j) kst[j] = load16(kb + (size_t)(4 * j) * st, off);
+    } else {
+      const int span = tp.end - 1 - tp.r0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) kst[j] = load16(kb, (uint32_t)min(4 * j + lg, span) * st + l16 * 16);
     }
+  };
+  auto issue_v = [&](const TilePos& tp) {
+    const AttnSeg& sg = P.seg[tp.seg];
+    const uint32_t st = sg.v_st;
+    const char* vb = sg.v + b * sg.v_sb + g * sg.v_sh + (int64_t)(tp.r0 - sg.t_lo) * st;
+    if (tp.r0 + kTile <= tp.end) {
+      const uint32_t off = lg * 4 * st + l16 * 16;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      int tv = min(r0 + (j >> 2) * 16 + lg * 4 + (j & 3), t_end - 1);    // V: contraction slot j of lane group lg
-      vst[j] = *reinterpret_cast<const uint4*>(row_address(P.V, b, g, tv) + l16 * 16);
+      for (int j = 0; j < 8; ++j) vst[j] = load16(vb + (size_t)((j >> 2) * 16 + (j & 3)) * st, off);
+    } else {
+      const int span = tp.end - 1 - tp.r0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        vst[j] = load16(vb, (uint32_t)min((j >> 2) * 16 + lg * 4 + (j & 3), span) * st + l16 * 16);
     }
   };
 
   uint4* my_lds = lds[wave];
-  if (wave < n_tiles) issue_loads(wave);
+  TilePos cur = locate_tile(P, t_begin, t_end, wave);
+  if (wave < n_tiles) {
+    issue_k(cur);
+    issue_v(cur);
+  }
   for (int tile = wave; tile < n_tiles; tile += WAVES) {
-    const int r0 = t_begin + tile * kTile;
+    const int r0 = cur.r0, r_end = cur.end;
+    const bool partial = r0 + kTile > r_end;
+    const bool more = tile + WAVES < n_tiles;
     // ---- stage K through LDS (swizzle: chunk c of row r sits at unit c ^ (r & 15))
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       int r = 4 * j + lg;
-      my_lds[r * 16 + (l16 ^ (r & 15))] = kst[j];
+      my_lds[r * 16 + (l16 ^ (r & 15))] = make_uint4(kst[j].w[0], kst[j].w[1], kst[j].w[2], kst[j].w[3]);
     }
-    uint4 vcur[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) vcur[j] = vst[j];
-    if (tile + WAVES < n_tiles) issue_loads(tile + WAVES);
+    if (more) {
+      cur = locate_tile(P, t_begin, t_end, tile + WAVES);
+      issue_k(cur);                      // next tile's K is in flight during this tile's math
+    }
 
     // ---- S^T = K . Q^T : two 16-row blocks, 4 k-steps each
     f32x4 s[2];
@@ -173,34 +248,35 @@ __global__ void __launch_bounds__(WAVES * 64) k_decode_attn(const AttnParams P) 
         s[u] = M::run(__builtin_bit_cast(opvec, raw), qreg[kk], s[u]);
       }
     }
-    // ---- online softmax; lane holds head l16, rows r0 + u*16 + lg*4 + i
+    // ---- softmax; lane holds head l16 and rows r0 + (j>>2)*16 + lg*4 + (j&3), j = 0..7
     float sv[8];
-    float tmax = -1.0e30f;
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+    for (int j = 0; j < 8; ++j) sv[j] = s[j >> 2][j & 3];
+    if (partial) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        int t = r0 + u * 16 + lg * 4 + i;
-        float x = s[u][i] * P.scale_log2;
-        x = t < t_end ? x : -1.0e30f;
-        sv[u * 4 + i] = x;
-        tmax = fmaxf(tmax, x);
+      for (int j = 0; j < 8; ++j)
+        if (r0 + (j >> 2) * 16 + lg * 4 + (j & 3) >= r_end) sv[j] = -3.0e38f;
+    }
+    float tmax = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+    tmax = fmaxf(tmax * c, -1.0e30f);
+    if (__builtin_amdgcn_ballot_w64(tmax > m_ref + M::kThreshold) != 0) {
+      // move the reference maximum of every head to its new maximum and rescale what was
+      // accumulated against the old one (rare after the first tiles)
+      float mn = fmaxf(m_ref, tmax);
+      mn = fmaxf(mn, __shfl_xor(mn, 16, 64));
+      mn = fmaxf(mn, __shfl_xor(mn, 32, 64));
+      const float alpha = __builtin_amdgcn_exp2f(m_ref - mn);
+      m_ref = mn;
+      l_run *= alpha;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        acc[e][0] *= alpha; acc[e][1] *= alpha; acc[e][2] *= alpha; acc[e][3] *= alpha;
       }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    const float m_new = fmaxf(m_run, tmax);
-    const float alpha = exp2f(m_run - m_new);
-    m_run = m_new;
-    float psum = 0.f;
+    }
     float pv[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      int t = r0 + (j >> 2) * 16 + lg * 4 + (j & 3);
-      float p = t < t_end ? exp2f(sv[j] - m_new) : 0.f;
-      pv[j] = p;
-      psum += p;
-    }
-    l_run = l_run * alpha + psum;
+    for (int j = 0; j < 8; ++j) pv[j] = __builtin_amdgcn_exp2f(fmaf(sv[j], c, -m_ref));   // masked rows: exp2(-huge) = 0
+    l_run += ((pv[0] + pv[1]) + (pv[2] + pv[3])) + ((pv[4] + pv[5]) + (pv[6] + pv[7]));
     uint4 praw = make_uint4(M::pack2(pv[0], pv[1]), M::pack2(pv[2], pv[3]), M::pack2(pv[4], pv[5]),
                             M::pack2(pv[6], pv[7]));
     const opvec pop = __builtin_bit_cast(opvec, praw);
@@ -210,23 +286,17 @@ __global__ void __launch_bounds__(WAVES * 64) k_decode_attn(const AttnParams P) 
       const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
       uint32_t w[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const uint32_t* lo = reinterpret_cast<const uint32_t*>(&vcur[2 * u]);
-        const uint32_t* hi = reinterpret_cast<const uint32_t*>(&vcur[2 * u + 1]);
-        w[u] = __builtin_amdgcn_perm(hi[e >> 1], lo[e >> 1], sel);
-      }
+      for (int u = 0; u < 4; ++u) w[u] = __builtin_amdgcn_perm(vst[2 * u + 1].w[e >> 1], vst[2 * u].w[e >> 1], sel);
       uint4 traw = make_uint4(w[0], w[1], w[2], w[3]);
-      f32x4 a = acc[e];
-      a[0] *= alpha; a[1] *= alpha; a[2] *= alpha; a[3] *= alpha;
-      acc[e] = M::run(__builtin_bit_cast(opvec, traw), pop, a);
+      acc[e] = M::run(__builtin_bit_cast(opvec, traw), pop, acc[e]);
     }
+    if (more) issue_v(cur);              // next tile's V: lands while the next K tile is being scored
   }
 
   // ---- merge the waves of the workgroup through LDS, then write the split's partial result
   l_run += __shfl_xor(l_run, 16, 64);
   l_run += __shfl_xor(l_run, 32, 64);
   __syncthreads();                       // every wave is done with its K tile
-  __shared__ float red_ml[WAVES * 16 * 2];                // [WAVES][16][2]
   float* red_o = reinterpret_cast<float*>(&lds[0][0]);    // [WAVES][G][D] floats: at most the K tiles' 32 KB
   const int G = P.G;
   if (l16 < G) {
@@ -235,12 +305,13 @@ __global__ void __launch_bounds__(WAVES * 64) k_decode_attn(const AttnParams P) 
 #pragma unroll
       for (int i = 0; i < 4; ++i) red_o[(wave * G + l16) * kD + (lg * 4 + i) * 8 + e] = acc[e][i];
     if (lg == 0) {
-      red_ml[(wave * 16 + l16) * 2 + 0] = m_run;
+      red_ml[(wave * 16 + l16) * 2 + 0] = m_ref;
       red_ml[(wave * 16 + l16) * 2 + 1] = l_run;
     }
   }
   __syncthreads();
-  const size_t unit = ((size_t)(b * P.Hkv + g) * P.n_splits + split);
+  const int bg = b * P.Hkv + g;
+  const size_t unit = (size_t)bg * P.n_splits + split;
   for (int idx = threadIdx.x; idx < G * kD; idx += WAVES * 64) {
     int h = idx / kD;
     float mx = -1.0e30f;
@@ -249,36 +320,78 @@ __global__ void __launch_bounds__(WAVES * 64) k_decode_attn(const AttnParams P) 
     float o = 0.f, l = 0.f;
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) {
-      float sc = exp2f(red_ml[(w * 16 + h) * 2] - mx);
+      float sc = __builtin_amdgcn_exp2f(red_ml[(w * 16 + h) * 2] - mx);
       o += red_o[(w * G + h) * kD + (idx - h * kD)] * sc;
       l += red_ml[(w * 16 + h) * 2 + 1] * sc;
     }
-    P.ws_o[unit * G * kD + idx] = o;
+    // partial results go out as device-scope atomic stores (written through to where every
+    // compute die sees them), so that no cache write-back is needed before the ticket
+    __hip_atomic_store(&P.ws_o[unit * G * kD + idx], o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (idx == h * kD) {
-      P.ws_ml[(unit * G + h) * 2 + 0] = mx;
-      P.ws_ml[(unit * G + h) * 2 + 1] = l;
+      __hip_atomic_store(&P.ws_ml[(unit * G + h) * 2 + 0], mx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&P.ws_ml[(unit * G + h) * 2 + 1], l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+  }
+
+  // ---- the last workgroup of this (b, g) to arrive merges the splits.  The barrier waits for
+  // every wave's stores to complete before one thread takes the ticket (a device-scope atomic);
+  // the merging workgroup reads the partial results with device-scope atomic loads, which do
+  // not hit stale cache lines.  atomicInc wraps to 0 at n_splits - 1, which leaves the counter
+  // ready for the next launch.  No wave ever waits for another workgroup.
+  __builtin_amdgcn_s_waitcnt(0);         // this wave's stores have completed (vmcnt = 0)
+  __syncthreads();
+  if (threadIdx.x == 0) ticket_sh = atomicInc(&P.tickets[bg], (uint32_t)(P.n_splits - 1));
+  __syncthreads();
+  if (ticket_sh != (uint32_t)(P.n_splits - 1)) return;
+  const size_t u0 = (size_t)bg * P.n_splits;
+  const int ns = P.n_splits;
+  T* out = static_cast<T*>(P.out);
+  auto ld = [](const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+  // (m, l) of every split and head go to LDS (ns * G * 2 contiguous floats; the K tiles' LDS is
+  // free now); the first eight partial outputs of this thread's (head, d) are requested in the
+  // same breath so that the merge costs one memory round trip, not two
+  float* ml_sh = reinterpret_cast<float*>(&lds[0][0]);
+  const int idx0 = threadIdx.x;                      // G * kD >= 128 threads are busy; the rest idle through
+  const int h0 = min(idx0 / kD, G - 1), d0 = idx0 % kD;
+  float v0[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) v0[u] = ld(&P.ws_o[((u0 + min(u, ns - 1)) * G + h0) * kD + d0]);
+  for (int i = threadIdx.x; i < ns * G * 2; i += WAVES * 64) ml_sh[i] = ld(&P.ws_ml[u0 * G * 2 + i]);
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < G * kD; idx += WAVES * 64) {
+    const int h = idx / kD, d = idx - h * kD;
+    float mx = -1.0e30f;
+    for (int sp = 0; sp < ns; ++sp) mx = fmaxf(mx, ml_sh[(sp * G + h) * 2]);
+    float o = 0.f, l = 0.f;
+    for (int sp0 = 0; sp0 < ns; sp0 += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {          // eight independent loads in flight
+        if (idx == idx0 && sp0 == 0) {
+          v[u] = v0[u];
+        } else {
+          int sp = min(sp0 + u, ns - 1);
+          v[u] = ld(&P.ws_o[((u0 + sp) * G + h) * kD + d]);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (sp0 + u < ns) {
+          float sc = __builtin_amdgcn_exp2f(ml_sh[((sp0 + u) * G + h) * 2] - mx);
+          o += v[u] * sc;
+          l += ml_sh[((sp0 + u) * G + h) * 2 + 1] * sc;
+        }
+      }
+    }
+    const size_t hq = (size_t)bg * G + h;      // = b * Hq + g * G + h
+    out[hq * kD + d] = from_float<T>(o / l);
+    if (P.lse && d == 0) P.lse[hq] = (mx + log2f(l)) * 0.6931471805599453f;
   }
 }
 
-// out[b, hq, :] = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M); one block of 128 threads per head.
-template <typename T>
-__global__ void __launch_bounds__(kD) k_decode_combine(const float* __restrict__ ws_o, const float* __restrict__ ws_ml,
-                                                       T* __restrict__ out, float* __restrict__ lse, int G, int n_splits) {
-  const int hq = blockIdx.x;            // b * Hq + h
-  const int unit = hq / G, j = hq - unit * G;
-  const int d = threadIdx.x;
-  float mx = -1.0e30f;
-  for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, ws_ml[(((size_t)unit * n_splits + s) * G + j) * 2]);
-  float o = 0.f, l = 0.f;
-  for (int s = 0; s < n_splits; ++s) {
-    size_t u = (size_t)unit * n_splits + s;
-    float sc = exp2f(ws_ml[(u * G + j) * 2] - mx);
-    o += ws_o[(u * G + j) * kD + d] * sc;
-    l += ws_ml[(u * G + j) * 2 + 1] * sc;
-  }
-  out[(size_t)hq * kD + d] = from_float<T>(o / l);
-  if (lse && d == 0) lse[hq] = (mx + log2f(l)) * 0.6931471805599453f;
+__global__ void k_zero_words(uint32_t* p, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
 }
 
 // ---------------------------------------------------------------- host: descriptor -> plan
@@ -305,6 +418,17 @@ int64_t broadcast_factor(const std::vector<Digit>& g) {
   for (int k = (int)g.size() - 1; k >= 0 && g[k].stride == 0 && g[k].table < 0; --k) f *= g[k].radix;
   return f;
 }
+
+struct PlanPiece {
+  const char* ptr;
+  int64_t sb, sh;
+  uint32_t st;
+  int32_t t_lo, t_hi;
+};
+struct AttnOperand {
+  PlanPiece pc[kMaxAttnPieces];
+  int n;
+};
 
 int plan_operand(const vt_desc& d, const char* name, int64_t G, AttnOperand* out) {
   const int esz = 2;
@@ -343,7 +467,7 @@ int plan_operand(const vt_desc& d, const char* name, int64_t G, AttnOperand* out
     if (!single_plain(hg, &sh)) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": kv-head dim must be one strided digit");
     const vt_source& src = d.sources[p.src];
     if (!src.ptr) return fail(VT_ERR_INVALID_ARG, std::string(name) + ": source without a device pointer");
-    AttnPiece& a = out->pc[i];
+    PlanPiece& a = out->pc[i];
     a.ptr = static_cast<const char*>(src.ptr) + p.v.base * esz;
     a.sb = sb * esz;
     a.sh = sh * esz;
@@ -370,6 +494,8 @@ constexpr int kWaves = 4;
 
 }  // namespace
 
+static size_t ticket_bytes(int64_t B, int64_t Hq) { return (size_t)((B * Hq * 4 + 255) / 256 * 256); }
+
 extern "C" {
 
 size_t vt_decode_attn_workspace(int B, int Hq, int D, int S, int n_splits) {
@@ -377,7 +503,15 @@ size_t vt_decode_attn_workspace(int B, int Hq, int D, int S, int n_splits) {
   // an upper bound that does not need the grouping: the fewest kv heads (16 query heads each)
   // give the most splits
   int ns = choose_splits(B * std::max(1, Hq / 16), S, n_splits);
-  return (size_t)B * Hq * ns * ((size_t)D + 2) * sizeof(float);
+  return ticket_bytes(B, Hq) + (size_t)B * Hq * ns * ((size_t)D + 2) * sizeof(float);
+}
+
+int vt_decode_attn_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+  if (!workspace || (uintptr_t)workspace % 16) return fail(VT_ERR_INVALID_ARG, "vt_decode_attn_workspace_init: NULL or misaligned workspace");
+  size_t words = workspace_bytes / 4;
+  if (words == 0) return VT_OK;
+  hipLaunchKernelGGL(k_zero_words, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, (hipStream_t)stream, (uint32_t*)workspace, words);
+  return check_launch("vt_decode_attn_workspace_init");
 }
 
 int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float scale, void* out, float* lse,
@@ -405,10 +539,29 @@ int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float s
   while (G > 16 || Hq % G) --G;      // the matrix-core tile holds at most 16 heads
   AttnParams P;
   memset(&P, 0, sizeof(P));
-  int rc = plan_operand(*K, "K", G, &P.K);
+  AttnOperand ko, vo;
+  int rc = plan_operand(*K, "K", G, &ko);
   if (rc != VT_OK) return rc;
-  rc = plan_operand(*V, "V", G, &P.V);
+  rc = plan_operand(*V, "V", G, &vo);
   if (rc != VT_OK) return rc;
+  {  // segments = union of the piece boundaries of K and V
+    int ik = 0, iv = 0, t = 0, n = 0;
+    while (t < S) {
+      while (ko.pc[ik].t_hi <= t) ++ik;
+      while (vo.pc[iv].t_hi <= t) ++iv;
+      int e = std::min(ko.pc[ik].t_hi, vo.pc[iv].t_hi);
+      if (n >= kMaxSegs) return fail(VT_ERR_UNSUPPORTED, "vt_decode_attn: more than 8 context segments");
+      AttnSeg& sg = P.seg[n++];
+      sg.k = ko.pc[ik].ptr + (int64_t)(t - ko.pc[ik].t_lo) * ko.pc[ik].st;
+      sg.v = vo.pc[iv].ptr + (int64_t)(t - vo.pc[iv].t_lo) * vo.pc[iv].st;
+      sg.k_sb = ko.pc[ik].sb; sg.k_sh = ko.pc[ik].sh; sg.k_st = ko.pc[ik].st;
+      sg.v_sb = vo.pc[iv].sb; sg.v_sh = vo.pc[iv].sh; sg.v_st = vo.pc[iv].st;
+      sg.t_lo = t;
+      sg.t_hi = e;
+      t = e;
+    }
+    P.n_seg = n;
+  }
   // Q: one piece, one stage, contiguous rows
   if (Q->pieces.size() != 1 || !Q->pieces[0].v.lower.empty()) return fail(VT_ERR_UNSUPPORTED, "Q: must be a single strided piece");
   {
@@ -428,7 +581,8 @@ int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float s
   int rows = (int)((S + ns - 1) / ns);
   rows = (rows + kTile - 1) / kTile * kTile;
   const int ns_eff = (int)((S + rows - 1) / rows);
-  const size_t need = (size_t)B * Hq * ns_eff * ((size_t)kD + 2) * sizeof(float);
+  if ((int64_t)ns_eff * G * 2 > kWaves * kTile * 64) return fail(VT_ERR_UNSUPPORTED, "vt_decode_attn: too many splits");
+  const size_t need = ticket_bytes(B, Hq) + (size_t)B * Hq * ns_eff * ((size_t)kD + 2) * sizeof(float);
   if (workspace_bytes < need) return fail(VT_ERR_INVALID_ARG, "vt_decode_attn: workspace too small");
   if ((uintptr_t)workspace % 16 || (uintptr_t)out % 2) return fail(VT_ERR_INVALID_ARG, "vt_decode_attn: misaligned workspace or out");
   P.B = (int)B;
@@ -438,25 +592,25 @@ int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float s
   P.n_splits = ns_eff;
   P.rows_per_split = rows;
   P.scale_log2 = scale * 1.4426950408889634f;
-  P.ws_o = static_cast<float*>(workspace);
-  P.ws_ml = P.ws_o + (size_t)B * Hq * ns_eff * kD;
+  P.tickets = static_cast<uint32_t*>(workspace);
+  P.ws_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + ticket_bytes(B, Hq));
+  P.ws_o = P.ws_ml + (size_t)B * Hq * ns_eff * 2;
+  P.out = out;
+  P.lse = lse;
   hipStream_t st = (hipStream_t)stream;
   dim3 grid(ns_eff, Hkv, (unsigned)B);
+  static const int occ = [] {
+    const char* e = getenv("VT_ATTN_OCC");     // tuning knob: waves per SIMD the kernel is compiled for
+    return e && atoi(e) == 2 ? 2 : 3;
+  }();
   if (Q->dtype == VT_BF16) {
-    hipLaunchKernelGGL((k_decode_attn<bf16_t, kWaves>), grid, dim3(kWaves * 64), 0, st, P);
+    if (occ == 2) hipLaunchKernelGGL((k_decode_attn<bf16_t, kWaves, 2>), grid, dim3(kWaves * 64), 0, st, P);
+    else hipLaunchKernelGGL((k_decode_attn<bf16_t, kWaves, 3>), grid, dim3(kWaves * 64), 0, st, P);
   } else {
-    hipLaunchKernelGGL((k_decode_attn<f16_t, kWaves>), grid, dim3(kWaves * 64), 0, st, P);
+    if (occ == 2) hipLaunchKernelGGL((k_decode_attn<f16_t, kWaves, 2>), grid, dim3(kWaves * 64), 0, st, P);
+    else hipLaunchKernelGGL((k_decode_attn<f16_t, kWaves, 3>), grid, dim3(kWaves * 64), 0, st, P);
   }
-  rc = check_launch("vt_decode_attn");
-  if (rc != VT_OK) return rc;
-  if (Q->dtype == VT_BF16) {
-    hipLaunchKernelGGL(k_decode_combine<bf16_t>, dim3((unsigned)(B * Hq)), dim3(kD), 0, st, P.ws_o, P.ws_ml, (bf16_t*)out, lse,
-                       (int)G, ns_eff);
-  } else {
-    hipLaunchKernelGGL(k_decode_combine<f16_t>, dim3((unsigned)(B * Hq)), dim3(kD), 0, st, P.ws_o, P.ws_ml, (f16_t*)out, lse,
-                       (int)G, ns_eff);
-  }
-  return check_launch("vt_decode_attn(combine)");
+  return check_launch("vt_decode_attn");
 }
 
 }  // extern "C"

@@ -98,6 +98,7 @@ class DecodeAttention:
         B, Hq, S, D = self.k.shape
         self.ws_bytes = vt.vt_decode_attn_workspace(B, Hq, D, S, n_splits)
         self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dw.device)
+        vt.vt_decode_attn_workspace_init(self.ws, self.ws_bytes)
         self.out = torch.empty((B, Hq, D), dtype=TORCH_DTYPE[dw.wl.dtype], device=dw.device)
         self.lse = torch.empty((B, Hq), dtype=torch.float32, device=dw.device) if want_lse else None
 
