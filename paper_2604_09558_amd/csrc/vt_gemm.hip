@@ -1,7 +1,415 @@
+// GEMM consumer on the matrix cores: C[g] = A[g] . B[g], A and B read through virtual-tensor
+// descriptors (Sec. 2.3: the three stages of a tiled matmul; only stage 1 changes, Sec. 4.2).
+// gfx950, wave64, v_mfma_f32_32x32x16 (bf16 / f16 operands, fp32 accumulation).
+//
+// Tiling: one workgroup of 4 waves computes a 256 x 256 tile of C over K in steps of 64; each
+// wave owns a 128 x 128 quadrant (4 x 4 MFMA blocks, 256 accumulator registers per lane).
+// Both operands are staged in LDS with the contraction index contiguous ([row][k] and
+// [col][k], 16-byte units, XOR-swizzled) so that every fragment is one conflict-free
+// ds_read_b128 in the matrix-core operand layout; LDS is double buffered, one barrier per step.
+//
+// Stage 1 through the map (block-wise virtual tensor I/O): the map of a 2-D operand separates
+// into row_offset(m) + col_offset(k).  A thread keeps the offsets of its 8 rows for the whole
+// K loop (mixed-radix digits and, for index_select, a table lookup: evaluated once) and
+// evaluates the column offset of its 8-element chunk once per step.  Global loads stay
+// 16 bytes per lane and cover whole 128-byte lines whenever the map keeps runs of 64 elements.
+//   A ([M,K], K contiguous in runs of >= 8): chunk -> LDS directly.
+//   B ([K,N], N contiguous, the usual row-major weight): each thread loads an 8 (k) x 8 (n)
+//     block with 8 row loads, transposes it in registers (v_perm_b32) and writes 8 k-contiguous
+//     units, so B arrives in LDS as B^T without any strided access.
+// Workgroup ids are remapped so that each XCD (own L2) works on a contiguous band of tiles,
+// walked in groups of 8 tile rows, which keeps the A and B panels of neighbouring tiles in
+// that L2.  A launch covers up to 8 groups (grouped GEMM: one tile list over all groups).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <type_traits>
+
 #include "vt_device.h"
+#include "vt_numeric.h"
+
 using namespace vt;
-extern "C" {
-int vt_gemm(const vt_desc* const*, const vt_desc* const*, void* const*, int, int, int, float, void*) {
-  return fail(VT_ERR_UNSUPPORTED, "vt_gemm: not built yet");
+
+namespace {
+
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int kMaxGroups = 8;
+constexpr int kGroupRows = 8;      // tile rows walked together (L2 reuse of the B panel)
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+template <int ND>
+struct AxisMap {
+  FastDiv radix[ND];        // outer -> inner
+  int64_t stride[ND];       // elements
+  const int32_t* table;     // digit `tdig` is looked up in this table first (index_select), or NULL
+  int32_t nd, tdig;
+};
+
+struct GemmGroup {
+  const char* a;
+  const char* b;
+  char* c;
+  AxisMap<5> a_row;
+  AxisMap<3> a_col, b_row, b_col;
+  int32_t M, tile_begin, tiles_m, pad;
+};
+
+struct GemmParams {
+  GemmGroup g[kMaxGroups];
+  int32_t n_groups, N, K, tiles_n, total_tiles, chunk, c_f32, pad;
+};
+
+// Offset contributed by index v along an axis.  Unused digits are padded on the host with
+// radix 1 / stride 0, so the walk is branch-free; the table (index_select) is only possible on
+// the row axis of A, which is evaluated once per thread before the K loop.
+template <int ND, bool TABLE>
+__device__ __forceinline__ int64_t axis_off(const AxisMap<ND>& a, uint32_t v) {
+  int64_t off = 0;
+#pragma unroll
+  for (int d = ND - 1; d >= 0; --d) {
+    uint32_t r;
+    if (d > 0) {
+      uint32_t q = fdiv(v, a.radix[d]);
+      r = v - q * a.radix[d].d;
+      v = q;
+    } else {
+      r = v;
+    }
+    if (TABLE) {
+      if (d == a.tdig) r = (uint32_t)a.table[r];
+    }
+    off += (int64_t)r * a.stride[d];
+  }
+  return off;
 }
+
+__device__ __forceinline__ uint32_t word(const uint4& v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
+
+template <typename T>
+struct Mma;
+template <>
+struct Mma<bf16_t> {
+  typedef bf16x8 vec;
+  static __device__ __forceinline__ f32x16 run(vec a, vec b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
+};
+template <>
+struct Mma<f16_t> {
+  typedef f16x8 vec;
+  static __device__ __forceinline__ f32x16 run(vec a, vec b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+  }
+};
+
+template <typename T, bool C_F32>
+__global__ void __launch_bounds__(256) k_gemm(const GemmParams P) {
+  typedef Mma<T> M_;
+  typedef typename M_::vec opvec;
+  __shared__ uint4 ldsA[2][BM * 8];     // [row][8 chunks of 8 k], chunk c of row r at r*8 + (c ^ (r & 7))
+  __shared__ uint4 ldsB[2][BN * 8];     // [col][8 chunks of 8 k], chunk c of col n at n*8 + (c ^ ((n ^ (n >> 3)) & 7))
+
+  // ---- which tile: XCD-contiguous bands, groups of kGroupRows tile rows
+  const int wg = blockIdx.x;
+  const int slot = wg >> 3;
+  const int idx = (wg & 7) * P.chunk + slot;
+  if (slot >= P.chunk || idx >= P.total_tiles) return;
+  int gi = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxGroups; ++i)
+    if (i < P.n_groups && idx >= P.g[i].tile_begin) gi = i;
+  const GemmGroup& G = P.g[gi];
+  const int local = idx - G.tile_begin;
+  const int width = kGroupRows * P.tiles_n;
+  const int first_m = (local / width) * kGroupRows;
+  const int gsz = min(G.tiles_m - first_m, kGroupRows);
+  const int tm = first_m + (local % width) % gsz;
+  const int tn = (local % width) / gsz;
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int Mg = G.M, N = P.N, K = P.K;
+
+  // ---- stage-1 bookkeeping: A rows of this thread (fixed over the K loop)
+  const int a_c = t & 7, a_r0 = t >> 3;                 // chunk (8 k) and first row; rows a_r0 + 32 i
+  int64_t a_rowoff[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a_rowoff[i] = axis_off<5, true>(G.a_row, (uint32_t)min(tm * BM + a_r0 + 32 * i, Mg - 1));
+  // B: an 8 (k) x 8 (n) block per thread; column chunk fixed over the K loop
+  const int b_cn = t & 31, b_kb = t >> 5;
+  const int b_n = tn * BN + b_cn * 8;
+  const bool b_nvalid = b_n < N;
+  const int64_t b_coloff = axis_off<3, false>(G.b_col, (uint32_t)min(b_n, N - 8));
+
+  uint4 ra[8], rb[8];
+  auto load_global = [&](int k0) {
+    const int ka = k0 + a_c * 8;
+    if (ka < K) {
+      const int64_t co = axis_off<3, false>(G.a_col, (uint32_t)ka);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ra[i] = *reinterpret_cast<const uint4*>(G.a + (a_rowoff[i] + co) * 2);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ra[i] = make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int kb = k0 + b_kb * 8 + j;
+      if (kb < K && b_nvalid) {
+        rb[j] = *reinterpret_cast<const uint4*>(G.b + (axis_off<3, false>(G.b_row, (uint32_t)kb) + b_coloff) * 2);
+      } else {
+        rb[j] = make_uint4(0, 0, 0, 0);
+      }
+    }
+  };
+  auto store_lds = [&](int buf) {
+    uint4* sa = ldsA[buf];
+    uint4* sb = ldsB[buf];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = a_r0 + 32 * i;
+      sa[r * 8 + (a_c ^ (r & 7))] = ra[i];
+    }
+    // transpose the 8x8 block: output e holds column b_cn*8 + e, its 8 k values contiguous
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+      uint32_t w[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        w[u] = __builtin_amdgcn_perm(word(rb[2 * u + 1], e >> 1), word(rb[2 * u], e >> 1), sel);
+      }
+      const int n = b_cn * 8 + e;
+      sb[n * 8 + (b_kb ^ ((n ^ (n >> 3)) & 7))] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+  };
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int nk = (K + BK - 1) / BK;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  for (int it = 0; it < nk; ++it) {
+    const int cur = it & 1;
+    if (it + 1 < nk) load_global((it + 1) * BK);
+    const uint4* sa = ldsA[cur];
+    const uint4* sb = ldsB[cur];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      opvec af[4], bf[4];
+      const int chunk = ks * 2 + lh;
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb) {
+        const int r = wm * 128 + mb * 32 + l32;
+        af[mb] = __builtin_bit_cast(opvec, sa[r * 8 + (chunk ^ (r & 7))]);
+      }
+#pragma unroll
+      for (int nb = 0; nb < 4; ++nb) {
+        const int n = wn * 128 + nb * 32 + l32;
+        bf[nb] = __builtin_bit_cast(opvec, sb[n * 8 + (chunk ^ ((n ^ (n >> 3)) & 7))]);
+      }
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) acc[mb][nb] = M_::run(af[mb], bf[nb], acc[mb][nb]);
+    }
+    if (it + 1 < nk) store_lds(cur ^ 1);
+    __syncthreads();
+  }
+
+  // ---- stage 3: plain contiguous store of the tile (lanes 0..31 write 32 consecutive columns)
+  typedef typename std::conditional<C_F32, float, T>::type CT;
+  CT* cbase = reinterpret_cast<CT*>(G.c);
+  const bool full = (tm + 1) * BM <= Mg && (tn + 1) * BN <= N;
+#pragma unroll
+  for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+      const int col = tn * BN + wn * 128 + nb * 32 + l32;
+      const int row0 = tm * BM + wm * 128 + mb * 32 + lh * 4;
+      CT* cp = cbase + (size_t)row0 * N + col;
+      if (full) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) cp[(size_t)(8 * j + i) * N] = from_float<CT>(acc[mb][nb][4 * j + i]);
+      } else if (col < N) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (row0 + 8 * j + i < Mg) cp[(size_t)(8 * j + i) * N] = from_float<CT>(acc[mb][nb][4 * j + i]);
+      }
+    }
+}
+
+// ---------------------------------------------------------------- host: descriptor -> axis maps
+// Concatenates the digit groups of dims [d0, d1) of a single-piece, single-stage descriptor.
+template <int ND>
+int make_axis(const vt_desc& d, const Piece& p, int d0, int d1, AxisMap<ND>* out, const char* what, bool allow_table = false) {
+  memset(out, 0, sizeof(*out));
+  out->tdig = -1;
+  std::vector<Digit> dg;
+  for (int i = d0; i < d1; ++i)
+    for (const Digit& g : p.v.groups[i]) dg.push_back(g);
+  // merge neighbours that form one dense digit
+  std::vector<Digit> m;
+  for (const Digit& g : dg) {
+    if (!m.empty() && m.back().table < 0 && g.table < 0 && m.back().stride == g.stride * g.radix) {
+      m.back().radix *= g.radix;
+      m.back().stride = g.stride;
+    } else {
+      m.push_back(g);
+    }
+  }
+  if ((int)m.size() > ND) return fail(VT_ERR_UNSUPPORTED, std::string(what) + ": too many index digits for the GEMM loader");
+  out->nd = (int)m.size();
+  for (int i = 0; i < ND; ++i) {        // padding: digits that are always 0
+    out->radix[i] = make_fastdiv(1);
+    out->stride[i] = 0;
+  }
+  // real digits occupy the innermost slots so that slot 0 (which takes what is left of the
+  // index without a division) is either the outermost real digit or padding over a zero
+  const int shift = ND - (int)m.size();
+  for (size_t i0 = 0; i0 < m.size(); ++i0) {
+    const int i = (int)i0 + shift;
+    const Digit& mi = m[i0];
+    if (mi.radix >= (1ll << 31)) return fail(VT_ERR_UNSUPPORTED, std::string(what) + ": extent too large");
+    out->radix[i] = make_fastdiv((uint32_t)mi.radix);
+    out->stride[i] = mi.stride;
+    if (mi.table >= 0) {
+      if (!allow_table) return fail(VT_ERR_UNSUPPORTED, std::string(what) + ": index_select is only supported on the rows of A");
+      if (out->table) return fail(VT_ERR_UNSUPPORTED, std::string(what) + ": two index tables on one axis");
+      const Table& t = d.tables[mi.table];
+      if (!t.dev) return fail(VT_ERR_INVALID_ARG, std::string(what) + ": index table without a device pointer");
+      out->table = t.dev + mi.table_off;
+      out->tdig = i;
+    }
+  }
+  return VT_OK;
+}
+
+template <int ND>
+bool strides_multiple_of(const AxisMap<ND>& a, int64_t q, int skip_inner) {
+  for (int i = 0; i < ND - skip_inner; ++i)
+    if (a.stride[i] % q) return false;
+  return true;
+}
+
+int plan_a(const vt_desc& d, GemmGroup* g, int64_t* M, int64_t* K) {
+  int n = (int)d.shape.size();
+  if (n < 2) return fail(VT_ERR_SHAPE, "vt_gemm: A must have at least 2 dims");
+  if (d.pieces.size() != 1 || !d.pieces[0].v.lower.empty())
+    return fail(VT_ERR_UNSUPPORTED, "vt_gemm: A must be a single piece with one index stage");
+  const Piece& p = d.pieces[0];
+  *K = d.shape[n - 1];
+  *M = 1;
+  for (int i = 0; i < n - 1; ++i) *M *= d.shape[i];
+  int rc = make_axis(d, p, 0, n - 1, &g->a_row, "vt_gemm: A rows", true);
+  if (rc != VT_OK) return rc;
+  rc = make_axis(d, p, n - 1, n, &g->a_col, "vt_gemm: A columns");
+  if (rc != VT_OK) return rc;
+  const vt_source& src = d.sources[p.src];
+  if (!src.ptr) return fail(VT_ERR_INVALID_ARG, "vt_gemm: A source without a device pointer");
+  g->a = static_cast<const char*>(src.ptr) + p.v.base * 2;
+  const AxisMap<3>& c = g->a_col;
+  bool ok = *K % 8 == 0 && (uintptr_t)g->a % 16 == 0 && strides_multiple_of(g->a_row, 8, 0);
+  ok = ok && c.nd >= 1 && c.stride[2] == 1 && c.radix[2].d % 8 == 0 && strides_multiple_of(c, 8, 1);
+  if (!ok) return fail(VT_ERR_UNSUPPORTED, "vt_gemm: A needs runs of 8 contiguous, 16-byte aligned elements along K");
+  return VT_OK;
+}
+
+int plan_b(const vt_desc& d, GemmGroup* g, int64_t* K, int64_t* N) {
+  if (d.shape.size() != 2) return fail(VT_ERR_SHAPE, "vt_gemm: B must be [K,N]");
+  if (d.pieces.size() != 1 || !d.pieces[0].v.lower.empty())
+    return fail(VT_ERR_UNSUPPORTED, "vt_gemm: B must be a single piece with one index stage");
+  const Piece& p = d.pieces[0];
+  *K = d.shape[0];
+  *N = d.shape[1];
+  int rc = make_axis(d, p, 0, 1, &g->b_row, "vt_gemm: B rows");
+  if (rc != VT_OK) return rc;
+  rc = make_axis(d, p, 1, 2, &g->b_col, "vt_gemm: B columns");
+  if (rc != VT_OK) return rc;
+  const vt_source& src = d.sources[p.src];
+  if (!src.ptr) return fail(VT_ERR_INVALID_ARG, "vt_gemm: B source without a device pointer");
+  g->b = static_cast<const char*>(src.ptr) + p.v.base * 2;
+  const AxisMap<3>& c = g->b_col;
+  bool ok = *N % 8 == 0 && (uintptr_t)g->b % 16 == 0 && strides_multiple_of(g->b_row, 8, 0) && c.nd >= 1 &&
+            c.stride[2] == 1 && c.radix[2].d % 8 == 0 && strides_multiple_of(c, 8, 1);
+  if (!ok) return fail(VT_ERR_UNSUPPORTED, "vt_gemm: B needs runs of 8 contiguous, 16-byte aligned elements along N");
+  return VT_OK;
+}
+
+}  // namespace
+
+extern "C" int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* const* C, int n_groups, int c_dtype,
+                       int prologue, float eps, void* stream) {
+  if (!A || !B || !C || n_groups < 1) return fail(VT_ERR_INVALID_ARG, "vt_gemm: NULL argument");
+  if (prologue != VT_GEMM_PLAIN) return fail(VT_ERR_UNSUPPORTED, "vt_gemm: LayerNorm prologue not built yet");
+  (void)eps;
+  const int dt = A[0] ? A[0]->dtype : -1;
+  if (dt != VT_BF16 && dt != VT_F16) return fail(VT_ERR_INVALID_ARG, "vt_gemm: operands must be f16 or bf16");
+  if (c_dtype != dt && c_dtype != VT_F32) return fail(VT_ERR_INVALID_ARG, "vt_gemm: C must have the operand dtype or f32");
+  hipStream_t st = (hipStream_t)stream;
+  int64_t N = -1, K = -1;
+  for (int g0 = 0; g0 < n_groups; g0 += kMaxGroups) {
+    GemmParams P;
+    memset(&P, 0, sizeof(P));
+    const int ng = std::min(kMaxGroups, n_groups - g0);
+    int tiles = 0;
+    for (int i = 0; i < ng; ++i) {
+      const vt_desc* a = A[g0 + i];
+      const vt_desc* b = B[g0 + i];
+      if (!a || !b || !C[g0 + i]) return fail(VT_ERR_INVALID_ARG, "vt_gemm: NULL descriptor or output");
+      if (a->dtype != dt || b->dtype != dt) return fail(VT_ERR_INVALID_ARG, "vt_gemm: mixed operand dtypes");
+      int64_t M, Ka, Kb, Nb;
+      int rc = plan_a(*a, &P.g[i], &M, &Ka);
+      if (rc != VT_OK) return rc;
+      rc = plan_b(*b, &P.g[i], &Kb, &Nb);
+      if (rc != VT_OK) return rc;
+      if (Ka != Kb) return fail(VT_ERR_SHAPE, "vt_gemm: inner dims of A and B differ");
+      if (N < 0) {
+        N = Nb;
+        K = Ka;
+      }
+      if (Nb != N || Ka != K) return fail(VT_ERR_SHAPE, "vt_gemm: all groups must share K and N");
+      if (M >= (1ll << 31) || N >= (1ll << 31) || K >= (1ll << 31)) return fail(VT_ERR_UNSUPPORTED, "vt_gemm: extents too large");
+      if ((uintptr_t)C[g0 + i] % 4) return fail(VT_ERR_INVALID_ARG, "vt_gemm: misaligned C");
+      P.g[i].c = static_cast<char*>(C[g0 + i]);
+      P.g[i].M = (int32_t)M;
+      P.g[i].tiles_m = (int32_t)((M + BM - 1) / BM);
+      P.g[i].tile_begin = tiles;
+      tiles += P.g[i].tiles_m * (int32_t)((N + BN - 1) / BN);
+    }
+    P.n_groups = ng;
+    P.N = (int32_t)N;
+    P.K = (int32_t)K;
+    P.tiles_n = (int32_t)((N + BN - 1) / BN);
+    P.total_tiles = tiles;
+    P.chunk = (tiles + 7) / 8;
+    P.c_f32 = c_dtype == VT_F32;
+    dim3 grid(P.chunk * 8);
+    if (dt == VT_BF16) {
+      if (P.c_f32) hipLaunchKernelGGL((k_gemm<bf16_t, true>), grid, dim3(256), 0, st, P);
+      else hipLaunchKernelGGL((k_gemm<bf16_t, false>), grid, dim3(256), 0, st, P);
+    } else {
+      if (P.c_f32) hipLaunchKernelGGL((k_gemm<f16_t, true>), grid, dim3(256), 0, st, P);
+      else hipLaunchKernelGGL((k_gemm<f16_t, false>), grid, dim3(256), 0, st, P);
+    }
+    int rc = check_launch("vt_gemm");
+    if (rc != VT_OK) return rc;
+  }
+  return VT_OK;
 }

@@ -1,0 +1,137 @@
+"""GPU parity of the GEMM consumer (bf16/f16 operands, fp32 accumulation) against the CPU
+oracle: |gpu - oracle| <= 1e-2 + 1e-2 |oracle| (the benchmark's stated bar)."""
+import numpy as np
+import pytest
+
+import workloads
+from oracle import consumers, dm_ops
+from oracle.run import run_workload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2604_09558_amd as vt
+    from paper_2604_09558_amd import pipelines, torch_io
+    vt.lib()
+    return vt, torch_io, pipelines, torch
+
+
+def check(got, ref, atol=1e-2, rtol=1e-2):
+    err = np.abs(got - ref)
+    bad = err > atol + rtol * np.abs(ref)
+    assert not bad.any(), "max abs err %.3e at %s (ref %.4f)" % (
+        err.max(), np.unravel_index(err.argmax(), err.shape), ref[np.unravel_index(err.argmax(), err.shape)])
+    return err.max()
+
+
+def run(pipelines, tio, torch, wl, **kw):
+    p = pipelines.Gemm(tio.DeviceWorkload(wl), **kw)
+    p.run()
+    torch.cuda.synchronize()
+    return p
+
+
+C3_CASES = [
+    # B, H, S, D, N, dtype
+    (2, 4, 96, 128, 256, "bf16"),       # M = 192 (< one tile), K = 512
+    (3, 2, 100, 64, 520, "bf16"),       # ragged M = 300, ragged N = 520, K = 128
+    (1, 3, 513, 8, 264, "f16"),         # K = 24: a single partial K step; M = 513 (3 tiles, ragged)
+    (2, 5, 130, 16, 1032, "bf16"),      # K = 80: one full and one partial K step; 5 column tiles
+]
+
+
+@pytest.mark.parametrize("B,H,S,D,N,dtype", C3_CASES)
+def test_c3_transposed_operand_small(gpu, B, H, S, D, N, dtype):
+    vt, tio, pipelines, torch = gpu
+    wl = workloads.c3_oproj_gemm(seed=1, B=B, H=H, S=S, D=D, N=N, dtype=dtype)
+    ref = run_workload(wl)["out"]
+    p = run(pipelines, tio, torch, wl)
+    check(tio.to_host_f64(p.out), ref)
+
+
+def test_identity_weight_turns_gemm_into_data_movement(gpu):
+    """W = I: C must equal the virtual A bit for bit (every product is exact)."""
+    vt, tio, pipelines, torch = gpu
+    wl = workloads.c3_oproj_gemm(seed=2, B=2, H=2, S=150, D=128, N=256, dtype="bf16")
+    wl.sources["W"] = workloads.encode(np.eye(256, dtype=np.float32), "bf16")
+    a_dense = dm_ops.run_chain(wl.chain, wl.sources)["A"]
+    p = run(pipelines, tio, torch, wl)
+    assert np.array_equal(tio.to_host_bits(p.out), a_dense)
+
+
+def test_virtual_equals_materialized_bitwise_and_f32_output(gpu):
+    vt, tio, pipelines, torch = gpu
+    wl = workloads.c3_oproj_gemm(seed=3, B=2, H=3, S=200, D=64, N=384, dtype="bf16")
+    a = run(pipelines, tio, torch, wl, materialized=False)
+    b = run(pipelines, tio, torch, wl, materialized=True)
+    assert np.array_equal(tio.to_host_bits(a.out), tio.to_host_bits(b.out))
+    # fp32 output: no final rounding, tighter agreement with the oracle
+    ref = run_workload(wl)["out"]
+    out32 = torch.empty(ref.shape, dtype=torch.float32, device="cuda:0")
+    vt.vt_gemm(a.A, a.B, [out32], "f32")
+    torch.cuda.synchronize()
+    assert np.max(np.abs(out32.cpu().numpy().astype(np.float64) - ref)) <= 2e-4 * max(1.0, np.abs(ref).max())
+
+
+@pytest.mark.parametrize("T,Hd,E,N", [(300, 256, 3, 264), (64, 64, 8, 256), (1000, 128, 8, 512)])
+def test_c5_gather_grouped_small(gpu, T, Hd, E, N):
+    vt, tio, pipelines, torch = gpu
+    wl = workloads.c5_moe_dispatch(seed=4, T=T, Hd=Hd, E=E, N=N)
+    ref = run_workload(wl)["out"]
+    p = run(pipelines, tio, torch, wl)
+    assert tuple(p.out.shape) == ref.shape
+    check(tio.to_host_f64(p.out), ref)
+    m = run(pipelines, tio, torch, wl, materialized=True)
+    assert np.array_equal(tio.to_host_bits(p.out), tio.to_host_bits(m.out))
+
+
+def test_c5_empty_and_tiny_experts(gpu):
+    """Routing that leaves one expert with a single token and another with none."""
+    vt, tio, pipelines, torch = gpu
+    wl = workloads.c5_moe_dispatch(seed=5, T=40, Hd=64, E=4, N=256)
+    wl.index_tables["idx1"] = wl.index_tables["idx1"][:1]
+    # an expert without tokens has no rows: it is simply not part of the launch
+    wl.chain = [s for s in wl.chain if s[0] not in ("A3", "w3", "B3")]
+    wl.consumer["a"], wl.consumer["b"] = ["A0", "A1", "A2"], ["B0", "B1", "B2"]
+    ref = run_workload(wl)["out"]
+    p = run(pipelines, tio, torch, wl)
+    check(tio.to_host_f64(p.out), ref)
+
+
+def test_c3_full_size_sampled_rows(gpu):
+    """Config 3 at the benchmark's size; 384 sampled rows (some from every 256-row tile band)
+    are compared with the oracle over all 4096 columns."""
+    vt, tio, pipelines, torch = gpu
+    wl = workloads.c3_oproj_gemm()
+    p = run(pipelines, tio, torch, wl)
+    a_dense = dm_ops.run_chain(wl.chain, wl.sources)["A"]
+    rng = np.random.default_rng(0)
+    rows = np.unique(np.concatenate([rng.integers(0, 8192, size=352), np.arange(0, 8192, 256)]))
+    ref = consumers.gemm(consumers.decode(a_dense[rows], "bf16"), consumers.decode(wl.sources["W"], "bf16"))
+    got = tio.to_host_f64(p.out[torch.from_numpy(rows).cuda()])
+    check(got, ref)
+    # column sums over ALL rows catch an error in any row (property that holds at any size)
+    colsum_ref = consumers.decode(a_dense, "bf16").sum(axis=0) @ consumers.decode(wl.sources["W"], "bf16")
+    colsum = tio.to_host_f64(p.out).sum(axis=0)
+    # each of the 8192 outputs of a column carries a bf16 rounding error of at most 2^-9 |c|
+    # (std 2^-9 |c| / sqrt(3)); their sum is a random walk: allow 8 standard deviations
+    bound = 8.0 * np.sqrt(8192.0) * 2.0 ** -9 / np.sqrt(3.0) * np.sqrt(np.mean(ref ** 2))
+    assert np.max(np.abs(colsum - colsum_ref)) <= bound, (np.max(np.abs(colsum - colsum_ref)), bound)
+
+
+def test_rejects_unsupported_operands(gpu):
+    vt, tio, pipelines, torch = gpu
+    wl = workloads.c3_oproj_gemm(seed=6, B=1, H=2, S=16, D=8, N=64)
+    dw = tio.DeviceWorkload(wl)
+    a = dw.build("A")
+    # B given transposed ([N,K] viewed as [K,N]): columns are not contiguous
+    bt = vt.build_chain([("Bt", "permute", ("W",), {"perm": (1, 0)})],
+                        {"W": ((64, 16), "bf16", dw.tensors["W"].data_ptr())}, "Bt")
+    out = torch.empty((16, 64), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(vt.VtError) as ei:
+        vt.vt_gemm([a], [bt], [out], "bf16")
+    assert ei.value.code == vt.ERR_UNSUPPORTED
