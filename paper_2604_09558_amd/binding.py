@@ -12,7 +12,7 @@ import os
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libvt.so")
+LIB_PATH = os.environ.get("VT_LIB_PATH", os.path.join(HERE, "libvt.so"))   # override: kernel experiments
 
 VT_MAX_DIMS = 8
 VT_MAX_OP_INPUTS = 8

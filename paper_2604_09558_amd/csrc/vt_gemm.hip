@@ -64,9 +64,8 @@ struct GemmParams {
 };
 
 // Offset contributed by index v along an axis.  Unused digits are padded on the host with
-// radix 1 / stride 0, so the walk is branch-free; the table (index_select) is only possible on
-// the row axis of A, which is evaluated once per thread before the K loop.
-template <int ND, bool TABLE>
+// radix 1 / stride 0 (in the outer slots), so the walk is branch-free.
+template <int ND>
 __device__ __forceinline__ int64_t axis_off(const AxisMap<ND>& a, uint32_t v) {
   int64_t off = 0;
 #pragma unroll
@@ -79,12 +78,34 @@ __device__ __forceinline__ int64_t axis_off(const AxisMap<ND>& a, uint32_t v) {
     } else {
       r = v;
     }
-    if (TABLE) {
-      if (d == a.tdig) r = (uint32_t)a.table[r];
-    }
     off += (int64_t)r * a.stride[d];
   }
   return off;
+}
+
+// The same with an index table on digit a.tdig (index_select): only the row axis of A can
+// carry one, and it is evaluated once per thread before the K loop.
+template <int ND>
+__device__ __forceinline__ int64_t axis_off_table(const AxisMap<ND>& a, uint32_t v) {
+  int64_t off = 0;
+  uint32_t rt = 0;
+  int64_t st = 0;
+#pragma unroll
+  for (int d = ND - 1; d >= 0; --d) {
+    uint32_t r;
+    if (d > 0) {
+      uint32_t q = fdiv(v, a.radix[d]);
+      r = v - q * a.radix[d].d;
+      v = q;
+    } else {
+      r = v;
+    }
+    const bool is_t = d == a.tdig;
+    rt = is_t ? r : rt;
+    st = is_t ? a.stride[d] : st;
+    off += is_t ? 0 : (int64_t)r * a.stride[d];
+  }
+  return off + (int64_t)a.table[rt] * st;
 }
 
 __device__ __forceinline__ uint32_t word(const uint4& v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
@@ -106,7 +127,7 @@ struct Mma<f16_t> {
   }
 };
 
-template <typename T, bool C_F32>
+template <typename T, bool C_F32, bool K_TAIL>
 __global__ void __launch_bounds__(256) k_gemm(const GemmParams P) {
   typedef Mma<T> M_;
   typedef typename M_::vec opvec;
@@ -135,58 +156,55 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P) {
   const int l32 = lane & 31, lh = lane >> 5;
   const int Mg = G.M, N = P.N, K = P.K;
 
-  // ---- stage-1 bookkeeping: A rows of this thread (fixed over the K loop)
+  // ---- stage-1 bookkeeping: A rows of this thread (fixed over the K loop); pointers include the row offset
   const int a_c = t & 7, a_r0 = t >> 3;                 // chunk (8 k) and first row; rows a_r0 + 32 i
-  int64_t a_rowoff[8];
+  uint32_t a_rowoff[8];                                 // byte offsets (the host checks that A spans < 4 GiB)
+  if (G.a_row.tdig >= 0) {
 #pragma unroll
-  for (int i = 0; i < 8; ++i) a_rowoff[i] = axis_off<5, true>(G.a_row, (uint32_t)min(tm * BM + a_r0 + 32 * i, Mg - 1));
-  // B: an 8 (k) x 8 (n) block per thread; column chunk fixed over the K loop
+    for (int i = 0; i < 8; ++i)
+      a_rowoff[i] = (uint32_t)(axis_off_table(G.a_row, (uint32_t)min(tm * BM + a_r0 + 32 * i, Mg - 1)) * 2);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      a_rowoff[i] = (uint32_t)(axis_off(G.a_row, (uint32_t)min(tm * BM + a_r0 + 32 * i, Mg - 1)) * 2);
+  }
+  // B: an 8 (k) x 8 (n) block per thread; column chunk fixed over the K loop; the 8 rows are
+  // consecutive k inside one innermost digit (its radix is a multiple of 8), stride b_kstride
   const int b_cn = t & 31, b_kb = t >> 5;
   const int b_n = tn * BN + b_cn * 8;
-  const bool b_nvalid = b_n < N;
-  const int64_t b_coloff = axis_off<3, false>(G.b_col, (uint32_t)min(b_n, N - 8));
+  const char* b_colptr = G.b + axis_off(G.b_col, (uint32_t)min(b_n, N - 8)) * 2;
+  const int64_t b_kstride = G.b_row.stride[2] * 2;
 
+  // ---- the pieces of one K step, each small enough to be placed between two MFMAs ----------
   uint4 ra[8], rb[8];
-  auto load_global = [&](int k0) {
-    const int ka = k0 + a_c * 8;
-    if (ka < K) {
-      const int64_t co = axis_off<3, false>(G.a_col, (uint32_t)ka);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) ra[i] = *reinterpret_cast<const uint4*>(G.a + (a_rowoff[i] + co) * 2);
-    } else {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) ra[i] = make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int kb = k0 + b_kb * 8 + j;
-      if (kb < K && b_nvalid) {
-        rb[j] = *reinterpret_cast<const uint4*>(G.b + (axis_off<3, false>(G.b_row, (uint32_t)kb) + b_coloff) * 2);
-      } else {
-        rb[j] = make_uint4(0, 0, 0, 0);
-      }
-    }
+  uint32_t g_aco = 0;            // column offset of this thread's A chunk for the tile being fetched
+  const char* g_bp = nullptr;    // first of this thread's 8 B rows for the tile being fetched
+  // Chunks past K (only when K is not a multiple of 64: the K_TAIL instantiation) read a
+  // clamped, valid address and are zeroed when they are written to LDS.  Columns past N need no
+  // masking: they only feed C columns that are never stored.
+  auto gload_prepare = [&](int k0) {
+    const int ka = k0 + a_c * 8, kb = k0 + b_kb * 8;
+    g_aco = (uint32_t)(axis_off(G.a_col, (uint32_t)(K_TAIL ? min(ka, K - 8) : ka)) * 2);
+    g_bp = b_colptr + axis_off(G.b_row, (uint32_t)(K_TAIL ? min(kb, K - 8) : kb)) * 2;
   };
-  auto store_lds = [&](int buf) {
-    uint4* sa = ldsA[buf];
-    uint4* sb = ldsB[buf];
+  auto gload_a = [&](int i) { ra[i] = *reinterpret_cast<const uint4*>(G.a + (a_rowoff[i] + g_aco)); };
+  auto gload_b = [&](int j) { rb[j] = *reinterpret_cast<const uint4*>(g_bp + j * b_kstride); };
+  auto store_a = [&](int buf, int i, int k0) {
+    const int r = a_r0 + 32 * i;
+    uint4 v = ra[i];
+    if (K_TAIL && k0 + a_c * 8 >= K) v = make_uint4(0, 0, 0, 0);
+    ldsA[buf][r * 8 + (a_c ^ (r & 7))] = v;
+  };
+  // column e of the thread's 8x8 block of B: gathered from the 8 row registers (v_perm_b32),
+  // its 8 k values written as one unit of B^T
+  auto store_b = [&](int buf, int e, int k0) {
+    const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+    uint32_t w[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int r = a_r0 + 32 * i;
-      sa[r * 8 + (a_c ^ (r & 7))] = ra[i];
-    }
-    // transpose the 8x8 block: output e holds column b_cn*8 + e, its 8 k values contiguous
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-      uint32_t w[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        w[u] = __builtin_amdgcn_perm(word(rb[2 * u + 1], e >> 1), word(rb[2 * u], e >> 1), sel);
-      }
-      const int n = b_cn * 8 + e;
-      sb[n * 8 + (b_kb ^ ((n ^ (n >> 3)) & 7))] = make_uint4(w[0], w[1], w[2], w[3]);
-    }
+    for (int u = 0; u < 4; ++u) w[u] = __builtin_amdgcn_perm(word(rb[2 * u + 1], e >> 1), word(rb[2 * u], e >> 1), sel);
+    if (K_TAIL && k0 + b_kb * 8 >= K) w[0] = w[1] = w[2] = w[3] = 0u;
+    const int n = b_cn * 8 + e;
+    ldsB[buf][n * 8 + (b_kb ^ ((n ^ (n >> 3)) & 7))] = make_uint4(w[0], w[1], w[2], w[3]);
   };
 
   f32x16 acc[4][4];
@@ -197,37 +215,111 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  const int nk = (K + BK - 1) / BK;
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
-  for (int it = 0; it < nk; ++it) {
-    const int cur = it & 1;
-    if (it + 1 < nk) load_global((it + 1) * BK);
-    const uint4* sa = ldsA[cur];
-    const uint4* sb = ldsB[cur];
+  // fragment addresses (16-byte units) for k-chunk 0; chunk c is reached by XOR with c
+  int a_unit[4], b_unit[4], a_key[4], b_key[4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      opvec af[4], bf[4];
-      const int chunk = ks * 2 + lh;
-#pragma unroll
-      for (int mb = 0; mb < 4; ++mb) {
-        const int r = wm * 128 + mb * 32 + l32;
-        af[mb] = __builtin_bit_cast(opvec, sa[r * 8 + (chunk ^ (r & 7))]);
-      }
-#pragma unroll
-      for (int nb = 0; nb < 4; ++nb) {
-        const int n = wn * 128 + nb * 32 + l32;
-        bf[nb] = __builtin_bit_cast(opvec, sb[n * 8 + (chunk ^ ((n ^ (n >> 3)) & 7))]);
-      }
-#pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb) acc[mb][nb] = M_::run(af[mb], bf[nb], acc[mb][nb]);
-    }
-    if (it + 1 < nk) store_lds(cur ^ 1);
-    __syncthreads();
+  for (int mb = 0; mb < 4; ++mb) {
+    const int r = wm * 128 + mb * 32 + l32;
+    a_unit[mb] = r * 8;
+    a_key[mb] = r & 7;
   }
+#pragma unroll
+  for (int nb = 0; nb < 4; ++nb) {
+    const int n = wn * 128 + nb * 32 + l32;
+    b_unit[nb] = n * 8;
+    b_key[nb] = (n ^ (n >> 3)) & 7;
+  }
+  opvec af[2][4], bf[2][4];
+  // fragment f of k16 step ks (f = 0: A0, 1..4: B0..B3, 5..7: A1..A3: the order the MFMAs need them)
+  auto read_frag = [&](int buf, int ks, int p, int f) {
+    const int chunk = ks * 2 + lh;
+    if (f == 0 || f >= 5) {
+      const int mb = f == 0 ? 0 : f - 4;
+      af[p][mb] = __builtin_bit_cast(opvec, ldsA[buf][a_unit[mb] + (chunk ^ a_key[mb])]);
+    } else {
+      const int nb = f - 1;
+      bf[p][nb] = __builtin_bit_cast(opvec, ldsB[buf][b_unit[nb] + (chunk ^ b_key[nb])]);
+    }
+  };
+  auto mma = [&](int p, int m) { acc[m >> 2][m & 3] = M_::run(af[p][m >> 2], bf[p][m & 3], acc[m >> 2][m & 3]); };
+#define VT_SB() __builtin_amdgcn_sched_barrier(0)
+
+  // ---- one K step (64 MFMAs per wave).  Source order IS the issue order: each group between
+  // two scheduling barriers holds two MFMAs and a little memory work that issues in the shadow
+  // of the matrix pipe.  Global loads run two K steps ahead, LDS stores of the next tile sit
+  // under k16 steps 1 and 2, fragments are read one k16 step ahead, and the only barrier comes
+  // before k16 step 3 so that the next tile's first fragments are in flight under its MFMAs.
+  auto k_step = [&](int it, auto do_store, auto do_load) {
+    const int cur = it & 1, nxt = cur ^ 1;
+    const int k_next = (it + 1) * BK;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {            // k16 step 0 | read fragments of step 1
+      mma(0, 2 * i);
+      read_frag(cur, 1, 1, i);
+      mma(0, 2 * i + 1);
+      VT_SB();
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {            // k16 step 1 | fragments of step 2, A tile of the next K step -> LDS
+      mma(1, 2 * i);
+      read_frag(cur, 2, 0, i);
+      mma(1, 2 * i + 1);
+      if (do_store.value) store_a(nxt, i, k_next);
+      VT_SB();
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {            // k16 step 2 | fragments of step 3, B tile transposed -> LDS
+      mma(0, 2 * i);
+      read_frag(cur, 3, 1, i);
+      mma(0, 2 * i + 1);
+      if (do_store.value) store_b(nxt, i, k_next);
+      VT_SB();
+    }
+    __syncthreads();
+    VT_SB();
+    if (do_load.value) gload_prepare((it + 2) * BK);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {            // k16 step 3 | first fragments of the next tile, global loads two steps ahead
+      mma(1, 2 * i);
+      if (do_store.value) read_frag(nxt, 0, 0, i);
+      if (do_load.value) gload_a(i);
+      mma(1, 2 * i + 1);
+      if (do_load.value) gload_b(i);
+      VT_SB();
+    }
+  };
+
+  const int nk = (K + BK - 1) / BK;
+  gload_prepare(0);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    gload_a(i);
+    gload_b(i);
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    store_a(0, i, 0);
+    store_b(0, i, 0);
+  }
+  if (nk > 1) {
+    gload_prepare(BK);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      gload_a(i);
+      gload_b(i);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int f = 0; f < 8; ++f) read_frag(0, 0, 0, f);
+  int it = 0;
+  for (; it + 2 < nk; ++it) k_step(it, std::true_type{}, std::true_type{});
+  if (it + 1 < nk) {
+    k_step(it, std::true_type{}, std::false_type{});
+    ++it;
+  }
+  k_step(it, std::false_type{}, std::false_type{});
+#undef VT_SB
 
   // ---- stage 3: plain contiguous store of the tile (lanes 0..31 write 32 consecutive columns)
   typedef typename std::conditional<C_F32, float, T>::type CT;
@@ -324,6 +416,17 @@ int plan_a(const vt_desc& d, GemmGroup* g, int64_t* M, int64_t* K) {
   const vt_source& src = d.sources[p.src];
   if (!src.ptr) return fail(VT_ERR_INVALID_ARG, "vt_gemm: A source without a device pointer");
   g->a = static_cast<const char*>(src.ptr) + p.v.base * 2;
+  {
+    int64_t span = 0;
+    for (int i = 0; i < 5; ++i) span += (int64_t)(g->a_row.radix[i].d - 1) * g->a_row.stride[i];
+    for (int i = 0; i < 3; ++i) span += (int64_t)(g->a_col.radix[i].d - 1) * g->a_col.stride[i];
+    if (g->a_row.table) {
+      // a table digit can reach any row of the source dim it indexes: bound by the source size
+      span = 1;
+      for (int i = 0; i < src.ndim; ++i) span *= src.shape[i];
+    }
+    if (span * 2 >= (1ll << 32)) return fail(VT_ERR_UNSUPPORTED, "vt_gemm: A spans 4 GiB or more");
+  }
   const AxisMap<3>& c = g->a_col;
   bool ok = *K % 8 == 0 && (uintptr_t)g->a % 16 == 0 && strides_multiple_of(g->a_row, 8, 0);
   ok = ok && c.nd >= 1 && c.stride[2] == 1 && c.radix[2].d % 8 == 0 && strides_multiple_of(c, 8, 1);
@@ -346,7 +449,8 @@ int plan_b(const vt_desc& d, GemmGroup* g, int64_t* K, int64_t* N) {
   if (!src.ptr) return fail(VT_ERR_INVALID_ARG, "vt_gemm: B source without a device pointer");
   g->b = static_cast<const char*>(src.ptr) + p.v.base * 2;
   const AxisMap<3>& c = g->b_col;
-  bool ok = *N % 8 == 0 && (uintptr_t)g->b % 16 == 0 && strides_multiple_of(g->b_row, 8, 0) && c.nd >= 1 &&
+  bool ok = *N % 8 == 0 && *K % 8 == 0 && g->b_row.radix[2].d % 8 == 0 && (uintptr_t)g->b % 16 == 0 &&
+            strides_multiple_of(g->b_row, 8, 0) && c.nd >= 1 &&
             c.stride[2] == 1 && c.radix[2].d % 8 == 0 && strides_multiple_of(c, 8, 1);
   if (!ok) return fail(VT_ERR_UNSUPPORTED, "vt_gemm: B needs runs of 8 contiguous, 16-byte aligned elements along N");
   return VT_OK;
@@ -401,13 +505,16 @@ extern "C" int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* c
     P.chunk = (tiles + 7) / 8;
     P.c_f32 = c_dtype == VT_F32;
     dim3 grid(P.chunk * 8);
+    const bool kt = K % BK != 0;
+#define VT_GEMM_LAUNCH(TT, CF, KT) hipLaunchKernelGGL((k_gemm<TT, CF, KT>), grid, dim3(256), 0, st, P)
     if (dt == VT_BF16) {
-      if (P.c_f32) hipLaunchKernelGGL((k_gemm<bf16_t, true>), grid, dim3(256), 0, st, P);
-      else hipLaunchKernelGGL((k_gemm<bf16_t, false>), grid, dim3(256), 0, st, P);
+      if (P.c_f32) { if (kt) VT_GEMM_LAUNCH(bf16_t, true, true); else VT_GEMM_LAUNCH(bf16_t, true, false); }
+      else { if (kt) VT_GEMM_LAUNCH(bf16_t, false, true); else VT_GEMM_LAUNCH(bf16_t, false, false); }
     } else {
-      if (P.c_f32) hipLaunchKernelGGL((k_gemm<f16_t, true>), grid, dim3(256), 0, st, P);
-      else hipLaunchKernelGGL((k_gemm<f16_t, false>), grid, dim3(256), 0, st, P);
+      if (P.c_f32) { if (kt) VT_GEMM_LAUNCH(f16_t, true, true); else VT_GEMM_LAUNCH(f16_t, true, false); }
+      else { if (kt) VT_GEMM_LAUNCH(f16_t, false, true); else VT_GEMM_LAUNCH(f16_t, false, false); }
     }
+#undef VT_GEMM_LAUNCH
     int rc = check_launch("vt_gemm");
     if (rc != VT_OK) return rc;
   }
