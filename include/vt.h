@@ -141,7 +141,9 @@ int vt_elementwise(int kind, const vt_desc* x, const vt_desc* y, float eps, void
  * accumulation, C[g] dense [M_g, N] row-major device pointers of dtype c_dtype (same as the
  * operands, or VT_F32).  One launch covers all groups.
  * prologue = VT_GEMM_LAYERNORM applies per-row LayerNorm (gamma 1, beta 0, eps) over K to A,
- * rounded to the operand dtype, before the product; it needs K <= 256.
+ * rounded to the operand dtype, before the product, inside the load stage (the normalised
+ * tensor is never stored).  The fused kernel takes K = 64 or 128, N <= 384, contiguous rows of
+ * A; other shapes return VT_ERR_UNSUPPORTED (run vt_elementwise(LAYERNORM) + vt_gemm instead).
  * A, B, C are host arrays of n_groups pointers. */
 typedef enum { VT_GEMM_PLAIN = 0, VT_GEMM_LAYERNORM = 1 } vt_gemm_prologue;
 int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* const* C, int n_groups,

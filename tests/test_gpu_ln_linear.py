@@ -1,0 +1,91 @@
+"""GPU parity of the window-partition -> LayerNorm -> linear chain (fp16; LayerNorm fused into the
+GEMM's load stage, and the unfused LayerNorm kernel + GEMM) against the CPU oracle.
+Tolerance |gpu - oracle| <= 1e-2 + 1e-2 |oracle| (the benchmark states none for fp16: the bf16
+bar is used; observed errors are ~1e-3, see the asserts on the maximum)."""
+import numpy as np
+import pytest
+
+import workloads
+from oracle.run import run_workload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2604_09558_amd as vt
+    from paper_2604_09558_amd import pipelines, torch_io
+    vt.lib()
+    return vt, torch_io, pipelines, torch
+
+
+def check(got, ref, atol=1e-2, rtol=1e-2):
+    err = np.abs(got - ref)
+    bad = err > atol + rtol * np.abs(ref)
+    assert not bad.any(), "max abs err %.3e at %s" % (err.max(), np.unravel_index(err.argmax(), err.shape))
+    return err.max()
+
+
+CASES = [
+    # B, R, win, C, N, dtype
+    (2, 14, 7, 128, 384, "f16"),       # 8 windows of 49 tokens: 392 rows (6 blocks + a ragged one)
+    (1, 6, 3, 128, 264, "f16"),        # N not a multiple of 128: masked columns
+    (3, 8, 4, 64, 128, "f16"),         # K = 64, one column block per wave
+    (2, 14, 7, 128, 384, "bf16"),
+    (1, 21, 7, 64, 200, "bf16"),
+]
+
+
+@pytest.mark.parametrize("B,R,win,C,N,dtype", CASES)
+def test_c4_fused_small(gpu, B, R, win, C, N, dtype):
+    vt, tio, pipelines, torch = gpu
+    wl = workloads.c4_window_ln_linear(seed=1, B=B, R=R, win=win, C=C, N=N, dtype=dtype)
+    ref = run_workload(wl)["out"]
+    p = pipelines.Gemm(tio.DeviceWorkload(wl), fused=True)
+    p.run()
+    torch.cuda.synchronize()
+    got = tio.to_host_f64(p.out).reshape(ref.shape)
+    check(got, ref)
+
+
+def test_c4_unfused_and_materialized_agree(gpu):
+    vt, tio, pipelines, torch = gpu
+    wl = workloads.c4_window_ln_linear(seed=2, B=2, R=14, win=7, C=128, N=384)
+    ref = run_workload(wl)["out"]
+    dw = tio.DeviceWorkload(wl)
+    outs = {}
+    for name, kw in (("fused", dict(fused=True)), ("unfused", dict(fused=False)),
+                     ("mat_fused", dict(fused=True, materialized=True))):
+        p = pipelines.Gemm(dw, **kw)
+        p.run()
+        torch.cuda.synchronize()
+        outs[name] = tio.to_host_f64(p.out).reshape(ref.shape)
+        check(outs[name], ref)
+    # same kernel on dense copies of the intermediates: identical bits
+    assert np.array_equal(outs["fused"], outs["mat_fused"])
+
+
+def test_c4_full_size(gpu):
+    """Config 4 at the benchmark's size: every output compared."""
+    vt, tio, pipelines, torch = gpu
+    wl = workloads.c4_window_ln_linear()
+    ref = run_workload(wl)["out"]
+    p = pipelines.Gemm(tio.DeviceWorkload(wl), fused=True)
+    p.run()
+    torch.cuda.synchronize()
+    got = tio.to_host_f64(p.out).reshape(ref.shape)
+    mx = check(got, ref)
+    assert mx <= 4e-3, mx      # outputs ~N(0, 0.23): fp16 rounding of LN (2^-11 rel) and of the result
+
+
+def test_constant_rows_give_zero(gpu):
+    """LayerNorm of a constant row is zero, so the product is zero (no NaN from 0 * rsqrt(eps))."""
+    vt, tio, pipelines, torch = gpu
+    wl = workloads.c4_window_ln_linear(seed=3, B=1, R=6, win=3, C=128, N=128)
+    wl.sources["X"][:] = np.float16(3.25)
+    p = pipelines.Gemm(tio.DeviceWorkload(wl), fused=True)
+    p.run()
+    torch.cuda.synchronize()
+    assert np.all(tio.to_host_f64(p.out) == 0.0)
