@@ -117,6 +117,46 @@ def cpu_baseline_c2(wl, alg_bytes):
             "sample": "one full pass of config 2 (B=8, context 4096): %.2f s wall" % dt, "seconds": dt}
 
 
+def chain_stats(torch, name, steps):
+    """Virtual and materialized (every operator an explicit copy kernel) timings of one of the
+    other benchmark chains; inputs rotate over enough copies to defeat the Infinity Cache where
+    the working set is small."""
+    import workloads
+    from paper_2604_09558_amd import pipelines
+    from paper_2604_09558_amd import torch_io as tio
+    copies = {"c1": 1, "c3": 3, "c4": 6, "c5": 1}[name]
+    wls = [workloads.CONFIGS[name](seed=s) for s in range(copies)]
+    dws = [tio.DeviceWorkload(w) for w in wls]
+    virt = [pipelines.make_pipeline(dw) for dw in dws]
+    torch.cuda.synchronize()
+    mk = lambda p: (lambda stream: p.run(stream))      # noqa: E731
+    n = steps
+    v_wall, v_ev = time_steps(torch, [mk(p) for p in virt], n, max(2, n // 10), False)
+    out = {"virtual_us": round(v_ev * 1e3, 2)}
+    p0 = virt[0]
+    if name in ("c3", "c5", "c4"):
+        rows, N, K = sum(p0.rows), p0.N, p0.A[0].shape[-1]
+        flops = 2.0 * rows * N * K
+        out["tflops"] = round(flops / (v_ev * 1e-3) / 1e12, 1)
+        out["mfma_pct_of_peak"] = round(100.0 * flops / (v_ev * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 1)
+        esz = 2
+        a_bytes = rows * K * esz if name != "c5" else dws[0].tensors["tokens"].numel() * esz
+        alg = a_bytes + len(p0.B) * K * N * esz + rows * N * esz
+        out["algorithmic_bytes"] = int(alg)
+        out["hbm_pct_of_peak"] = round(100.0 * alg / (v_ev * 1e-3) / 1e9 / HBM_PEAK_GBS, 1)
+    mat = pipelines.make_pipeline(dws[0], materialized=True)
+    torch.cuda.synchronize()
+    m_wall, m_ev = time_steps(torch, [mk(mat)], max(3, n // 4), 2, False)
+    out["materialized_full_us"] = round(m_ev * 1e3, 2)
+    out["speedup_vs_materialized_full"] = round(m_ev / v_ev, 3)
+    out["intermediate_bytes_saved"] = int(mat.mat.bytes_written)
+    if name == "c4":
+        unf = pipelines.Gemm(dws[0], fused=False)
+        u_wall, u_ev = time_steps(torch, [mk(unf)], n, 2, False)
+        out["virtual_unfused_us"] = round(u_ev * 1e3, 2)
+    return out
+
+
 def main():
     a = parse()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -185,6 +225,14 @@ def main():
         out["intermediate_bytes_saved"] = mat.mat.bytes_written
         del mat
         torch.cuda.empty_cache()
+
+    if a.extra:
+        del virt, dws
+        torch.cuda.empty_cache()
+        out["chains"] = {}
+        for name in a.extra.split(","):
+            out["chains"][name] = chain_stats(torch, name, {"c1": 200, "c3": 30, "c4": 100, "c5": 6}[name])
+            torch.cuda.empty_cache()
 
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline_c2(wls[0], alg)

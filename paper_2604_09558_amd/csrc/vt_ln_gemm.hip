@@ -10,7 +10,10 @@
 // row_offset(m) (mixed-radix digits / index table, evaluated per row); the same lanes reduce
 // mean and variance with xor-shuffles, normalise in fp32, round to the operand type and write
 // the row into an XOR-swizzled LDS tile; the rows of the next block are in flight while the
-// current block is multiplied (v_mfma_f32_32x32x16).  Stage 3 is a plain store of C.
+// current block is multiplied (v_mfma_f32_32x32x16).  The product is formed transposed (W^T as the
+// first operand), so a lane ends up with 4 consecutive output columns; stage 3 packs them,
+// bounces the wave's 64 x N/4 sub-tile through LDS and leaves with 16-byte stores that cover
+// whole row segments (the output is three quarters of all traffic).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -24,6 +27,21 @@ using namespace vt::gemm;
 
 namespace {
 
+// Sum over the LPR (8 or 16) consecutive lanes that share a row, on the VALU's data-parallel
+// primitives (mirror within 16 / 8 lanes, then the two quad permutes): every lane gets the total.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+template <int LPR>
+__device__ __forceinline__ float group_sum(float v) {
+  if (LPR == 16) v += dpp_move<0x140>(v);   // row_mirror: lane i <-> 15 - i
+  v += dpp_move<0x141>(v);                  // row_half_mirror: i <-> 7 - i
+  v += dpp_move<0xB1>(v);                   // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);                   // quad_perm [2,3,0,1]
+  return v;
+}
+
 constexpr int LBM = 64;           // rows per block
 constexpr int LMB = LBM / 32;     // 32-row MFMA blocks per block
 
@@ -35,7 +53,7 @@ struct LnGemmParams {
   AxisMap<3> b_row, b_col;
   int32_t M, N, K, n_blocks;
   float eps;
-  int32_t pad;
+  int32_t w_rows_of_8;   // W has runs of 8 contiguous, 16-byte aligned elements along N: coalesced prologue
 };
 
 // LPR = lanes per row = K / 8; NB = 32-column blocks per wave
@@ -47,20 +65,61 @@ __global__ void __launch_bounds__(256) k_ln_gemm(const LnGemmParams P) {
   constexpr int KS = K / 16;                 // k16 steps
   constexpr int RPP = 256 / LPR;             // rows staged per pass of the workgroup
   constexpr int PASSES = LBM / RPP;
-  __shared__ uint4 ldsA[2][LBM * LPR];       // [row][LPR chunks of 8 k], chunk c of row r at r*LPR + (c ^ (r & (LPR-1) & 7))
+  constexpr int CW = NB * 32;                // output columns per wave
+  constexpr int CPITCH = CW * 2 + 16;        // bytes per staged row (16-byte aligned, de-phased banks)
+  constexpr int kABytes = 2 * LBM * LPR * 16, kCBytes = 4 * LBM * CPITCH, kWBytes = 4 * CW * K * 2;
+  constexpr int kLdsBytes = kABytes + kCBytes > kWBytes ? kABytes + kCBytes : kWBytes;
+  __shared__ __attribute__((aligned(16))) char lds_raw[kLdsBytes];
+  // steady state: two A tiles [row][LPR chunks of 8 k] (chunk c of row r at r*LPR + (c ^ (r & 7))) and
+  // one staging area per wave for its C sub-tile; during the prologue the same memory holds W^T
+  uint4 (*ldsA)[LBM * LPR] = reinterpret_cast<uint4 (*)[LBM * LPR]>(lds_raw);
+  char (*ldsC)[LBM * CPITCH] = reinterpret_cast<char (*)[LBM * CPITCH]>(lds_raw + kABytes);
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int l32 = lane & 31, lh = lane >> 5;
   const int M = P.M, N = P.N;
 
-  // ---- this wave's slice of W, as MFMA B operands: lane holds column n = col0 + nb*32 + l32 and
-  // the 8 consecutive k of its half; read once through the map
+  // ---- this wave's slice of W as MFMA operands (lane: column n = wave*CW + nb*32 + l32, the 8
+  // consecutive k of its half), kept in registers for the whole kernel
   opvec wf[KS][NB];
-  {
+  if (P.w_rows_of_8) {
+    // coalesced: 8x8 blocks of W are loaded row-wise (16 bytes per lane), transposed in registers
+    // and parked in LDS as W^T [n][k]; every wave then picks its operands with ds_read_b128
+    uint4* ldsW = reinterpret_cast<uint4*>(lds_raw);   // unit (n, kc) at n*LPR + (kc ^ ((n ^ (n >> 3)) & 7))
+    const int nblk = (N / 8) * LPR;                    // 8x8 blocks: N/8 across, K/8 down
+    for (int bidx = t; bidx < nblk; bidx += 256) {
+      const int kb = bidx / (N / 8), cn = bidx - kb * (N / 8);
+      const char* bp = P.b + axis_off(P.b_col, (uint32_t)(cn * 8)) * 2;
+      uint4 rb[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) rb[j] = *reinterpret_cast<const uint4*>(bp + axis_off(P.b_row, (uint32_t)(kb * 8 + j)) * 2);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+        uint32_t w[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) w[u] = __builtin_amdgcn_perm(word(rb[2 * u + 1], e >> 1), word(rb[2 * u], e >> 1), sel);
+        const int n = cn * 8 + e;
+        ldsW[n * LPR + (kb ^ ((n ^ (n >> 3)) & 7))] = make_uint4(w[0], w[1], w[2], w[3]);
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int n = wave * CW + nb * 32 + l32;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (n < N) v = ldsW[n * LPR + ((ks * 2 + lh) ^ ((n ^ (n >> 3)) & 7))];
+        wf[ks][nb] = __builtin_bit_cast(opvec, v);
+      }
+    }
+    __syncthreads();                                   // W^T is no longer needed: the memory becomes tiles
+  } else {
     const T* bp = reinterpret_cast<const T*>(P.b);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      const int n = wave * (NB * 32) + nb * 32 + l32;
+      const int n = wave * CW + nb * 32 + l32;
       const int64_t co = axis_off(P.b_col, (uint32_t)min(n, N - 1));
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
@@ -72,29 +131,34 @@ __global__ void __launch_bounds__(256) k_ln_gemm(const LnGemmParams P) {
     }
   }
 
+  // ---- stage 1 bookkeeping.  LPR lanes share a row; the 16 rows a wave stages per block are
+  // evaluated through the map by 16 lanes (one row each) and handed to the lanes that load them.
   const int a_c = t % LPR, a_r0 = t / LPR;             // chunk and first row; rows a_r0 + RPP * i
-  uint4 ra[PASSES];
-  auto load_rows = [&](int blk) {
+  uint4 ra[2][PASSES];                                  // rows of the next two blocks (prefetch distance 2)
+  constexpr int RW = 64 / LPR;                          // rows per wave and pass
+  const int my_i = (lane & 15) / RW, my_g = (lane & 15) % RW;   // the row this lane evaluates: pass my_i, group my_g
+  auto load_rows = [&](int blk, int slot) {
+    const int m = min(blk * LBM + wave * RW + my_g + RPP * my_i, M - 1);
+    const int64_t ro = P.a_row.tdig >= 0 ? axis_off_table(P.a_row, (uint32_t)m) : axis_off(P.a_row, (uint32_t)m);
+    const uint32_t ro32 = (uint32_t)(ro * 2);           // byte offset (the host checks that A spans < 4 GiB)
 #pragma unroll
     for (int i = 0; i < PASSES; ++i) {
-      const int m = min(blk * LBM + a_r0 + RPP * i, M - 1);
-      const int64_t ro = P.a_row.tdig >= 0 ? axis_off_table(P.a_row, (uint32_t)m) : axis_off(P.a_row, (uint32_t)m);
-      ra[i] = *reinterpret_cast<const uint4*>(P.a + (ro + a_c * 8) * 2);
+      const uint32_t o = (uint32_t)__shfl((int)ro32, i * RW + lane / LPR, 64);
+      ra[slot][i] = *reinterpret_cast<const uint4*>(P.a + (o + a_c * 16));
     }
   };
   // LayerNorm of the rows held in ra (each row spread over LPR consecutive lanes), then -> LDS
-  auto norm_store = [&](int buf) {
+  auto norm_store = [&](int buf) {   // rows come from register slot `buf`, go to LDS tile `buf`
 #pragma unroll
     for (int i = 0; i < PASSES; ++i) {
       float x[8];
       {
-        const Vec<T, 8> v = __builtin_bit_cast(Vec<T, 8>, ra[i]);
+        const Vec<T, 8> v = __builtin_bit_cast(Vec<T, 8>, ra[buf][i]);
 #pragma unroll
         for (int j = 0; j < 8; ++j) x[j] = to_float(v.v[j]);
       }
       float s = ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]));
-#pragma unroll
-      for (int d = 1; d < LPR; d <<= 1) s += __shfl_xor(s, d, 64);
+      s = group_sum<LPR>(s);
       const float mean = s * (1.0f / K);
       float q = 0.f;
 #pragma unroll
@@ -102,8 +166,7 @@ __global__ void __launch_bounds__(256) k_ln_gemm(const LnGemmParams P) {
         x[j] -= mean;
         q += x[j] * x[j];
       }
-#pragma unroll
-      for (int d = 1; d < LPR; d <<= 1) q += __shfl_xor(q, d, 64);
+      q = group_sum<LPR>(q);
       const float rstd = 1.0f / sqrtf(q * (1.0f / K) + P.eps);
       Vec<T, 8> o;
 #pragma unroll
@@ -113,18 +176,17 @@ __global__ void __launch_bounds__(256) k_ln_gemm(const LnGemmParams P) {
     }
   };
 
-  typedef typename std::conditional<C_F32, float, T>::type CT;
-  CT* cbase = reinterpret_cast<CT*>(P.c);
-
   int blk = blockIdx.x;
   if (blk >= P.n_blocks) return;
-  load_rows(blk);
+  const int stride = gridDim.x;
+  load_rows(blk, 0);
+  if (blk + stride < P.n_blocks) load_rows(blk + stride, 1);
   norm_store(0);
-  int buf = 0;
-  for (; blk < P.n_blocks; blk += gridDim.x, buf ^= 1) {
-    const int nxt = blk + gridDim.x;
+  auto step = [&](int blk, auto parity) {
+    constexpr int buf = decltype(parity)::value;
+    const int nxt = blk + stride;
     __syncthreads();                                  // tile `buf` is complete; tile buf^1 is free again
-    if (nxt < P.n_blocks) load_rows(nxt);             // in flight during the MFMAs below
+    if (nxt + stride < P.n_blocks) load_rows(nxt + stride, buf);   // two blocks ahead: lands while this and the next block are multiplied
     f32x16 acc[LMB][NB];
 #pragma unroll
     for (int mb = 0; mb < LMB; ++mb)
@@ -144,25 +206,57 @@ __global__ void __launch_bounds__(256) k_ln_gemm(const LnGemmParams P) {
 #pragma unroll
       for (int mb = 0; mb < LMB; ++mb)
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = M_::run(af[mb], wf[ks][nb], acc[mb][nb]);
+        for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = M_::run(wf[ks][nb], af[mb], acc[mb][nb]);   // C^T block: rows = n, cols = m
     }
-    // ---- stage 3
+    // ---- stage 3: lane holds row m = mb*32 + l32 and columns nb*32 + lh*4 + 8j + (0..3)
+    if (C_F32) {
 #pragma unroll
-    for (int mb = 0; mb < LMB; ++mb)
+      for (int mb = 0; mb < LMB; ++mb)
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        const int col = wave * (NB * 32) + nb * 32 + l32;
-        const int row0 = blk * LBM + mb * 32 + lh * 4;
-        if (col < N) {
-          CT* cp = cbase + (size_t)row0 * N + col;
+        for (int nb = 0; nb < NB; ++nb) {
+          const int row = blk * LBM + mb * 32 + l32;
 #pragma unroll
-          for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-              if (row0 + 8 * j + i < M) cp[(size_t)(8 * j + i) * N] = from_float<CT>(acc[mb][nb][4 * j + i]);
+          for (int j = 0; j < 4; ++j) {
+            const int col = wave * CW + nb * 32 + lh * 4 + 8 * j;
+            if (row < M && col < N) {       // N is a multiple of 8, so the 4 columns are valid together
+              float4 v = make_float4(acc[mb][nb][4 * j], acc[mb][nb][4 * j + 1], acc[mb][nb][4 * j + 2], acc[mb][nb][4 * j + 3]);
+              *reinterpret_cast<float4*>(reinterpret_cast<float*>(P.c) + (size_t)row * N + col) = v;
+            }
+          }
         }
+    } else {
+      char* sc = ldsC[wave];
+#pragma unroll
+      for (int mb = 0; mb < LMB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            Vec<T, 4> o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o.v[i] = from_float<T>(acc[mb][nb][4 * j + i]);
+            *reinterpret_cast<Vec<T, 4>*>(sc + (mb * 32 + l32) * CPITCH + (nb * 32 + lh * 4 + 8 * j) * 2) = o;
+          }
+      // wave-local: the same wave reads back what it wrote (LDS operations of a wave stay in order)
+      constexpr int CH = CW / 8;             // 16-byte chunks per staged row
+#pragma unroll
+      for (int q = 0; q < LBM * CH / 64; ++q) {
+        const int id = q * 64 + lane;
+        const int r = id / CH, ch = id - r * CH;
+        const int row = blk * LBM + r, col = wave * CW + ch * 8;
+        const uint4 v = *reinterpret_cast<const uint4*>(sc + r * CPITCH + ch * 16);
+        if (row < M && col < N) *reinterpret_cast<uint4*>(reinterpret_cast<T*>(P.c) + (size_t)row * N + col) = v;
       }
+    }
     if (nxt < P.n_blocks) norm_store(buf ^ 1);
+  };
+  for (;;) {
+    step(blk, std::integral_constant<int, 0>{});
+    blk += stride;
+    if (blk >= P.n_blocks) break;
+    step(blk, std::integral_constant<int, 1>{});
+    blk += stride;
+    if (blk >= P.n_blocks) break;
   }
 }
 
@@ -224,6 +318,18 @@ int ln_gemm_launch(const vt_desc& A, const vt_desc& B, void* C, int c_dtype, flo
   P.b = static_cast<const char*>(sb.ptr) + pb.v.base * 2;
   if ((uintptr_t)P.a % 16 || !strides_multiple_of(P.a_row, 8, 0))
     return fail(VT_ERR_UNSUPPORTED, "vt_gemm(layernorm): rows of A must be 16-byte aligned");
+  if ((uintptr_t)C % 16) return fail(VT_ERR_INVALID_ARG, "vt_gemm(layernorm): C must be 16-byte aligned");
+  {
+    int64_t span = 0;
+    for (int i = 0; i < 5; ++i) span += (int64_t)(P.a_row.radix[i].d - 1) * P.a_row.stride[i];
+    if (P.a_row.table) {
+      span = 1;
+      for (int i = 0; i < sa.ndim; ++i) span *= sa.shape[i];
+    }
+    if ((span + K) * 2 >= (1ll << 32)) return fail(VT_ERR_UNSUPPORTED, "vt_gemm(layernorm): A spans 4 GiB or more");
+  }
+  P.w_rows_of_8 = (uintptr_t)P.b % 16 == 0 && P.b_col.stride[2] == 1 && P.b_col.radix[2].d % 8 == 0 &&
+                  strides_multiple_of(P.b_col, 8, 1) && strides_multiple_of(P.b_row, 8, 0);
   P.c = static_cast<char*>(C);
   P.M = (int32_t)M;
   P.N = (int32_t)N;
