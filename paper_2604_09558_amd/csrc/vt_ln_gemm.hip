@@ -1,19 +1,19 @@
 // LayerNorm fused into the load stage of a skinny GEMM: C = LN(A) . W with A virtual [.., K],
 // K = 64 or 128, W virtual [K, N], N <= 384 (the window-partition -> LayerNorm -> linear chain).
 // The whole path is bound by HBM (the output is 3x the input), so the design goal is to touch
-// every byte once: the normalised tokens never exist in global memory, and W never leaves
-// registers.
+// every byte once and to keep enough waves resident to hide latency: the normalised tokens never
+// exist in global memory, and W never leaves registers.
 //
-// A persistent workgroup of 4 waves walks over blocks of 64 rows.  Each wave owns N/4 output
-// columns and keeps its slice of W in registers for the whole kernel (K/16 x NB MFMA operands).
-// Stage 1 through the map: 16 (K=128) or 8 (K=64) lanes fetch one row with 16-byte loads at
-// row_offset(m) (mixed-radix digits / index table, evaluated per row); the same lanes reduce
-// mean and variance with xor-shuffles, normalise in fp32, round to the operand type and write
-// the row into an XOR-swizzled LDS tile; the rows of the next block are in flight while the
-// current block is multiplied (v_mfma_f32_32x32x16).  The product is formed transposed (W^T as the
-// first operand), so a lane ends up with 4 consecutive output columns; stage 3 packs them,
-// bounces the wave's 64 x N/4 sub-tile through LDS and leaves with 16-byte stores that cover
-// whole row segments (the output is three quarters of all traffic).
+// A persistent workgroup of 8 waves (two per SIMD) walks over blocks of 64 rows.  Each wave owns
+// N/8 output columns (up to 48) and keeps its slice of W in registers for the whole kernel as
+// v_mfma_f32_16x16x32 operands.  Stage 1 through the map: 16 (K=128) or 8 (K=64) lanes fetch one
+// row with 16-byte loads at row_offset(m) (mixed-radix digits / index table; one lane evaluates a
+// row and hands the offset to the lanes that load it); the same lanes reduce mean and variance
+// with DPP row operations, normalise in fp32, round to the operand type and write the row into
+// an XOR-swizzled LDS tile; rows of the next two blocks are in flight while the current block is
+// multiplied.  The product is formed transposed (W^T as the first operand), so a lane ends up
+// with 4 consecutive output columns; stage 3 packs them, bounces the wave's 64 x N/8 sub-tile
+// through LDS and leaves with 16-byte stores (the output is three quarters of all traffic).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -26,6 +26,25 @@ using namespace vt;
 using namespace vt::gemm;
 
 namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <typename T>
+struct Mma16;
+template <>
+struct Mma16<bf16_t> {
+  typedef bf16x8 vec;
+  static __device__ __forceinline__ f32x4 run(vec a, vec b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+  }
+};
+template <>
+struct Mma16<f16_t> {
+  typedef f16x8 vec;
+  static __device__ __forceinline__ f32x4 run(vec a, vec b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+  }
+};
 
 // Sum over the LPR (8 or 16) consecutive lanes that share a row, on the VALU's data-parallel
 // primitives (mirror within 16 / 8 lanes, then the two quad permutes): every lane gets the total.
@@ -42,8 +61,11 @@ __device__ __forceinline__ float group_sum(float v) {
   return v;
 }
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 constexpr int LBM = 64;           // rows per block
-constexpr int LMB = LBM / 32;     // 32-row MFMA blocks per block
+constexpr int LWAVES = 8;
+constexpr int LTHREADS = LWAVES * 64;
 
 struct LnGemmParams {
   const char* a;
@@ -51,66 +73,151 @@ struct LnGemmParams {
   char* c;
   AxisMap<5> a_row;
   AxisMap<3> b_row, b_col;
-  int32_t M, N, K, n_blocks;
+  int32_t M, N, K;
+  int32_t n_full;        // rounds of full blocks: in round i workgroup w takes block i * gridDim.x + w
+  int32_t tail_rows;     // then rows [tail0 + w * tail_rows, + tail_rows) of what is left, tail0 = n_full * gridDim.x * LBM
   float eps;
   int32_t w_rows_of_8;   // W has runs of 8 contiguous, 16-byte aligned elements along N: coalesced prologue
+  int32_t w_k_runs_of_8; // rows 8i .. 8i+7 of W are equally spaced (innermost K digit has a radix that 8 divides)
 };
 
-// LPR = lanes per row = K / 8; NB = 32-column blocks per wave
+// LPR = lanes per row = K / 8; NB = 16-column blocks per wave
 template <typename T, bool C_F32, int LPR, int NB>
-__global__ void __launch_bounds__(256) k_ln_gemm(const LnGemmParams P) {
-  typedef Mma<T> M_;
+__global__ void __launch_bounds__(LTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+k_ln_gemm(const LnGemmParams P) {
+  typedef Mma16<T> M_;
   typedef typename M_::vec opvec;
   constexpr int K = LPR * 8;
-  constexpr int KS = K / 16;                 // k16 steps
-  constexpr int RPP = 256 / LPR;             // rows staged per pass of the workgroup
+  constexpr int KS = K / 32;                 // k32 steps
+  constexpr int RPP = LTHREADS / LPR;        // rows staged per pass of the workgroup
   constexpr int PASSES = LBM / RPP;
-  constexpr int CW = NB * 32;                // output columns per wave
+  constexpr int CW = NB * 16;                // output columns per wave
   constexpr int CPITCH = CW * 2 + 16;        // bytes per staged row (16-byte aligned, de-phased banks)
-  constexpr int kABytes = 2 * LBM * LPR * 16, kCBytes = 4 * LBM * CPITCH, kWBytes = 4 * CW * K * 2;
+  constexpr int kABytes = 2 * LBM * LPR * 16, kCBytes = LWAVES * LBM * CPITCH, kWBytes = LWAVES * CW * K * 2;
   constexpr int kLdsBytes = kABytes + kCBytes > kWBytes ? kABytes + kCBytes : kWBytes;
   __shared__ __attribute__((aligned(16))) char lds_raw[kLdsBytes];
   // steady state: two A tiles [row][LPR chunks of 8 k] (chunk c of row r at r*LPR + (c ^ (r & 7))) and
   // one staging area per wave for its C sub-tile; during the prologue the same memory holds W^T
+  // Rows of A travel global -> LDS without touching registers (three blocks deep).  Each lane later
+  // reads back exactly the 16 bytes its own request delivered, so the memory needs no barrier; it
+  // is an object of its own, touched only by those requests and by the read below, so that no
+  // other LDS access is ordered against a request still in flight.
+  __shared__ __attribute__((aligned(16))) uint4 lds_rows[3][LBM * LPR];
   uint4 (*ldsA)[LBM * LPR] = reinterpret_cast<uint4 (*)[LBM * LPR]>(lds_raw);
   char (*ldsC)[LBM * CPITCH] = reinterpret_cast<char (*)[LBM * CPITCH]>(lds_raw + kABytes);
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int l32 = lane & 31, lh = lane >> 5;
+  const int l16 = lane & 15, lg = lane >> 4;
   const int M = P.M, N = P.N;
 
-  // ---- this wave's slice of W as MFMA operands (lane: column n = wave*CW + nb*32 + l32, the 8
-  // consecutive k of its half), kept in registers for the whole kernel
+  // ---- stage 1 bookkeeping.  LPR lanes share a row.  A wave stages 8 rows of every block; their
+  // offsets are evaluated through the map for 8 blocks at a time (lane: block lane/8 of the batch,
+  // row lane%8) and handed to the lanes that load them.
+  const int a_c = t % LPR, a_r0 = t / LPR;             // chunk and first row; rows a_r0 + RPP * i
+  constexpr int RW = 64 / LPR;                          // rows per wave and pass
+  static_assert(RW * PASSES == 8, "a wave stages 8 rows per block");
+  // This workgroup's blocks.  Rounds of full blocks are interleaved over the workgroups, so that at
+  // any moment the chip reads and writes one compact window of memory (contiguous ranges per
+  // workgroup, 256 separate streams, measured 10% slower); the rows left after the last full round
+  // are dealt out in shares of tail_rows.
+  const int n_full = P.n_full, wg = blockIdx.x;
+  const int64_t tail0 = (int64_t)n_full * gridDim.x * LBM + (int64_t)wg * P.tail_rows;
+  const int n_it = n_full + (tail0 < M ? 1 : 0);
+  if (n_it == 0) return;
+  auto block_rows = [&](int i, int64_t* first, int64_t* end) {   // rows [first, end) of this workgroup's block i
+    if (i < n_full) {
+      *first = ((int64_t)i * gridDim.x + wg) * LBM;
+      *end = *first + LBM;
+    } else {
+      *first = tail0;
+      *end = min((int64_t)M, tail0 + P.tail_rows);
+    }
+  };
+  const int ev_row = wave * RW + (lane & 7) % RW + RPP * ((lane & 7) / RW);
+  uint32_t ro32 = 0;                                    // byte offset of this lane's row (the host checks that A spans < 4 GiB)
+  auto eval_rows = [&](int it0) {                       // blocks it0 .. it0+7 of this workgroup
+    int64_t first, end;
+    block_rows(min(it0 + (lane >> 3), n_it - 1), &first, &end);   // past the last block: it again, not used
+    const int m = (int)min(first + ev_row, end - 1);
+    const int64_t ro = P.a_row.tdig >= 0 ? axis_off_table(P.a_row, (uint32_t)m) : axis_off(P.a_row, (uint32_t)m);
+    ro32 = (uint32_t)(ro * 2);
+  };
+  typedef __attribute__((address_space(3))) void* lptr_t;
+  auto load_rows = [&](int j, int slot) {               // block j of the evaluated batch -> lds_rows[slot]
+#pragma unroll
+    for (int i = 0; i < PASSES; ++i) {
+      const uint32_t o = (uint32_t)__shfl((int)ro32, j * 8 + i * RW + lane / LPR, 64);
+      // lane l of the wave lands at (wave base) + 16 l: rows wave*RW + RPP*i .. + RW, unswizzled
+      // Written as assembly so that the request stays unknown to the compiler, which would
+      // otherwise order every later LDS access of the kernel behind it; the waits for these
+      // requests are the explicit ones below.
+      const uint32_t dst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lptr_t)&lds_rows[slot][(wave * RW + RPP * i) * LPR]);
+      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                   :: "v"(o + a_c * 16), "s"(P.a), "s"(dst) : "memory", "m0");
+    }
+  };
+  // the first two blocks' rows are requested before anything else: their latency hides behind the W prologue
+  eval_rows(0);
+  load_rows(0, 0);
+  load_rows(1, 1);
+
+  // ---- this wave's slice of W as MFMA operands (lane: column n = wave*CW + nb*16 + l16, the 8
+  // consecutive k of its quarter), kept in registers for the whole kernel
   opvec wf[KS][NB];
   if (P.w_rows_of_8) {
     // coalesced: 8x8 blocks of W are loaded row-wise (16 bytes per lane), transposed in registers
     // and parked in LDS as W^T [n][k]; every wave then picks its operands with ds_read_b128
     uint4* ldsW = reinterpret_cast<uint4*>(lds_raw);   // unit (n, kc) at n*LPR + (kc ^ ((n ^ (n >> 3)) & 7))
-    const int nblk = (N / 8) * LPR;                    // 8x8 blocks: N/8 across, K/8 down
-    for (int bidx = t; bidx < nblk; bidx += 256) {
-      const int kb = bidx / (N / 8), cn = bidx - kb * (N / 8);
-      const char* bp = P.b + axis_off(P.b_col, (uint32_t)(cn * 8)) * 2;
-      uint4 rb[8];
+    const int nblk = (N / 8) * LPR;                    // 8x8 blocks: N/8 across, K/8 down; at most 2 per thread
+    static_assert(48 * LPR <= 2 * LTHREADS, "two rounds cover W");
+    uint4 rb[2][8];
+    // Every workgroup reads all of W at the same moment; each starts at a different block so
+    // that they do not all queue on the same L2 channel.
+    const int rot = (int)((blockIdx.x * 61u) % (uint32_t)nblk);
+    int kbs[2], cns[2];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) rb[j] = *reinterpret_cast<const uint4*>(bp + axis_off(P.b_row, (uint32_t)(kb * 8 + j)) * 2);
+    for (int r = 0; r < 2; ++r) {                      // all loads of both rounds are in flight together
+      const int idx = t + r * LTHREADS;
+      if (idx < nblk) {
+        int bidx = idx + rot;
+        bidx = bidx >= nblk ? bidx - nblk : bidx;
+        const int kb = bidx / (N / 8), cn = bidx - kb * (N / 8);
+        kbs[r] = kb, cns[r] = cn;
+        const char* bp = P.b + axis_off(P.b_col, (uint32_t)(cn * 8)) * 2;
+        if (P.w_k_runs_of_8) {                         // the 8 rows of a block are one stride apart
+          bp += axis_off(P.b_row, (uint32_t)(kb * 8)) * 2;
+          const int64_t rs = P.b_row.stride[2] * 2;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-        uint32_t w[4];
+          for (int j = 0; j < 8; ++j) rb[r][j] = *reinterpret_cast<const uint4*>(bp + j * rs);
+        } else {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) w[u] = __builtin_amdgcn_perm(word(rb[2 * u + 1], e >> 1), word(rb[2 * u], e >> 1), sel);
-        const int n = cn * 8 + e;
-        ldsW[n * LPR + (kb ^ ((n ^ (n >> 3)) & 7))] = make_uint4(w[0], w[1], w[2], w[3]);
+          for (int j = 0; j < 8; ++j) rb[r][j] = *reinterpret_cast<const uint4*>(bp + axis_off(P.b_row, (uint32_t)(kb * 8 + j)) * 2);
+        }
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      if (t + r * LTHREADS < nblk) {
+        const int kb = kbs[r], cn = cns[r];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+          uint32_t w[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) w[u] = __builtin_amdgcn_perm(word(rb[r][2 * u + 1], e >> 1), word(rb[r][2 * u], e >> 1), sel);
+          const int n = cn * 8 + e;
+          ldsW[n * LPR + (kb ^ ((n ^ (n >> 3)) & 7))] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
       }
     }
     __syncthreads();
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      const int n = wave * CW + nb * 32 + l32;
+      const int n = wave * CW + nb * 16 + l16;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         uint4 v = make_uint4(0, 0, 0, 0);
-        if (n < N) v = ldsW[n * LPR + ((ks * 2 + lh) ^ ((n ^ (n >> 3)) & 7))];
+        if (n < N) v = ldsW[n * LPR + ((ks * 4 + lg) ^ ((n ^ (n >> 3)) & 7))];
         wf[ks][nb] = __builtin_bit_cast(opvec, v);
       }
     }
@@ -119,41 +226,42 @@ __global__ void __launch_bounds__(256) k_ln_gemm(const LnGemmParams P) {
     const T* bp = reinterpret_cast<const T*>(P.b);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      const int n = wave * CW + nb * 32 + l32;
+      const int n = wave * CW + nb * 16 + l16;
       const int64_t co = axis_off(P.b_col, (uint32_t)min(n, N - 1));
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         Vec<T, 8> e;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) e.v[j] = bp[axis_off(P.b_row, (uint32_t)(ks * 16 + lh * 8 + j)) + co];
+        for (int j = 0; j < 8; ++j) e.v[j] = bp[axis_off(P.b_row, (uint32_t)(ks * 32 + lg * 8 + j)) + co];
         wf[ks][nb] = __builtin_bit_cast(opvec, e);
       }
     }
   }
 
-  // ---- stage 1 bookkeeping.  LPR lanes share a row; the 16 rows a wave stages per block are
-  // evaluated through the map by 16 lanes (one row each) and handed to the lanes that load them.
-  const int a_c = t % LPR, a_r0 = t / LPR;             // chunk and first row; rows a_r0 + RPP * i
-  uint4 ra[2][PASSES];                                  // rows of the next two blocks (prefetch distance 2)
-  constexpr int RW = 64 / LPR;                          // rows per wave and pass
-  const int my_i = (lane & 15) / RW, my_g = (lane & 15) % RW;   // the row this lane evaluates: pass my_i, group my_g
-  auto load_rows = [&](int blk, int slot) {
-    const int m = min(blk * LBM + wave * RW + my_g + RPP * my_i, M - 1);
-    const int64_t ro = P.a_row.tdig >= 0 ? axis_off_table(P.a_row, (uint32_t)m) : axis_off(P.a_row, (uint32_t)m);
-    const uint32_t ro32 = (uint32_t)(ro * 2);           // byte offset (the host checks that A spans < 4 GiB)
-#pragma unroll
-    for (int i = 0; i < PASSES; ++i) {
-      const uint32_t o = (uint32_t)__shfl((int)ro32, i * RW + lane / LPR, 64);
-      ra[slot][i] = *reinterpret_cast<const uint4*>(P.a + (o + a_c * 16));
+  // Memory operations a step issues after its row requests; together with the next step's requests
+  // they are what may still be in flight when the rows requested one step earlier are needed
+  // (vector memory operations complete in the order they were issued).
+  constexpr int kStores = C_F32 ? (LBM / 16) * NB : LBM * (CW / 8) / 64;
+  constexpr int kInFlight = 2 * kStores + PASSES;
+  constexpr int kWaitRows = (kInFlight & 15) | ((kInFlight >> 4) << 14) | 0x0F70;   // s_waitcnt vmcnt(kInFlight)
+  static_assert(kInFlight < 64, "vmcnt has 6 bits");
+  // LayerNorm of the rows parked in lds_rows[slot] (each row spread over LPR consecutive lanes),
+  // then -> LDS tile `buf`
+  auto norm_store = [&](int buf, int slot) {
+    u32x4 raw[PASSES];
+    {
+      const uint32_t addr = (uint32_t)(uintptr_t)(lptr_t)&lds_rows[slot][wave * RW * LPR + lane];
+      if constexpr (PASSES == 1)
+        asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(raw[0]) : "v"(addr) : "memory");
+      else
+        asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:%3\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&v"(raw[0]), "=&v"(raw[PASSES - 1]) : "v"(addr), "i"(RPP * LPR * 16) : "memory");
     }
-  };
-  // LayerNorm of the rows held in ra (each row spread over LPR consecutive lanes), then -> LDS
-  auto norm_store = [&](int buf) {   // rows come from register slot `buf`, go to LDS tile `buf`
 #pragma unroll
     for (int i = 0; i < PASSES; ++i) {
       float x[8];
       {
-        const Vec<T, 8> v = __builtin_bit_cast(Vec<T, 8>, ra[buf][i]);
+        const Vec<T, 8> v = __builtin_bit_cast(Vec<T, 8>, raw[i]);
 #pragma unroll
         for (int j = 0; j < 8; ++j) x[j] = to_float(v.v[j]);
       }
@@ -167,97 +275,105 @@ __global__ void __launch_bounds__(256) k_ln_gemm(const LnGemmParams P) {
         q += x[j] * x[j];
       }
       q = group_sum<LPR>(q);
-      const float rstd = 1.0f / sqrtf(q * (1.0f / K) + P.eps);
+      const float rstd = __builtin_amdgcn_rsqf(q * (1.0f / K) + P.eps);
       Vec<T, 8> o;
 #pragma unroll
       for (int j = 0; j < 8; ++j) o.v[j] = from_float<T>(x[j] * rstd);
       const int r = a_r0 + RPP * i;
-      ldsA[buf][r * LPR + (a_c ^ (r & 7 & (LPR - 1)))] = __builtin_bit_cast(uint4, o);
+      ldsA[buf][r * LPR + (a_c ^ (r & 7))] = __builtin_bit_cast(uint4, o);
     }
   };
+  static_assert(PASSES <= 2, "the read-back above handles one or two passes");
 
-  int blk = blockIdx.x;
-  if (blk >= P.n_blocks) return;
-  const int stride = gridDim.x;
-  load_rows(blk, 0);
-  if (blk + stride < P.n_blocks) load_rows(blk + stride, 1);
-  norm_store(0);
-  auto step = [&](int blk, auto parity) {
+  int it = 0;
+  int slot_req = 2;                                   // where the next request lands: block it+2 -> slot (it+2) % 3
+  __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): the first two blocks' rows are in LDS
+  norm_store(0, 0);
+  auto step = [&](auto parity) {
     constexpr int buf = decltype(parity)::value;
-    const int nxt = blk + stride;
+    int64_t row0, r_end;
+    block_rows(it, &row0, &r_end);
     __syncthreads();                                  // tile `buf` is complete; tile buf^1 is free again
-    if (nxt + stride < P.n_blocks) load_rows(nxt + stride, buf);   // two blocks ahead: lands while this and the next block are multiplied
-    f32x16 acc[LMB][NB];
-#pragma unroll
-    for (int mb = 0; mb < LMB; ++mb)
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[mb][nb][e] = 0.f;
+    {
+      // request the rows two blocks ahead, unconditionally (past the end of the range they are not
+      // used): the explicit wait below counts on the same number of operations in every step
+      const int j = (it + 2) & 7;
+      if (j == 0) eval_rows(it + 2);
+      load_rows(j, slot_req);
+    }
+    f32x4 acc[LBM / 16][NB];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      opvec af[LMB];
-      const int chunk = ks * 2 + lh;
+      opvec af[LBM / 16];
+      const int chunk = ks * 4 + lg;
 #pragma unroll
-      for (int mb = 0; mb < LMB; ++mb) {
-        const int r = mb * 32 + l32;
-        af[mb] = __builtin_bit_cast(opvec, ldsA[buf][r * LPR + (chunk ^ (r & 7 & (LPR - 1)))]);
+      for (int mb = 0; mb < LBM / 16; ++mb) {
+        const int r = mb * 16 + l16;
+        af[mb] = __builtin_bit_cast(opvec, ldsA[buf][r * LPR + (chunk ^ (r & 7))]);
       }
 #pragma unroll
-      for (int mb = 0; mb < LMB; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = M_::run(wf[ks][nb], af[mb], acc[mb][nb]);   // C^T block: rows = n, cols = m
-    }
-    // ---- stage 3: lane holds row m = mb*32 + l32 and columns nb*32 + lh*4 + 8j + (0..3)
-    if (C_F32) {
-#pragma unroll
-      for (int mb = 0; mb < LMB; ++mb)
+      for (int mb = 0; mb < LBM / 16; ++mb)
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-          const int row = blk * LBM + mb * 32 + l32;
+          const f32x4 c0 = ks == 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : acc[mb][nb];
+          acc[mb][nb] = M_::run(wf[ks][nb], af[mb], c0);   // C^T block: rows = n, cols = m
+        }
+    }
+    // ---- stage 3: lane holds row m = mb*16 + l16 and columns nb*16 + lg*4 + (0..3).
+    // C is written through a buffer descriptor that starts at this block's first row and ends with
+    // the block: rows past it fall outside and the hardware drops them; lanes whose
+    // columns are past N get an offset outside it.  No store is conditional: every step issues the
+    // same number of memory operations, which the explicit wait for the rows relies on.
+    constexpr int kEs = C_F32 ? 4 : 2;
+    const uint64_t c_skip = (uint64_t)row0 * (uint64_t)N * kEs;
+    const uint64_t c_left = (uint64_t)(r_end - row0) * (uint64_t)N * kEs;
+    const __amdgpu_buffer_rsrc_t c_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        P.c + c_skip, 0, (int)min(c_left, (uint64_t)0x7fffffffu), 0x00020000);
+    if (C_F32) {
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int col = wave * CW + nb * 32 + lh * 4 + 8 * j;
-            if (row < M && col < N) {       // N is a multiple of 8, so the 4 columns are valid together
-              float4 v = make_float4(acc[mb][nb][4 * j], acc[mb][nb][4 * j + 1], acc[mb][nb][4 * j + 2], acc[mb][nb][4 * j + 3]);
-              *reinterpret_cast<float4*>(reinterpret_cast<float*>(P.c) + (size_t)row * N + col) = v;
-            }
-          }
+      for (int mb = 0; mb < LBM / 16; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          const int col = wave * CW + nb * 16 + lg * 4;   // N is a multiple of 8, so the 4 columns are valid together
+          const uint32_t off = col < N ? (uint32_t)((mb * 16 + l16) * N + col) * 4u : 0x80000000u;
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[mb][nb]), c_rsrc, (int)off, 0, 0);
         }
     } else {
       char* sc = ldsC[wave];
 #pragma unroll
-      for (int mb = 0; mb < LMB; ++mb)
+      for (int mb = 0; mb < LBM / 16; ++mb)
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
+        for (int nb = 0; nb < NB; ++nb) {
+          Vec<T, 4> o;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            Vec<T, 4> o;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) o.v[i] = from_float<T>(acc[mb][nb][4 * j + i]);
-            *reinterpret_cast<Vec<T, 4>*>(sc + (mb * 32 + l32) * CPITCH + (nb * 32 + lh * 4 + 8 * j) * 2) = o;
-          }
+          for (int i = 0; i < 4; ++i) o.v[i] = from_float<T>(acc[mb][nb][i]);
+          *reinterpret_cast<Vec<T, 4>*>(sc + (mb * 16 + l16) * CPITCH + (nb * 16 + lg * 4) * 2) = o;
+        }
       // wave-local: the same wave reads back what it wrote (LDS operations of a wave stay in order)
       constexpr int CH = CW / 8;             // 16-byte chunks per staged row
 #pragma unroll
       for (int q = 0; q < LBM * CH / 64; ++q) {
         const int id = q * 64 + lane;
         const int r = id / CH, ch = id - r * CH;
-        const int row = blk * LBM + r, col = wave * CW + ch * 8;
-        const uint4 v = *reinterpret_cast<const uint4*>(sc + r * CPITCH + ch * 16);
-        if (row < M && col < N) *reinterpret_cast<uint4*>(reinterpret_cast<T*>(P.c) + (size_t)row * N + col) = v;
+        const int col = wave * CW + ch * 8;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(sc + r * CPITCH + ch * 16);
+        const uint32_t off = col < N ? (uint32_t)(r * N + col) * 2u : 0x80000000u;
+        __builtin_amdgcn_raw_buffer_store_b128(v, c_rsrc, (int)off, 0, 0);
       }
     }
-    if (nxt < P.n_blocks) norm_store(buf ^ 1);
+    if (it + 1 < n_it) {
+      __builtin_amdgcn_s_waitcnt(kWaitRows);          // the rows requested one step ago have landed
+      norm_store(buf ^ 1, slot_req == 0 ? 2 : slot_req - 1);
+    }
+    slot_req = slot_req == 2 ? 0 : slot_req + 1;
   };
   for (;;) {
-    step(blk, std::integral_constant<int, 0>{});
-    blk += stride;
-    if (blk >= P.n_blocks) break;
-    step(blk, std::integral_constant<int, 1>{});
-    blk += stride;
-    if (blk >= P.n_blocks) break;
+    step(std::integral_constant<int, 0>{});
+    if (++it >= n_it) break;
+    step(std::integral_constant<int, 1>{});
+    if (++it >= n_it) break;
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70);                 // requests past the last block still target this workgroup's LDS
 }
 
 template <typename T, bool C_F32>
@@ -267,10 +383,17 @@ int launch_t(const LnGemmParams& P, int lpr, int nb, hipStream_t st) {
     if (hipGetDevice(&dev) == hipSuccess) hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
     return n > 0 ? n : 256;
   }();
-  dim3 grid((unsigned)std::min(P.n_blocks, n_cu));     // persistent: one workgroup per compute unit
+  // One workgroup per compute unit: full rounds of blocks, then one more block for as many
+  // workgroups as the rest needs.  (Dealing the rest out in 16-row shares to all workgroups was
+  // measured and is slower: every workgroup then pays the fixed cost of one more step.)
+  LnGemmParams Q = P;
+  Q.n_full = P.M / (n_cu * LBM);
+  const int rest = P.M - Q.n_full * n_cu * LBM;
+  Q.tail_rows = LBM;
+  dim3 grid((unsigned)(Q.n_full > 0 ? n_cu : (rest + Q.tail_rows - 1) / Q.tail_rows));
 #define VT_LN_CASE(L, B)                                                                     \
   if (lpr == L && nb == B) {                                                                 \
-    hipLaunchKernelGGL((k_ln_gemm<T, C_F32, L, B>), grid, dim3(256), 0, st, P);              \
+    hipLaunchKernelGGL((k_ln_gemm<T, C_F32, L, B>), grid, dim3(LTHREADS), 0, st, Q);              \
     return check_launch("vt_gemm(layernorm)");                                               \
   }
   VT_LN_CASE(16, 1) VT_LN_CASE(16, 2) VT_LN_CASE(16, 3) VT_LN_CASE(8, 1) VT_LN_CASE(8, 2) VT_LN_CASE(8, 3)
@@ -330,14 +453,15 @@ int ln_gemm_launch(const vt_desc& A, const vt_desc& B, void* C, int c_dtype, flo
   }
   P.w_rows_of_8 = (uintptr_t)P.b % 16 == 0 && P.b_col.stride[2] == 1 && P.b_col.radix[2].d % 8 == 0 &&
                   strides_multiple_of(P.b_col, 8, 1) && strides_multiple_of(P.b_row, 8, 0);
+  P.w_k_runs_of_8 = P.b_row.radix[2].d % 8 == 0;
   P.c = static_cast<char*>(C);
   P.M = (int32_t)M;
   P.N = (int32_t)N;
   P.K = (int32_t)K;
-  P.n_blocks = (int32_t)((M + LBM - 1) / LBM);
   P.eps = eps;
+  if (M == 0) return VT_OK;                            // nothing to compute
   const int lpr = (int)(K / 8);
-  const int nb = (int)((N + 127) / 128);
+  const int nb = (int)((N + 127) / 128);               // 16-column blocks per wave: 8 waves x nb x 16 >= N
   const bool c32 = c_dtype == VT_F32;
   if (dt == VT_BF16) return c32 ? launch_t<bf16_t, true>(P, lpr, nb, st) : launch_t<bf16_t, false>(P, lpr, nb, st);
   return c32 ? launch_t<f16_t, true>(P, lpr, nb, st) : launch_t<f16_t, false>(P, lpr, nb, st);
