@@ -105,6 +105,17 @@ int vt_free(vt_desc* d);
  * minimum over pieces).  Any output pointer may be NULL.  shape must hold VT_MAX_DIMS. */
 int vt_desc_info(const vt_desc* d, int* ndim, int64_t* shape, int* dtype,
                  int64_t* contiguous_run, int* n_pieces);
+/* Profitability class of reading through the descriptor instead of a dense copy (Sec. 4.3,
+ * Def. 5 and Theorem 1).  FULL: the whole virtual tensor is one contiguous range of one source,
+ * i.e. the map is the original access pattern plus a constant bias: always profitable (Type I),
+ * no measurement needed.  PARTIAL: not FULL, but every run of consecutive elements is at least
+ * unit_bytes long (the minimal memory transfer unit; 0 selects 128 bytes, one cache line of the
+ * target): likely profitable.  SCATTERED: some run is shorter; profitability is uncertain
+ * (Type II) and is decided by timing both paths.  min_run_bytes (may be NULL) receives the
+ * shortest run in bytes.  Host only. */
+typedef enum { VT_ACCESS_FULL = 0, VT_ACCESS_PARTIAL = 1, VT_ACCESS_SCATTERED = 2 } vt_access_class;
+int vt_classify(const vt_desc* d, int64_t unit_bytes, int* access_class, int64_t* min_run_bytes);
+
 /* Piece p: its box [lo,hi) in virtual index space, its source number and its own run. */
 int vt_desc_piece(const vt_desc* d, int p, int64_t* lo, int64_t* hi, int* src_id, int64_t* run);
 /* CPU evaluation of the map at one virtual index (host logic; used by tests).  vindex holds

@@ -24,6 +24,7 @@ OP_KINDS = {"reshape": 0, "permute": 1, "slice": 2, "split": 3, "concat": 4, "ex
             "unsqueeze": 6, "index_select": 7}
 EW_ADD_ROWSUM, EW_LAYERNORM = 0, 1
 GEMM_PLAIN, GEMM_LAYERNORM = 0, 1
+ACCESS_FULL, ACCESS_PARTIAL, ACCESS_SCATTERED = 0, 1, 2
 
 
 class VtSource(C.Structure):
@@ -61,6 +62,7 @@ def lib():
                                    C.POINTER(C.c_int64), C.POINTER(C.c_int)]
         L.vt_desc_piece.argtypes = [P, C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int),
                                     C.POINTER(C.c_int64)]
+        L.vt_classify.argtypes = [P, C.c_int64, C.POINTER(C.c_int), C.POINTER(C.c_int64)]
         L.vt_eval_host.argtypes = [P, C.POINTER(C.c_int64), C.POINTER(C.c_int), C.POINTER(C.c_int64)]
         L.vt_eval_device_form.argtypes = [P, C.POINTER(C.c_int64), C.POINTER(C.c_int), C.POINTER(C.c_int64)]
         L.vt_desc_dump.argtypes = [P, C.c_char_p, C.c_size_t]
@@ -160,6 +162,12 @@ class Desc:
     @property
     def shape(self):
         return self.info()["shape"]
+
+    def classify(self, unit_bytes=0):
+        """(class, shortest run in bytes); class is ACCESS_FULL / ACCESS_PARTIAL / ACCESS_SCATTERED."""
+        cls, run = C.c_int(), C.c_int64()
+        _check(lib().vt_classify(self.handle, unit_bytes, C.byref(cls), C.byref(run)))
+        return cls.value, run.value
 
     def piece(self, p):
         lo, hi = (C.c_int64 * VT_MAX_DIMS)(), (C.c_int64 * VT_MAX_DIMS)()

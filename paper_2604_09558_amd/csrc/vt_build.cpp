@@ -687,6 +687,22 @@ int vt_desc_info(const vt_desc* d, int* ndim, int64_t* shape, int* dtype, int64_
   return VT_OK;
 }
 
+int vt_classify(const vt_desc* d, int64_t unit_bytes, int* access_class, int64_t* min_run_bytes) {
+  if (!d || !access_class) return fail(VT_ERR_INVALID_ARG, "vt_classify: NULL argument");
+  if (unit_bytes < 0) return fail(VT_ERR_INVALID_ARG, "vt_classify: negative unit");
+  if (unit_bytes == 0) unit_bytes = 128;
+  const int64_t esz = d->dtype == VT_F32 ? 4 : 2;
+  int64_t numel = 1;
+  for (int64_t e : d->shape) numel *= e;
+  const int64_t run_bytes = d->run * esz;
+  if (min_run_bytes) *min_run_bytes = run_bytes;
+  // one piece whose run spans the whole tensor: minimal contiguous dimension 1 (Def. 5)
+  if (d->pieces.size() == 1 && d->run >= numel) *access_class = VT_ACCESS_FULL;
+  else if (run_bytes >= unit_bytes) *access_class = VT_ACCESS_PARTIAL;
+  else *access_class = VT_ACCESS_SCATTERED;
+  return VT_OK;
+}
+
 int vt_desc_piece(const vt_desc* d, int p, int64_t* lo, int64_t* hi, int* src_id, int64_t* run) {
   if (!d || p < 0 || p >= (int)d->pieces.size()) return fail(VT_ERR_INVALID_ARG, "vt_desc_piece: no such piece");
   const Piece& pc = d->pieces[p];

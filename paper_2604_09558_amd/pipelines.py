@@ -188,3 +188,51 @@ def make_pipeline(dw: DeviceWorkload, materialized=False, **kw):
     if kind == "decode_attn":
         return DecodeAttention(dw, materialized, **kw)
     return Gemm(dw, materialized, **kw)
+
+
+# ------------------------------------------------------------------------------------------
+# Profitability (Sec. 4.3) and the measured latency saving w(e) (Sec. 5.2) of one chain
+# ------------------------------------------------------------------------------------------
+def consumer_operands(p):
+    """Descriptors the consumer of pipeline `p` reads."""
+    if isinstance(p, AddRowsum):
+        return [p.x, p.y]
+    if isinstance(p, DecodeAttention):
+        return [p.q, p.k, p.v]
+    return list(p.A) + list(p.B)
+
+
+def time_pipeline(p, iters=20, warmup=3):
+    """Mean microseconds per run of the launches `p.run()` makes, by HIP events on the current stream."""
+    for _ in range(warmup):
+        p.run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        p.run()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / iters
+
+
+def choose_path(dw: DeviceWorkload, iters=20, warmup=3, unit_bytes=0, **kw):
+    """Decide between reading the chain through descriptors and executing it as copies.
+
+    The class of the chain is the worst class among the consumer's operands.  A fully contiguous
+    chain is always profitable (Theorem 1) and is taken without measuring.  Any other chain is
+    measured both ways, as the greedy search does for every candidate edge: the saving
+    w = t(materialized) - t(virtual) decides, and a non-positive saving keeps the copies.
+    Returns the chosen pipeline (ready to run) and a report."""
+    virt = make_pipeline(dw, materialized=False, **kw)
+    classes = [d.classify(unit_bytes) for d in consumer_operands(virt)]
+    cls = max(c for c, _ in classes)
+    report = {"class": ("full", "partial", "scattered")[cls], "min_run_bytes": min(r for _, r in classes)}
+    if cls == vt.ACCESS_FULL:
+        report.update(choice="virtual", measured=False)
+        return virt, report
+    mat = make_pipeline(dw, materialized=True, **kw)
+    tv, tm = time_pipeline(virt, iters, warmup), time_pipeline(mat, iters, warmup)
+    report.update(virtual_us=tv, materialized_us=tm, saving_us=tm - tv, measured=True,
+                  choice="virtual" if tm - tv > 0 else "materialized")
+    return (virt if tm - tv > 0 else mat), report

@@ -223,6 +223,69 @@ def test_paper_contiguity_cases():
     assert ds.eval_host((2, 3))[1] == 2 * 8 + 3 * 2 and ds.info()["run"] == 1
 
 
+def test_profitability_classes_of_the_papers_cases():
+    """Sec. 4.3/4.4: split along axis 0, a reshape and a whole-range slice keep the original
+    access pattern up to a constant bias (Type I); split along another axis, expand, permute and
+    concat do not, and whether they keep partial contiguity depends on the run against the
+    minimal transfer unit."""
+    src = {"X": ((6, 64), "f32")}
+    full = [
+        [("a", "split", ("X",), {"dim": 0, "sizes": (2, 4), "output": 1})],
+        [("a", "reshape", ("X",), {"shape": (3, 2, 8, 8)})],
+        [("a", "slice", ("X",), {"dim": 0, "start": 2, "stop": 5})],
+    ]
+    for chain in full:
+        cls, run = vt.build_chain(chain, src, "a").classify()
+        assert cls == vt.ACCESS_FULL, chain
+    # split along axis 1: runs of 24 floats = 96 bytes: partial for a 64-byte unit, scattered for 128
+    d = vt.build_chain([("a", "split", ("X",), {"dim": 1, "sizes": (40, 24), "output": 1})], src, "a")
+    assert d.classify(64) == (vt.ACCESS_PARTIAL, 96)
+    assert d.classify(128) == (vt.ACCESS_SCATTERED, 96)
+    assert d.classify() == (vt.ACCESS_SCATTERED, 96)         # default unit: 128 bytes
+    # transposed matrix: single elements
+    assert vt.build_chain([("t", "permute", ("X",), {"perm": (1, 0)})], src, "t").classify() == (vt.ACCESS_SCATTERED, 4)
+    # expand is never Type I (Sec. 4.4), even though every replica is one long run
+    chain = [("u", "unsqueeze", ("X",), {"dim": 0}), ("e", "expand", ("u",), {"shape": (4, 6, 64)})]
+    assert vt.build_chain(chain, src, "e").classify() == (vt.ACCESS_PARTIAL, 6 * 64 * 4)
+    # a tensor stitched from separately stored parts (the input of a split seen as a virtual
+    # tensor of its outputs) is not Type I either
+    two = {"A": ((2, 64), "f32"), "B": ((4, 64), "f32")}
+    d = vt.build_chain([("c", "concat", ("A", "B"), {"dim": 0})], two, "c")
+    assert d.classify() == (vt.ACCESS_PARTIAL, 2 * 64 * 4)
+    assert vt.lib().vt_classify(None, 0, None, None) == vt.ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_full_class_means_identity_plus_bias(seed):
+    """Theorem 1's premise checked by brute force: FULL iff walking the virtual tensor in
+    row-major order walks one source in consecutive offsets."""
+    wl = workloads.random_chain(seed, n_ops=3)
+    try:
+        d = vt.build_chain(wl.chain, specs_of(wl), "R", wl.index_tables)
+    except vt.VtError:
+        pytest.skip("outside the descriptor's reach")
+    shape = d.info()["shape"]
+    walk = [d.eval_host(x) for x in itertools.product(*[range(n) for n in shape])]
+    identity = all(s == walk[0][0] and o == walk[0][1] + i for i, (s, o) in enumerate(walk))
+    cls, run = d.classify()
+    if ",T" in d.dump() and identity:
+        return                                              # an index table that happens to be consecutive
+    assert (cls == vt.ACCESS_FULL) == identity, (d.dump(), cls)
+
+
+def test_benchmark_chains_classes():
+    c1 = workloads.c1_tiny_chain()
+    assert vt.build_chain(c1.chain, specs_of(c1), c1.consumer["x"]).classify()[0] == vt.ACCESS_SCATTERED
+    c2 = workloads.c2_decode_attention()
+    for name in ("K", "V"):
+        cls, run = vt.build_chain(c2.chain, specs_of(c2), c2.consumer[name.lower()]).classify()
+        assert (cls, run) == (vt.ACCESS_PARTIAL, 256)       # the new token's row in the fused QKV buffer
+    c3 = workloads.c3_oproj_gemm()
+    assert vt.build_chain(c3.chain, specs_of(c3), "A").classify() == (vt.ACCESS_PARTIAL, 256)
+    c4 = workloads.c4_window_ln_linear()
+    assert vt.build_chain(c4.chain, specs_of(c4), c4.consumer["x"]).classify() == (vt.ACCESS_PARTIAL, 7 * 128 * 2)
+
+
 def test_stacked_stage_case():
     # a reshape that straddles a slice boundary needs a second stage
     chain = [("a", "slice", ("X",), {"dim": 1, "start": 0, "stop": 3, "step": 1}),
