@@ -90,3 +90,19 @@ def decode_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float):
         out[b] = np.einsum("ht,htd->hd", e / den, vb)
         lse[b] = (m + np.log(den))[:, 0]
     return out, lse
+
+
+def round_to(x: np.ndarray, dtype: str) -> np.ndarray:
+    """float64 values -> stored bits of the 16-bit type, round to nearest even (the output type of
+    a GEMM is the type of its inputs).  bf16 is rounded from the float32 nearest to the value."""
+    if dtype == "f16":
+        return x.astype(np.float16)
+    if dtype == "bf16":
+        b = x.astype(np.float32).view(np.uint32)
+        keep = b >> np.uint32(16)
+        rest = b & np.uint32(0xFFFF)
+        up = (rest > 0x8000) | ((rest == 0x8000) & ((keep & np.uint32(1)) == 1))
+        nan = (b & np.uint32(0x7FFFFFFF)) > np.uint32(0x7F800000)
+        r = np.where(nan, keep | np.uint32(0x40), keep + up.astype(np.uint32))
+        return r.astype(np.uint16)
+    raise ValueError(dtype)

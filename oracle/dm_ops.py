@@ -88,3 +88,29 @@ def run_chain(chain, sources, tables=None, keep=None):
                 if last_use[i] == k and i not in keep and i not in sources:
                     env.pop(i, None)
     return env
+
+
+def store_through(chain, sources, name, values, tables=None):
+    """Producer-side store (Sec. 4.2, the write direction of Def. 2): the virtual tensor `name`
+    is assigned `values`; every element lands in the physical tensor and at the index that the
+    chain's map names, and everything else keeps what it held (the result of a ScatterND is a
+    clone of its data input with the updates written in, Sec. 4.4).  The map must be one to one
+    on the elements it reaches: two virtual elements on one physical element is an error.
+
+    Returns updated copies of the sources that were written (others are not returned)."""
+    from .index_maps import Chain
+    import itertools
+    ch = Chain(chain, {k: v.shape for k, v in sources.items()}, tables)
+    shp = ch.shapes[name]
+    values = np.asarray(values)
+    assert values.shape == shp, (values.shape, shp)
+    out, seen = {}, set()
+    for x in itertools.product(*[range(n) for n in shp]):
+        s, y = ch.pull_back(name, x)
+        if (s, y) in seen:
+            raise ValueError("store through a map that is not one to one: %s%s written twice" % (s, y))
+        seen.add((s, y))
+        if s not in out:
+            out[s] = sources[s].copy()
+        out[s][y] = values[x]
+    return out

@@ -11,6 +11,14 @@ def run_workload(wl, keep_intermediates: bool = False):
     """Returns a dict: 'out' (float64 or, for add_rowsum, float32), extra keys per consumer."""
     c = wl.consumer
     kind = c["kind"]
+    if kind == "gemm_store":
+        # the chain describes the OUTPUT here: the product of two physical operands, rounded to
+        # the storage type, is assigned to the virtual tensor the chain defines
+        a = consumers.decode(wl.sources[c["a"]], wl.dtype)
+        b = consumers.decode(wl.sources[c["b"]], wl.dtype)
+        out = consumers.gemm(a, b)
+        return {"out": out, "stored": dm_ops.store_through(wl.chain, wl.sources, c["out"],
+                                                           consumers.round_to(out, wl.dtype), wl.index_tables)}
     if kind == "grouped_gemm":
         wanted = set(c["a"]) | set(c["b"])
     else:

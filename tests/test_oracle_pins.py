@@ -387,3 +387,79 @@ def test_bf16_encode_decode_roundtrip_and_rne():
     # 1.01171875 = 1 + 3*2^-8 is a tie between 1.0078125 and 1.015625 -> even (1.015625)
     assert back[2] == 1.015625
     assert back[0] == 1.0 and back[3] == -2.5 and back[4] == 3.140625 and back[5] == 0.0
+
+
+# ------------------------------------------------------------------ producer-side store (Sec. 3.1, 4.2, 4.4)
+def test_store_through_round_trip_and_untouched_elements():
+    """Assigning to a virtual tensor and reading it back through the same chain returns the
+    values; physical elements the map does not reach keep their contents (clone semantics of
+    ScatterND's data input)."""
+    rng = np.random.default_rng(0)
+    src = {"A": rng.integers(0, 1000, size=(4, 6, 5)).astype(np.int64),
+           "B": rng.integers(0, 1000, size=(3, 4)).astype(np.int64)}
+    chain = [("a1", "slice", ("A",), {"dim": 1, "start": 1, "stop": 4}),          # [4,3,5]
+             ("a2", "permute", ("a1",), {"perm": (1, 0, 2)}),                       # [3,4,5]
+             ("a3", "reshape", ("a2",), {"shape": (3, 20)}),
+             ("R", "concat", ("a3", "B"), {"dim": 1})]                             # [3,24]
+    vals = np.arange(3 * 24).reshape(3, 24) + 5000
+    out = dm_ops.store_through(chain, src, "R", vals)
+    ch = index_maps.Chain(chain, {k: v.shape for k, v in src.items()})
+    assert np.array_equal(ch.materialize_by_pull_back("R", out), vals)
+    # written region of A is exactly the slice; the rest is the old data
+    mask = np.zeros(src["A"].shape, bool)
+    mask[:, 1:4, :] = True
+    assert np.array_equal(out["A"][~mask], src["A"][~mask])
+    assert (out["A"][mask] >= 5000).all() and (out["B"] >= 5000).all()
+    # the same result from the operators written out one by one (Split, Transpose, slice assignment)
+    a_part, b_part = vals[:, :20], vals[:, 20:]
+    expect_a = src["A"].copy()
+    expect_a[:, 1:4, :] = a_part.reshape(3, 4, 5).transpose(1, 0, 2)
+    assert np.array_equal(out["A"], expect_a) and np.array_equal(out["B"], b_part)
+
+
+def test_store_through_rejects_maps_that_are_not_one_to_one():
+    src = {"A": np.zeros((2, 3), np.int64)}
+    chain = [("u", "unsqueeze", ("A",), {"dim": 0}), ("e", "expand", ("u",), {"shape": (4, 2, 3)})]
+    with pytest.raises(ValueError):
+        dm_ops.store_through(chain, src, "e", np.zeros((4, 2, 3), np.int64))
+    with pytest.raises(ValueError):
+        dm_ops.store_through([("g", "index_select", ("A",), {"dim": 0, "index": "i"})], src, "g",
+                             np.zeros((3, 3), np.int64), {"i": np.array([0, 1, 0], np.int32)})
+
+
+@pytest.mark.parametrize("T", [1, 3])
+def test_qkv_projection_store_equals_split_reshape_scatter(T):
+    """Fig. 4 / Sec. 3.1: storing the merged projection through the virtual tensor equals
+    Split into Q, K, V, Reshape, and ScatterND of K, V into the cache at positions pos .. pos+T-1."""
+    B, Hq, Hkv, D, cap, pos, hidden = 2, 4, 2, 8, 16, 5, 32
+    wl = workloads.qkv_proj_store(seed=3, B=B, hidden=hidden, Hq=Hq, Hkv=Hkv, D=D, cap=cap, pos=pos, T=T)
+    res = run_workload(wl)
+    c = consumers.round_to(res["out"], "bf16")                       # [B*T, (Hq+2Hkv)*D]
+    q, k, v = c[:, :Hq * D], c[:, Hq * D:(Hq + Hkv) * D], c[:, (Hq + Hkv) * D:]
+    assert np.array_equal(res["stored"]["Qbuf"], q.reshape(B, T, Hq * D))
+    for name, part in (("Kcache", k), ("Vcache", v)):
+        expect = wl.sources[name].copy()
+        for b in range(B):
+            for t in range(T):
+                for h in range(Hkv):
+                    expect[b, h, pos + t, :] = part[b * T + t, h * D:(h + 1) * D]    # ScatterND: one row per index
+        assert np.array_equal(res["stored"][name], expect)
+        assert not np.array_equal(expect, wl.sources[name])
+    # and the product itself against a plain triple loop on a few entries
+    a, w = consumers.decode(wl.sources["X"], "bf16"), consumers.decode(wl.sources["W"], "bf16")
+    for (i, j) in [(0, 0), (B * T - 1, (Hq + 2 * Hkv) * D - 1), (1, Hq * D + 3)]:
+        assert abs(sum(a[i, kk] * w[kk, j] for kk in range(hidden)) - res["out"][i, j]) < 1e-12
+
+
+def test_round_to_bf16_is_round_to_nearest_even():
+    # exact bf16 values stay; ties go to the even mantissa; the rest to the nearest
+    def bits(f):
+        return int(np.array([f], np.float32).view(np.uint32)[0] >> 16)
+    x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, -2.5, 0.0, 3.0e38])
+    r = consumers.round_to(x, "bf16")
+    assert list(r[:4]) == [bits(1.0), bits(1.0), bits(1.0 + 2.0 ** -6), bits(1.0 + 2.0 ** -7)]
+    assert r[4] == bits(-2.5) and r[5] == 0
+    assert np.array_equal(consumers.decode(r, "bf16")[:1], [1.0])
+    # agrees with the input generator's rounding on random float32 values
+    y = np.random.default_rng(1).standard_normal(4096).astype(np.float32)
+    assert np.array_equal(consumers.round_to(y.astype(np.float64), "bf16"), workloads.encode(y, "bf16"))

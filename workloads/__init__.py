@@ -1,5 +1,6 @@
 """Seeded synthetic workloads: tensor shapes, value distributions and the
-data-movement chains of the five benchmark configurations.
+data-movement chains of the five benchmark configurations (plus the QKV projection that
+stores through a virtual tensor).
 
 This package holds *descriptions* only: random source tensors and, for each
 configuration, the list of data-movement operators between the producer and the
@@ -16,6 +17,8 @@ from .inputs import (  # noqa: F401
     c3_oproj_gemm,
     c4_window_ln_linear,
     c5_moe_dispatch,
+    qkv_proj_store,
+    qkv_store_chain,
     random_chain,
     CONFIGS,
 )

@@ -206,12 +206,48 @@ def c5_moe_dispatch(seed: int = 0, T: int = 16384, Hd: int = 4096, E: int = 8, N
                     {"kind": "grouped_gemm", "a": a_names, "b": b_names}, tables)
 
 
+# ----------------------------------------------------------------------------------------
+# QKV projection that writes through a virtual tensor (producer-side store), bf16
+# ----------------------------------------------------------------------------------------
+def qkv_store_chain(B: int, Hq: int, Hkv: int, cap: int, D: int, pos: int, T: int = 1):
+    """The projection's output C[B*T, (Hq+2Hkv)*D] seen as a virtual tensor of three physical
+    tensors (Fig. 4): columns [0, Hq*D) are the Q buffer, the next Hkv*D columns are slots
+    pos .. pos+T-1 of the K cache [B,Hkv,cap,D], the last Hkv*D those of the V cache."""
+    chain = [("q2", "reshape", ("Qbuf",), {"shape": (B * T, Hq * D)})]
+    for n, cache in (("k", "Kcache"), ("v", "Vcache")):
+        chain += [
+            (n + "s", "slice", (cache,), {"dim": 2, "start": pos, "stop": pos + T}),      # [B,Hkv,T,D]
+            (n + "p", "permute", (n + "s",), {"perm": (0, 2, 1, 3)}),                       # [B,T,Hkv,D]
+            (n + "2", "reshape", (n + "p",), {"shape": (B * T, Hkv * D)}),
+        ]
+    chain.append(("Cout", "concat", ("q2", "k2", "v2"), {"dim": 1}))
+    return chain
+
+
+def qkv_proj_store(seed: int = 0, B: int = 8, hidden: int = 4096, Hq: int = 32, Hkv: int = 8, D: int = 128,
+                   cap: int = 4096, pos: int = 4095, T: int = 1, dtype: str = "bf16") -> Workload:
+    """Decode step (T = 1) or a chunk of T new tokens per sequence: X[B*T, hidden] . W[hidden, (Hq+2Hkv)*D],
+    result stored straight into the Q buffer and the cache slots.  The caches and the Q buffer
+    hold random values beforehand so that a store to a wrong place, or a missing one, shows."""
+    E = (Hq + 2 * Hkv) * D
+    src = {
+        "X": _normal(seed, 0, (B * T, hidden), 1.0, dtype),
+        "W": _normal(seed, 1, (hidden, E), 0.02, dtype),
+        "Qbuf": _normal(seed, 2, (B, T, Hq * D), 1.0, dtype),
+        "Kcache": _normal(seed, 3, (B, Hkv, cap, D), 1.0, dtype),
+        "Vcache": _normal(seed, 4, (B, Hkv, cap, D), 1.0, dtype),
+    }
+    return Workload("qkv_proj_store", dtype, src, qkv_store_chain(B, Hq, Hkv, cap, D, pos, T),
+                    {"kind": "gemm_store", "a": "X", "b": "W", "out": "Cout"})
+
+
 CONFIGS = {
     "c1": c1_tiny_chain,
     "c2": c2_decode_attention,
     "c3": c3_oproj_gemm,
     "c4": c4_window_ln_linear,
     "c5": c5_moe_dispatch,
+    "qkv_store": qkv_proj_store,
 }
 
 
