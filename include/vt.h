@@ -178,6 +178,35 @@ int vt_decode_attn_workspace_init(void* workspace, size_t workspace_bytes, void*
 int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float scale, void* out,
                    float* lse, void* workspace, size_t workspace_bytes, int n_splits, void* stream);
 
+/* Copy kernel in the store direction: every element of the virtual tensor src is written to the
+ * physical place that dst's map names; other elements of dst's tensors are left alone.  This is
+ * the explicit Split / Reshape / ScatterND of the materialized comparison path.  src and dst have
+ * the same shape and dtype; dst must be one to one (as for vt_gemm_store) and its sources must
+ * carry writable device pointers.  Asynchronous on `stream`. */
+int vt_scatter(const vt_desc* src, const vt_desc* dst, void* stream);
+
+/* Producer-side virtual store (Sec. 3.1 and Fig. 4; Sec. 4.2, stage 3 through the map):
+ * C = A . B, fp32 accumulation, each element rounded to the operands' 16-bit type and written to
+ * the physical tensor and offset that the OUTPUT descriptor C names; nothing else is written, so
+ * the tensors behind C keep all other contents (what Split + Reshape + ScatterND would produce
+ * from the dense product, without executing them).
+ *   A  [M,K]: single piece, rows through its map, K contiguous, 8-byte aligned rows.
+ *   B  [K,N]: a row-major matrix (constant row stride, multiple of 8 elements, 16-byte aligned).
+ *   C  [M,N]: its pieces split the columns only (at most 4); every source carries a writable
+ *      device pointer.  The map must be one to one: a broadcast digit or pieces whose ranges in
+ *      one tensor may overlap give VT_ERR_NOT_ONE_TO_ONE; index tables and stacked stages on
+ *      the output give VT_ERR_UNSUPPORTED.
+ * N and K are multiples of 8.  The kernel is built for a handful of rows (a decode step:
+ * M = batch); more rows are processed 16 at a time and B is read once per 16 rows.
+ * workspace: device pointer (16-byte aligned), at least vt_gemm_store_workspace(M, N, K) bytes,
+ * cleared once with vt_gemm_store_workspace_init (arrival counters, left at zero by every call,
+ * and the partial sums of the K slices); calls that share a workspace must not overlap in time.
+ * Results are bitwise reproducible from call to call.  Asynchronous on `stream`. */
+size_t vt_gemm_store_workspace(int64_t M, int64_t N, int64_t K);
+int vt_gemm_store_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+int vt_gemm_store(const vt_desc* A, const vt_desc* B, const vt_desc* C, void* workspace,
+                  size_t workspace_bytes, void* stream);
+
 const char* vt_last_error(void);
 const char* vt_version(void);
 

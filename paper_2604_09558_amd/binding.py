@@ -70,6 +70,11 @@ def lib():
         L.vt_copy_op.argtypes = [C.POINTER(VtSource), C.c_int, C.POINTER(VtOp), P, P]
         L.vt_elementwise.argtypes = [C.c_int, P, P, C.c_float, P, P]
         L.vt_gemm.argtypes = [C.POINTER(P), C.POINTER(P), C.POINTER(P), C.c_int, C.c_int, C.c_int, C.c_float, P]
+        L.vt_scatter.argtypes = [P, P, P]
+        L.vt_gemm_store_workspace.argtypes = [C.c_int64, C.c_int64, C.c_int64]
+        L.vt_gemm_store_workspace.restype = C.c_size_t
+        L.vt_gemm_store_workspace_init.argtypes = [P, C.c_size_t, P]
+        L.vt_gemm_store.argtypes = [P, P, P, P, C.c_size_t, P]
         L.vt_decode_attn_workspace.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
         L.vt_decode_attn_workspace.restype = C.c_size_t
         L.vt_decode_attn_workspace_init.argtypes = [P, C.c_size_t, P]
@@ -301,3 +306,19 @@ def vt_decode_attn(Q: Desc, K: Desc, V: Desc, scale: float, out, workspace, work
                    lse=None, stream=None):
     _check(lib().vt_decode_attn(Q.handle, K.handle, V.handle, C.c_float(scale), _ptr(out), _ptr(lse),
                                 _ptr(workspace), workspace_bytes, n_splits, _stream(stream)))
+
+
+def vt_gemm_store_workspace(M, N, K) -> int:
+    return int(lib().vt_gemm_store_workspace(M, N, K))
+
+
+def vt_gemm_store_workspace_init(workspace, workspace_bytes: int, stream=None):
+    _check(lib().vt_gemm_store_workspace_init(_ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def vt_gemm_store(A: Desc, B: Desc, Cout: Desc, workspace, workspace_bytes: int, stream=None):
+    _check(lib().vt_gemm_store(A.handle, B.handle, Cout.handle, _ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def vt_scatter(src: Desc, dst: Desc, stream=None):
+    _check(lib().vt_scatter(src.handle, dst.handle, _stream(stream)))

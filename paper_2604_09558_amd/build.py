@@ -11,7 +11,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libvt.so")
 
 HOST_SOURCES = ["vt_build.cpp", "vt_device_host.cpp"]
-HIP_SOURCES = ["vt_kernels.hip", "vt_attn.hip", "vt_gemm.hip", "vt_ln_gemm.hip"]
+HIP_SOURCES = ["vt_kernels.hip", "vt_attn.hip", "vt_gemm.hip", "vt_ln_gemm.hip", "vt_gemm_store.hip"]
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC, "-Wall", "-Wno-unused-function"]
 # gfx950 only; packed-fp32 instructions are switched off (they have given wrong results on

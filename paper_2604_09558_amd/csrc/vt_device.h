@@ -129,5 +129,7 @@ int vector_width(const vt_desc& d);
 
 // launch bookkeeping shared by the kernels' host wrappers
 int check_launch(const char* what);
+// VT_OK if the descriptor can be the target of a store: no two virtual elements share a physical one.
+int check_store_map(const vt_desc& d, const char* who);
 
 }  // namespace vt

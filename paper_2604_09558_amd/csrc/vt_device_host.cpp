@@ -1,4 +1,5 @@
 // Host helpers: conversion of a descriptor to its device form, vector-width analysis.
+#include <algorithm>
 #include <cstring>
 
 #include "vt_device.h"
@@ -112,6 +113,44 @@ int vector_width(const vt_desc& d) {
   while (vec > 1 && !ok(vec)) vec >>= 1;
   return vec;
 }
+
+// A physical tensor may be written through a map only if no two virtual elements share a
+// physical one.  Sufficient conditions checked here: no broadcast digit, no index table, no
+// stacked stage; inside a piece the digits, ordered by stride, nest (each stride at least the
+// span of the smaller ones); pieces of one source cover disjoint offset ranges.
+int check_store_map(const vt_desc& d, const char* who) {
+  const std::string w(who);
+  struct Range {
+    int src;
+    int64_t lo, hi;
+  };
+  std::vector<Range> ranges;
+  for (const Piece& p : d.pieces) {
+    if (!p.v.lower.empty()) return fail(VT_ERR_UNSUPPORTED, w + ": output with stacked index stages");
+    std::vector<std::pair<int64_t, int64_t>> dg;    // (|stride|, radix)
+    int64_t lo = p.v.base, hi = p.v.base;
+    for (const auto& grp : p.v.groups)
+      for (const Digit& g : grp) {
+        if (g.radix <= 1) continue;
+        if (g.table >= 0) return fail(VT_ERR_UNSUPPORTED, w + ": output through an index table");
+        if (g.stride == 0) return fail(VT_ERR_NOT_ONE_TO_ONE, w + ": the output map sends several elements to one place (broadcast)");
+        dg.push_back({g.stride < 0 ? -g.stride : g.stride, g.radix});
+        (g.stride < 0 ? lo : hi) += (g.radix - 1) * g.stride;
+      }
+    std::sort(dg.begin(), dg.end());
+    int64_t span = 1;
+    for (const auto& sr : dg) {
+      if (sr.first < span) return fail(VT_ERR_NOT_ONE_TO_ONE, w + ": the output map is not one to one (overlapping strides)");
+      span = sr.first * (sr.second - 1) + span;
+    }
+    for (const Range& r : ranges)
+      if (r.src == p.src && !(hi < r.lo || r.hi < lo))
+        return fail(VT_ERR_NOT_ONE_TO_ONE, w + ": two pieces of the output may overlap in one tensor");
+    ranges.push_back({p.src, lo, hi});
+  }
+  return VT_OK;
+}
+
 
 }  // namespace vt
 

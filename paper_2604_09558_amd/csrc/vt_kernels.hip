@@ -25,6 +25,50 @@ __global__ void __launch_bounds__(256) k_materialize(const DevDesc D, V* __restr
   }
 }
 
+// The reverse direction: every element of the virtual tensor S is written to the place the map
+// of D names (D one to one).  The explicit Split / Reshape / ScatterND of the materialized path.
+template <typename V>
+__global__ void __launch_bounds__(256) k_scatter(const DevDesc S, const DevDesc D, uint32_t inner_vecs, uint32_t vec_elems,
+                                                 uint32_t outer) {
+  uint32_t vi = blockIdx.x * 256u + threadIdx.x;
+  if (vi >= inner_vecs) return;
+  for (uint32_t o = blockIdx.y; o < outer; o += gridDim.y) {
+    int64_t so, dof;
+    const void *sp, *dp;
+    vtd_eval(S, o, vi * vec_elems, &so, &sp);
+    vtd_eval(D, o, vi * vec_elems, &dof, &dp);
+    *reinterpret_cast<V*>(static_cast<char*>(const_cast<void*>(dp)) + dof * D.elem_size) =
+        *reinterpret_cast<const V*>(static_cast<const char*>(sp) + so * S.elem_size);
+  }
+}
+
+static int launch_scatter(const vt_desc& s, const vt_desc& d, hipStream_t stream) {
+  DevDesc S, D;
+  int64_t outer, inner, outer2, inner2;
+  int rc = to_device(s, &S, &outer, &inner);
+  if (rc != VT_OK) return rc;
+  rc = to_device(d, &D, &outer2, &inner2);
+  if (rc != VT_OK) return rc;
+  const int vec = std::min(vector_width(s), vector_width(d));
+  const uint32_t inner_vecs = (uint32_t)(inner / vec);
+  dim3 grid((inner_vecs + 255) / 256, (unsigned)std::min<int64_t>(outer, 65535));
+  switch (vec * dtype_size(s.dtype)) {
+    case 16:
+      hipLaunchKernelGGL(k_scatter<uint4>, grid, dim3(256), 0, stream, S, D, inner_vecs, (uint32_t)vec, (uint32_t)outer);
+      break;
+    case 8:
+      hipLaunchKernelGGL(k_scatter<uint2>, grid, dim3(256), 0, stream, S, D, inner_vecs, (uint32_t)vec, (uint32_t)outer);
+      break;
+    case 4:
+      hipLaunchKernelGGL(k_scatter<uint32_t>, grid, dim3(256), 0, stream, S, D, inner_vecs, (uint32_t)vec, (uint32_t)outer);
+      break;
+    default:
+      hipLaunchKernelGGL(k_scatter<uint16_t>, grid, dim3(256), 0, stream, S, D, inner_vecs, (uint32_t)vec, (uint32_t)outer);
+      break;
+  }
+  return check_launch("vt_scatter");
+}
+
 static int launch_materialize(const vt_desc& d, void* dst, hipStream_t stream) {
   DevDesc D;
   int64_t outer, inner;
@@ -177,6 +221,16 @@ extern "C" {
 int vt_materialize(const vt_desc* d, void* dst, void* stream) {
   if (!d || !dst) return fail(VT_ERR_INVALID_ARG, "vt_materialize: NULL argument");
   return launch_materialize(*d, dst, (hipStream_t)stream);
+}
+
+int vt_scatter(const vt_desc* src, const vt_desc* dst, void* stream) {
+  if (!src || !dst) return fail(VT_ERR_INVALID_ARG, "vt_scatter: NULL argument");
+  if (src->shape != dst->shape || src->dtype != dst->dtype) return fail(VT_ERR_SHAPE, "vt_scatter: source and destination differ in shape or dtype");
+  int rc = check_store_map(*dst, "vt_scatter");
+  if (rc != VT_OK) return rc;
+  for (const Piece& p : dst->pieces)
+    if (!dst->sources[p.src].ptr) return fail(VT_ERR_INVALID_ARG, "vt_scatter: destination tensor without a device pointer");
+  return launch_scatter(*src, *dst, (hipStream_t)stream);
 }
 
 int vt_copy_op(const vt_source* in, int n_in, const vt_op* op, void* dst, void* stream) {

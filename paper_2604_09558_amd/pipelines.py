@@ -181,7 +181,45 @@ class Gemm:
         return self.out
 
 
+# ------------------------------------------------------------------------------------------
+# QKV projection with a producer-side store
+# ------------------------------------------------------------------------------------------
+class GemmStore:
+    """consumer kind "gemm_store": the chain describes the OUTPUT.  virtual: one launch of
+    vt_gemm_store writes the product through the output descriptor.  materialized: the same
+    kernel writes the product to a dense buffer and a copy kernel scatters it to the physical
+    targets (the Split / Reshape / ScatterND that the virtual store removes)."""
+
+    def __init__(self, dw: DeviceWorkload, materialized=False):
+        c = dw.wl.consumer
+        wl = dw.wl
+        self.dw = dw
+        self.materialized = materialized
+        self.A, self.B = dw.build(c["a"]), dw.build(c["b"])
+        self.Cout = dw.build(c["out"])
+        M, K = self.A.shape
+        N = self.B.shape[1]
+        self.shape = (M, N, K)
+        self.ws_bytes = vt.vt_gemm_store_workspace(M, N, K)
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dw.device)
+        vt.vt_gemm_store_workspace_init(self.ws, self.ws_bytes)
+        if materialized:
+            self.dense = torch.empty((M, N), dtype=TORCH_DTYPE[wl.dtype], device=dw.device)
+            self.dense_desc = vt.build_chain([], {"dense": ((M, N), wl.dtype, self.dense.data_ptr())}, "dense")
+
+    def run(self, stream=None):
+        if not self.materialized:
+            vt.vt_gemm_store(self.A, self.B, self.Cout, self.ws, self.ws_bytes, stream=stream)
+        else:
+            # the same GEMM kernel into a dense buffer (identity descriptor), then the scatter
+            vt.vt_gemm_store(self.A, self.B, self.dense_desc, self.ws, self.ws_bytes, stream=stream)
+            vt.vt_scatter(self.dense_desc, self.Cout, stream=stream)
+        return None
+
+
 def make_pipeline(dw: DeviceWorkload, materialized=False, **kw):
+    if dw.wl.consumer["kind"] == "gemm_store":
+        return GemmStore(dw, materialized)
     kind = dw.wl.consumer["kind"]
     if kind == "add_rowsum":
         return AddRowsum(dw, materialized)

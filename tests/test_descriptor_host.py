@@ -334,3 +334,30 @@ def test_error_paths():
     with pytest.raises(vt.VtError) as ei:
         vt.vt_materialize(d, 16, stream=0)
     assert ei.value.code == vt.ERR_INVALID_ARG
+
+
+def test_store_maps_must_be_one_to_one():
+    """A descriptor is a legal store target only if no two virtual elements share a physical one
+    (host check; no kernel is launched for a rejected map)."""
+    fake = 0x1000        # never dereferenced: the check comes before any launch
+    src = vt.build_chain([], {"S": ((4, 6), "f32", fake)}, "S")
+    exp = vt.build_chain([("u", "unsqueeze", ("A",), {"dim": 0}), ("e", "expand", ("u",), {"shape": (4, 6)})],
+                         {"A": ((6,), "f32", fake)}, "e")
+    with pytest.raises(vt.VtError) as ei:
+        vt.vt_scatter(src, exp)
+    assert ei.value.code == vt.ERR_NOT_ONE_TO_ONE
+    # the same tensor twice in a concat: the two pieces overlap
+    twice = vt.build_chain([("c", "concat", ("A", "A"), {"dim": 1})], {"A": ((4, 3), "f32", fake)}, "c")
+    with pytest.raises(vt.VtError) as ei:
+        vt.vt_scatter(src, twice)
+    assert ei.value.code == vt.ERR_NOT_ONE_TO_ONE
+    # an index table on the output is refused (it may repeat entries)
+    tab = vt.build_chain([("g", "index_select", ("A",), {"dim": 0, "index": "i"})], {"A": ((4, 6), "f32", fake)}, "g",
+                         {"i": np.array([0, 1, 2, 3], np.int32)}, {"i": fake})
+    with pytest.raises(vt.VtError) as ei:
+        vt.vt_scatter(src, tab)
+    assert ei.value.code == vt.ERR_UNSUPPORTED
+    # shapes must agree
+    with pytest.raises(vt.VtError) as ei:
+        vt.vt_scatter(src, vt.build_chain([], {"S": ((6, 4), "f32", fake)}, "S"))
+    assert ei.value.code == vt.ERR_SHAPE
