@@ -19,7 +19,9 @@
 #include <algorithm>
 #include <cstdlib>
 #include <cstring>
+#include <type_traits>
 
+#include "vt_coherent.h"
 #include "vt_gemm_common.h"
 
 using namespace vt;
@@ -83,10 +85,10 @@ __device__ __forceinline__ Regs16 load16(const char* p) {
 }
 
 template <typename T>
-__global__ void __launch_bounds__(kWaves * 64) k_gemm_store(const StoreParams P) {
+__global__ void __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) k_gemm_store(const StoreParams P) {
   typedef Mma16<T> M_;
   typedef typename M_::vec opvec;
-  __shared__ float red[kWaves][kBM * kBN];     // 32 KB
+  __shared__ __attribute__((aligned(16))) float red[kWaves][kBM * kBN];     // 32 KB
   __shared__ uint32_t ticket_sh;
 
   const int split = blockIdx.x, cb = blockIdx.y, rb = blockIdx.z;
@@ -100,6 +102,8 @@ __global__ void __launch_bounds__(kWaves * 64) k_gemm_store(const StoreParams P)
   // whose results are never stored) and its row of A
   const int col = min(cb * kBN + l16 * 8, N - 8);
   const char* bp = P.b + (size_t)col * 2;
+  const size_t row_bytes = (size_t)P.ldb * 2;
+  const uint32_t lane_off = (uint32_t)(lg * 4 * row_bytes + (size_t)col * 2);   // the host checks 16 rows of B < 4 GiB
   const int m = rb * kBM + l16;
   const bool m_ok = m < M;
   const char* ap = P.a + axis_off(P.a_row, (uint32_t)min(m, M - 1)) * 2;
@@ -109,39 +113,62 @@ __global__ void __launch_bounds__(kWaves * 64) k_gemm_store(const StoreParams P)
   for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   // B rows of a tile: load j is contraction slot j of the lane group, row (j>>2)*16 + lg*4 + (j&3);
-  // rows past k_end repeat the last valid row and meet a zero in A
-  Regs16 bst[8];
-  uint2 a_lo, a_hi;
-  auto issue = [&](int k0) {
-    const int last = k_end - 1 - k0;
+  // rows past k_end repeat the last valid row and meet a zero in A.  Three register sets: the
+  // loads of the next two tiles are in flight while one tile is multiplied (a wave has only a
+  // few tiles, so the depth of this pipeline is what hides the memory latency).
+  Regs16 bst[3][8];
+  uint2 a_lo[3], a_hi[3];
+  auto issue = [&](int tile, auto set) {
+    constexpr int S = decltype(set)::value;
+    if (tile >= n_tiles) return;
+    const int k0 = k_begin + tile * kTileK;
+    if (k0 + kTileK <= k_end) {
+      // a full tile: one wave-uniform base per load plus ONE per-lane offset
+      const char* wb = P.b + (size_t)k0 * row_bytes;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int r = min((j >> 2) * 16 + lg * 4 + (j & 3), last);
-      bst[j] = load16(bp + (size_t)(k0 + r) * P.ldb * 2);
+      for (int j = 0; j < 8; ++j) bst[S][j] = load16(wb + (size_t)((j >> 2) * 16 + (j & 3)) * row_bytes + lane_off);
+    } else {
+      const int last = k_end - 1 - k0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int r = min((j >> 2) * 16 + lg * 4 + (j & 3), last);
+        bst[S][j] = load16(bp + (size_t)(k0 + r) * row_bytes);
+      }
     }
     // A^T fragment: k = k0 + lg*4 + (0..3) and k0 + 16 + lg*4 + (0..3) of row m (K % 8 == 0, so
     // a group of 4 is valid or not as a whole)
-    a_lo = make_uint2(0, 0);
-    a_hi = make_uint2(0, 0);
-    if (m_ok && k0 + lg * 4 < k_end) a_lo = *reinterpret_cast<const uint2*>(ap + (size_t)(k0 + lg * 4) * 2);
-    if (m_ok && k0 + 16 + lg * 4 < k_end) a_hi = *reinterpret_cast<const uint2*>(ap + (size_t)(k0 + 16 + lg * 4) * 2);
+    a_lo[S] = make_uint2(0, 0);
+    a_hi[S] = make_uint2(0, 0);
+    if (m_ok && k0 + lg * 4 < k_end) a_lo[S] = *reinterpret_cast<const uint2*>(ap + (size_t)(k0 + lg * 4) * 2);
+    if (m_ok && k0 + 16 + lg * 4 < k_end) a_hi[S] = *reinterpret_cast<const uint2*>(ap + (size_t)(k0 + 16 + lg * 4) * 2);
   };
-
-  if (wave < n_tiles) issue(k_begin + wave * kTileK);
-  for (int tile = wave; tile < n_tiles; tile += kWaves) {
-    Regs16 cur[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) cur[j] = bst[j];
-    const opvec aop = __builtin_bit_cast(opvec, make_uint4(a_lo.x, a_lo.y, a_hi.x, a_hi.y));
-    if (tile + kWaves < n_tiles) issue(k_begin + (tile + kWaves) * kTileK);    // next tile in flight under this one
+  auto multiply = [&](auto set) {
+    constexpr int S = decltype(set)::value;
+    const opvec aop = __builtin_bit_cast(opvec, make_uint4(a_lo[S].x, a_lo[S].y, a_hi[S].x, a_hi[S].y));
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
       uint32_t w[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) w[u] = __builtin_amdgcn_perm(cur[2 * u + 1].w[e >> 1], cur[2 * u].w[e >> 1], sel);
+      for (int u = 0; u < 4; ++u) w[u] = __builtin_amdgcn_perm(bst[S][2 * u + 1].w[e >> 1], bst[S][2 * u].w[e >> 1], sel);
       acc[e] = M_::run(__builtin_bit_cast(opvec, make_uint4(w[0], w[1], w[2], w[3])), aop, acc[e]);
     }
+  };
+  typedef std::integral_constant<int, 0> S0;
+  typedef std::integral_constant<int, 1> S1;
+  typedef std::integral_constant<int, 2> S2;
+  // this wave's tiles: wave, wave + kWaves, ...
+  issue(wave, S0{});
+  issue(wave + kWaves, S1{});
+  for (int tile = wave; tile < n_tiles; tile += 3 * kWaves) {
+    issue(tile + 2 * kWaves, S2{});
+    multiply(S0{});
+    if (tile + kWaves >= n_tiles) break;
+    issue(tile + 3 * kWaves, S0{});
+    multiply(S1{});
+    if (tile + 2 * kWaves >= n_tiles) break;
+    issue(tile + 4 * kWaves, S1{});
+    multiply(S2{});
   }
 
   // ---- sum the waves through LDS.  acc[e][i] is C[m = l16][n = (lg*4 + i)*8 + e] of the block.
@@ -153,12 +180,15 @@ __global__ void __launch_bounds__(kWaves * 64) k_gemm_store(const StoreParams P)
   const size_t blk = (size_t)rb * gridDim.y + cb;
   float* mine = P.partial + (blk * P.n_splits + split) * (kBM * kBN);
   const int n_valid = min(kBM, M - rb * kBM) * kBN;     // rows past M are neither summed nor stored
-  for (int idx = threadIdx.x; idx < n_valid; idx += kWaves * 64) {
-    float s = red[0][idx];
+  // four consecutive columns per thread: 16-byte device-coherent stores, whole lines per wave
+  for (int idx = threadIdx.x * 4; idx < n_valid; idx += kWaves * 64 * 4) {
+    float4 s = *reinterpret_cast<const float4*>(&red[0][idx]);
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) s += red[w][idx];
-    // device-scope atomic stores: written through to where every compute die sees them
-    __hip_atomic_store(&mine[idx], s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int w = 1; w < kWaves; ++w) {
+      const float4 t = *reinterpret_cast<const float4*>(&red[w][idx]);
+      s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+    }
+    store_device_b128(&mine[idx], __builtin_bit_cast(u32x4_t, s));
   }
   // ---- the last workgroup of this block to arrive adds the K slices and stores.  The barrier
   // waits for every wave's stores to complete before one thread takes the ticket; atomicInc
@@ -169,28 +199,36 @@ __global__ void __launch_bounds__(kWaves * 64) k_gemm_store(const StoreParams P)
   __syncthreads();
   if (ticket_sh != (uint32_t)(P.n_splits - 1)) return;
   const float* all = P.partial + blk * P.n_splits * (kBM * kBN);
-  for (int idx = threadIdx.x; idx < n_valid; idx += kWaves * 64) {
-    const int mm = rb * kBM + idx / kBN, n = cb * kBN + idx % kBN;
-    float s = 0.f;
-    for (int sp0 = 0; sp0 < P.n_splits; sp0 += 8) {
-      float v[8];
+  for (int idx = threadIdx.x * 4; idx < n_valid; idx += kWaves * 64 * 4) {
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int sp0 = 0; sp0 < P.n_splits; sp0 += 4) {      // slices in order: the sum is reproducible
+      u32x4_t v[4];
+      const float* q[4];
 #pragma unroll
-      for (int u = 0; u < 8; ++u)            // eight independent loads in flight
-        v[u] = __hip_atomic_load(&all[(size_t)min(sp0 + u, P.n_splits - 1) * (kBM * kBN) + idx], __ATOMIC_RELAXED,
-                                 __HIP_MEMORY_SCOPE_AGENT);
+      for (int u = 0; u < 4; ++u) q[u] = &all[(size_t)min(sp0 + u, P.n_splits - 1) * (kBM * kBN) + idx];
+      load_device_4xb128(q[0], q[1], q[2], q[3], v);
 #pragma unroll
-      for (int u = 0; u < 8; ++u)
-        if (sp0 + u < P.n_splits) s += v[u];
+      for (int u = 0; u < 4; ++u)
+        if (sp0 + u < P.n_splits) {
+          const float4 t = __builtin_bit_cast(float4, v[u]);
+          s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+        }
     }
-    if (n >= N) continue;
-    // stage 3 through the map: which physical tensor holds column n, and where
-    int pc = 0;
+    const float sv[4] = {s.x, s.y, s.z, s.w};
+    const int mm = rb * kBM + idx / kBN;
 #pragma unroll
-    for (int i = 1; i < kMaxOutPieces; ++i)
-      if (i < P.n_out && n >= P.out[i].col_lo) pc = i;
-    const OutPiece& o = P.out[pc];
-    const int64_t off = axis_off(o.row, (uint32_t)mm) + axis_off(o.col, (uint32_t)(n - o.col_lo));
-    *reinterpret_cast<T*>(o.base + off * 2) = from_float<T>(s);
+    for (int c = 0; c < 4; ++c) {
+      const int n = cb * kBN + idx % kBN + c;
+      if (n >= N) continue;
+      // stage 3 through the map: which physical tensor holds column n, and where
+      int pc = 0;
+#pragma unroll
+      for (int i = 1; i < kMaxOutPieces; ++i)
+        if (i < P.n_out && n >= P.out[i].col_lo) pc = i;
+      const OutPiece& o = P.out[pc];
+      const int64_t off = axis_off(o.row, (uint32_t)mm) + axis_off(o.col, (uint32_t)(n - o.col_lo));
+      *reinterpret_cast<T*>(o.base + off * 2) = from_float<T>(sv[c]);
+    }
   }
 }
 
@@ -199,15 +237,19 @@ __global__ void k_zero_store_ws(uint32_t* p, size_t n) {
   if (i < n) p[i] = 0u;
 }
 
-// Slices of K per block: about three workgroups per compute unit, at least one tile per wave.
+// Slices of K per block: a power of two (equal slices), about 192 workgroups in all (measured
+// best on the 4096 x 6144 projection: fewer leave compute units idle, more lengthen the merge),
+// at least one tile per wave.
 int choose_k_splits(int64_t blocks, int64_t K) {
   const int64_t max_splits = std::max<int64_t>(1, K / (kTileK * kWaves));
   static const int target = [] {
     const char* e = getenv("VT_STORE_WGS");             // tuning knob: workgroups the launch aims for
-    return e && atoi(e) > 0 ? atoi(e) : 768;
+    return e && atoi(e) > 0 ? atoi(e) : 192;
   }();
-  const int64_t want = std::max<int64_t>(1, (target + blocks - 1) / blocks);
-  return (int)std::min<int64_t>(std::min(want, max_splits), 64);
+  const int64_t want = std::min<int64_t>(std::min(std::max<int64_t>(1, (target + blocks - 1) / blocks), max_splits), 64);
+  int ns = 1;
+  while (ns * 2 <= want) ns *= 2;
+  return ns;
 }
 
 size_t ticket_area(int64_t blocks) { return (size_t)((blocks * 4 + 255) / 256 * 256); }
@@ -274,6 +316,7 @@ int vt_gemm_store(const vt_desc* A, const vt_desc* B, const vt_desc* C, void* wo
     if (br.nd != 1 || !(bc.nd == 1 && bc.stride[2] == 1) || br.stride[2] % 8 || br.stride[2] < 0 || (uintptr_t)P.b % 16)
       return fail(VT_ERR_UNSUPPORTED, "vt_gemm_store: B must be a row-major matrix with 16-byte aligned rows");
     P.ldb = br.stride[2];
+    if (P.ldb * 2 * 16 + N * 2 >= (1ll << 32)) return fail(VT_ERR_UNSUPPORTED, "vt_gemm_store: rows of B too far apart");
   }
   // the output: pieces that split the columns
   int rc = check_store_map(*C, "vt_gemm_store");
