@@ -162,7 +162,7 @@ int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* const* C, in
 
 /* Split-K flash-decoding attention with grouped queries (Sec. 3.1: the attention kernel
  * reads the un-expanded cache).  Q virtual [B,Hq,1,D], K and V virtual [B,Hq,S,D]
- * (f16/bf16, D = 128).  out dense [B,Hq,D], same dtype.  softmax(scale * q.k) in fp32.
+ * (f16/bf16, D = 128).  out dense [B,Hq,D], same dtype, 8-byte aligned.  softmax(scale * q.k) in fp32.
  * Query heads whose K/V rows coincide (a broadcast digit in the map) share one read.
  * workspace: device pointer (16-byte aligned) of at least vt_decode_attn_workspace(...) bytes,
  * holding arrival counters and the per-split partial results, prepared once with

@@ -33,6 +33,7 @@
 #include <cstring>
 #include <numeric>
 
+#include "vt_coherent.h"
 #include "vt_device.h"
 #include "vt_numeric.h"
 
@@ -312,21 +313,23 @@ k_decode_attn(const AttnParams P) {
   __syncthreads();
   const int bg = b * P.Hkv + g;
   const size_t unit = (size_t)bg * P.n_splits + split;
-  for (int idx = threadIdx.x; idx < G * kD; idx += WAVES * 64) {
-    int h = idx / kD;
+  // four consecutive d per thread; partial results go out as 16-byte device-coherent stores
+  // (written through to where every compute die sees them), whole cache lines per wave
+  for (int idx = threadIdx.x * 4; idx < G * kD; idx += WAVES * 64 * 4) {
+    const int h = idx / kD;
     float mx = -1.0e30f;
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) mx = fmaxf(mx, red_ml[(w * 16 + h) * 2]);
-    float o = 0.f, l = 0.f;
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+    float l = 0.f;
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) {
-      float sc = __builtin_amdgcn_exp2f(red_ml[(w * 16 + h) * 2] - mx);
-      o += red_o[(w * G + h) * kD + (idx - h * kD)] * sc;
+      const float sc = __builtin_amdgcn_exp2f(red_ml[(w * 16 + h) * 2] - mx);
+      const float4 r = *reinterpret_cast<const float4*>(&red_o[(w * G + h) * kD + (idx - h * kD)]);
+      o.x += r.x * sc; o.y += r.y * sc; o.z += r.z * sc; o.w += r.w * sc;
       l += red_ml[(w * 16 + h) * 2 + 1] * sc;
     }
-    // partial results go out as device-scope atomic stores (written through to where every
-    // compute die sees them), so that no cache write-back is needed before the ticket
-    __hip_atomic_store(&P.ws_o[unit * G * kD + idx], o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    store_device_b128(&P.ws_o[unit * G * kD + idx], __builtin_bit_cast(u32x4_t, o));
     if (idx == h * kD) {
       __hip_atomic_store(&P.ws_ml[(unit * G + h) * 2 + 0], mx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(&P.ws_ml[(unit * G + h) * 2 + 1], l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -348,43 +351,38 @@ k_decode_attn(const AttnParams P) {
   T* out = static_cast<T*>(P.out);
   auto ld = [](const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
   // (m, l) of every split and head go to LDS (ns * G * 2 contiguous floats; the K tiles' LDS is
-  // free now); the first eight partial outputs of this thread's (head, d) are requested in the
-  // same breath so that the merge costs one memory round trip, not two
+  // free now); each thread then merges four consecutive d of one head, reading the splits'
+  // partial outputs with 16-byte device-coherent loads, four in flight
   float* ml_sh = reinterpret_cast<float*>(&lds[0][0]);
-  const int idx0 = threadIdx.x;                      // G * kD >= 128 threads are busy; the rest idle through
-  const int h0 = min(idx0 / kD, G - 1), d0 = idx0 % kD;
-  float v0[8];
-#pragma unroll
-  for (int u = 0; u < 8; ++u) v0[u] = ld(&P.ws_o[((u0 + min(u, ns - 1)) * G + h0) * kD + d0]);
   for (int i = threadIdx.x; i < ns * G * 2; i += WAVES * 64) ml_sh[i] = ld(&P.ws_ml[u0 * G * 2 + i]);
   __syncthreads();
-  for (int idx = threadIdx.x; idx < G * kD; idx += WAVES * 64) {
+  for (int idx = threadIdx.x * 4; idx < G * kD; idx += WAVES * 64 * 4) {
     const int h = idx / kD, d = idx - h * kD;
     float mx = -1.0e30f;
     for (int sp = 0; sp < ns; ++sp) mx = fmaxf(mx, ml_sh[(sp * G + h) * 2]);
-    float o = 0.f, l = 0.f;
-    for (int sp0 = 0; sp0 < ns; sp0 += 8) {
-      float v[8];
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+    float l = 0.f;
+    for (int sp0 = 0; sp0 < ns; sp0 += 4) {
+      u32x4_t v[4];
+      const float* q[4];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {          // eight independent loads in flight
-        if (idx == idx0 && sp0 == 0) {
-          v[u] = v0[u];
-        } else {
-          int sp = min(sp0 + u, ns - 1);
-          v[u] = ld(&P.ws_o[((u0 + sp) * G + h) * kD + d]);
-        }
-      }
+      for (int u = 0; u < 4; ++u) q[u] = &P.ws_o[((u0 + min(sp0 + u, ns - 1)) * G + h) * kD + d];
+      load_device_4xb128(q[0], q[1], q[2], q[3], v);
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < 4; ++u) {
         if (sp0 + u < ns) {
-          float sc = __builtin_amdgcn_exp2f(ml_sh[((sp0 + u) * G + h) * 2] - mx);
-          o += v[u] * sc;
+          const float sc = __builtin_amdgcn_exp2f(ml_sh[((sp0 + u) * G + h) * 2] - mx);
+          const float4 r = __builtin_bit_cast(float4, v[u]);
+          o.x += r.x * sc; o.y += r.y * sc; o.z += r.z * sc; o.w += r.w * sc;
           l += ml_sh[((sp0 + u) * G + h) * 2 + 1] * sc;
         }
       }
     }
     const size_t hq = (size_t)bg * G + h;      // = b * Hq + g * G + h
-    out[hq * kD + d] = from_float<T>(o / l);
+    Vec<T, 4> r;
+    r.v[0] = from_float<T>(o.x / l); r.v[1] = from_float<T>(o.y / l);
+    r.v[2] = from_float<T>(o.z / l); r.v[3] = from_float<T>(o.w / l);
+    *reinterpret_cast<Vec<T, 4>*>(&out[hq * kD + d]) = r;
     if (P.lse && d == 0) P.lse[hq] = (mx + log2f(l)) * 0.6931471805599453f;
   }
 }
@@ -584,7 +582,7 @@ int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float s
   if ((int64_t)ns_eff * G * 2 > kWaves * kTile * 64) return fail(VT_ERR_UNSUPPORTED, "vt_decode_attn: too many splits");
   const size_t need = ticket_bytes(B, Hq) + (size_t)B * Hq * ns_eff * ((size_t)kD + 2) * sizeof(float);
   if (workspace_bytes < need) return fail(VT_ERR_INVALID_ARG, "vt_decode_attn: workspace too small");
-  if ((uintptr_t)workspace % 16 || (uintptr_t)out % 2) return fail(VT_ERR_INVALID_ARG, "vt_decode_attn: misaligned workspace or out");
+  if ((uintptr_t)workspace % 16 || (uintptr_t)out % 8) return fail(VT_ERR_INVALID_ARG, "vt_decode_attn: misaligned workspace or out (16 and 8 bytes)");
   P.B = (int)B;
   P.Hkv = Hkv;
   P.G = (int)G;
