@@ -351,25 +351,44 @@ k_decode_attn(const AttnParams P) {
   T* out = static_cast<T*>(P.out);
   auto ld = [](const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
   // (m, l) of every split and head go to LDS (ns * G * 2 contiguous floats; the K tiles' LDS is
-  // free now); each thread then merges four consecutive d of one head, reading the splits'
-  // partial outputs with 16-byte device-coherent loads, four in flight
+  // free now).  Each thread merges four consecutive d of one head; the first eight splits'
+  // partial outputs are requested in the same breath as (m, l), with 16-byte device-coherent
+  // loads, so that the merge costs one memory round trip, not two.
   float* ml_sh = reinterpret_cast<float*>(&lds[0][0]);
-  for (int i = threadIdx.x; i < ns * G * 2; i += WAVES * 64) ml_sh[i] = ld(&P.ws_ml[u0 * G * 2 + i]);
+  const int idx0 = threadIdx.x * 4;                   // G * kD / 4 >= 32 threads are busy; the rest idle through
+  const int h0 = min(idx0 / kD, G - 1), d0 = idx0 % kD;
+  const int i_ml = threadIdx.x;                       // ns * G * 2 <= 256 * 32 ... a thread may own several
+  float ml_first = 0.f;
+  if (i_ml < ns * G * 2) ml_first = ld(&P.ws_ml[u0 * G * 2 + i_ml]);
+  u32x4_t v0[8];
+  {
+    const void* q[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) q[u] = &P.ws_o[((u0 + min(u, ns - 1)) * G + h0) * kD + d0];
+    load_device_8xb128(q, v0);
+  }
+  if (i_ml < ns * G * 2) ml_sh[i_ml] = ml_first;
+  for (int i = i_ml + WAVES * 64; i < ns * G * 2; i += WAVES * 64) ml_sh[i] = ld(&P.ws_ml[u0 * G * 2 + i]);
   __syncthreads();
-  for (int idx = threadIdx.x * 4; idx < G * kD; idx += WAVES * 64 * 4) {
+  for (int idx = idx0; idx < G * kD; idx += WAVES * 64 * 4) {
     const int h = idx / kD, d = idx - h * kD;
     float mx = -1.0e30f;
     for (int sp = 0; sp < ns; ++sp) mx = fmaxf(mx, ml_sh[(sp * G + h) * 2]);
     float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
     float l = 0.f;
-    for (int sp0 = 0; sp0 < ns; sp0 += 4) {
-      u32x4_t v[4];
-      const float* q[4];
+    for (int sp0 = 0; sp0 < ns; sp0 += 8) {
+      u32x4_t v[8];
+      if (idx == idx0 && sp0 == 0) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) q[u] = &P.ws_o[((u0 + min(sp0 + u, ns - 1)) * G + h) * kD + d];
-      load_device_4xb128(q[0], q[1], q[2], q[3], v);
+        for (int u = 0; u < 8; ++u) v[u] = v0[u];
+      } else {
+        const void* q[8];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < 8; ++u) q[u] = &P.ws_o[((u0 + min(sp0 + u, ns - 1)) * G + h) * kD + d];
+        load_device_8xb128(q, v);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
         if (sp0 + u < ns) {
           const float sc = __builtin_amdgcn_exp2f(ml_sh[((sp0 + u) * G + h) * 2] - mx);
           const float4 r = __builtin_bit_cast(float4, v[u]);
