@@ -58,8 +58,10 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 struct AttnSeg {
   const char* k;         // K element (b=0, g=0, t=t_lo, d=0)
   const char* v;
-  int64_t k_sb, k_sh, v_sb, v_sh;   // bytes per batch / per kv head
+  int64_t k_sb, k_sh, v_sb, v_sh;   // bytes per batch / per stored head
   uint32_t k_st, v_st;              // bytes per context row
+  int32_t k_hdiv, v_hdiv;           // head group g reads stored head g / hdiv (1 unless this operand is
+                                    // broadcast over more heads than the group size G both operands share)
   int32_t t_lo, t_hi;
 };
 struct AttnParams {
@@ -189,7 +191,7 @@ k_decode_attn(const AttnParams P) {
   auto issue_k = [&](const TilePos& tp) {
     const AttnSeg& sg = P.seg[tp.seg];
     const uint32_t st = sg.k_st;
-    const char* kb = sg.k + b * sg.k_sb + g * sg.k_sh + (int64_t)(tp.r0 - sg.t_lo) * st;
+    const char* kb = sg.k + b * sg.k_sb + (g / sg.k_hdiv) * sg.k_sh + (int64_t)(tp.r0 - sg.t_lo) * st;
     if (tp.r0 + kTile <= tp.end) {
       const uint32_t off = lg * st + l16 * 16;
 #pragma unroll
@@ -203,7 +205,7 @@ k_decode_attn(const AttnParams P) {
   auto issue_v = [&](const TilePos& tp) {
     const AttnSeg& sg = P.seg[tp.seg];
     const uint32_t st = sg.v_st;
-    const char* vb = sg.v + b * sg.v_sb + g * sg.v_sh + (int64_t)(tp.r0 - sg.t_lo) * st;
+    const char* vb = sg.v + b * sg.v_sb + (g / sg.v_hdiv) * sg.v_sh + (int64_t)(tp.r0 - sg.t_lo) * st;
     if (tp.r0 + kTile <= tp.end) {
       const uint32_t off = lg * 4 * st + l16 * 16;
 #pragma unroll
@@ -417,16 +419,20 @@ struct HeadMap {
   int64_t G;        // query heads per kv head (trailing broadcast digits)
 };
 
+// A digit group that acts as ONE strided digit: a single plain digit, or several that nest
+// densely (each stride = the next stride x the next radix, as a reshape of a dense buffer
+// leaves them).
 bool single_plain(const std::vector<Digit>& g, int64_t* stride) {
   if (g.empty()) {
     *stride = 0;
     return true;
   }
-  if (g.size() == 1 && g[0].table < 0) {
-    *stride = g[0].stride;
-    return true;
+  for (size_t i = 0; i < g.size(); ++i) {
+    if (g[i].table >= 0) return false;
+    if (i + 1 < g.size() && g[i].stride != g[i + 1].stride * g[i + 1].radix) return false;
   }
-  return false;
+  *stride = g.back().stride;
+  return true;
 }
 
 // Trailing zero-stride digits of the head group = heads that share rows.
@@ -439,6 +445,7 @@ int64_t broadcast_factor(const std::vector<Digit>& g) {
 struct PlanPiece {
   const char* ptr;
   int64_t sb, sh;
+  int32_t hdiv;
   uint32_t st;
   int32_t t_lo, t_hi;
 };
@@ -468,6 +475,7 @@ int plan_operand(const vt_desc& d, const char* name, int64_t G, AttnOperand* out
     if (sd != 1) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": rows must be contiguous along the head dim");
     // head group: [kv heads (stride sh)] x [G broadcast]
     std::vector<Digit> hg = p.v.groups[1];
+    int32_t a_hdiv = 1;
     int64_t left = G;
     while (left > 1) {
       if (hg.empty() || hg.back().stride != 0 || hg.back().table >= 0 || (left % hg.back().radix != 0 && hg.back().radix % left != 0))
@@ -480,11 +488,21 @@ int plan_operand(const vt_desc& d, const char* name, int64_t G, AttnOperand* out
         left = 1;
       }
     }
+    // heads this operand still shares beyond G (the other operand is broadcast less, or not at
+    // all: the group size is the factor common to both): consecutive groups read one stored head
+    int64_t hdiv = 1;
+    while (!hg.empty() && hg.back().stride == 0 && hg.back().table < 0) {
+      hdiv *= hg.back().radix;
+      hg.pop_back();
+    }
+    if (hdiv >= (1ll << 31)) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": head broadcast too wide");
+    a_hdiv = (int32_t)hdiv;
     int64_t sh;
     if (!single_plain(hg, &sh)) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": kv-head dim must be one strided digit");
     const vt_source& src = d.sources[p.src];
     if (!src.ptr) return fail(VT_ERR_INVALID_ARG, std::string(name) + ": source without a device pointer");
     PlanPiece& a = out->pc[i];
+    a.hdiv = a_hdiv;
     a.ptr = static_cast<const char*>(src.ptr) + p.v.base * esz;
     a.sb = sb * esz;
     a.sh = sh * esz;
@@ -571,8 +589,8 @@ int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float s
       AttnSeg& sg = P.seg[n++];
       sg.k = ko.pc[ik].ptr + (int64_t)(t - ko.pc[ik].t_lo) * ko.pc[ik].st;
       sg.v = vo.pc[iv].ptr + (int64_t)(t - vo.pc[iv].t_lo) * vo.pc[iv].st;
-      sg.k_sb = ko.pc[ik].sb; sg.k_sh = ko.pc[ik].sh; sg.k_st = ko.pc[ik].st;
-      sg.v_sb = vo.pc[iv].sb; sg.v_sh = vo.pc[iv].sh; sg.v_st = vo.pc[iv].st;
+      sg.k_sb = ko.pc[ik].sb; sg.k_sh = ko.pc[ik].sh; sg.k_st = ko.pc[ik].st; sg.k_hdiv = ko.pc[ik].hdiv;
+      sg.v_sb = vo.pc[iv].sb; sg.v_sh = vo.pc[iv].sh; sg.v_st = vo.pc[iv].st; sg.v_hdiv = vo.pc[iv].hdiv;
       sg.t_lo = t;
       sg.t_hi = e;
       t = e;

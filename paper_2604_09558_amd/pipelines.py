@@ -274,3 +274,134 @@ def choose_path(dw: DeviceWorkload, iters=20, warmup=3, unit_bytes=0, **kw):
     report.update(virtual_us=tv, materialized_us=tm, saving_us=tm - tv, measured=True,
                   choice="virtual" if tm - tv > 0 else "materialized")
     return (virt if tm - tv > 0 else mat), report
+
+
+# ------------------------------------------------------------------------------------------
+# A workload run under an arbitrary strategy of virtual tensors (Sec. 5): what the greedy search
+# of vtog.py measures, and what it finally keeps
+# ------------------------------------------------------------------------------------------
+class StrategyPipeline:
+    """`chosen` maps tensor names to read-direction opportunities (vtog.Opportunity): those
+    tensors are virtual.  Every other intermediate the consumer depends on is physical and is
+    produced by one copy kernel that reads through the descriptor of the eliminated operators
+    above it; the consumer reads its operands through descriptors over the nearest physical
+    tensors.  With `chosen` empty this is the fully materialized path, with every tensor chosen
+    the fully virtual one."""
+
+    def __init__(self, dw: DeviceWorkload, chosen, **kw):
+        from . import vtog
+        wl = dw.wl
+        self.dw = dw
+        stmts = list(wl.chain)
+        produced = {}
+        for k, st in enumerate(stmts):
+            for o in vtog.outputs_of(st):
+                produced[o] = k
+        self.consumer = make_pipeline(dw, materialized=False, **kw)
+        operands = self._operand_names()
+        self.bufs = {n: t for n, t in dw.tensors.items()}
+        self.shapes = {n: tuple(t.shape) for n, t in dw.tensors.items()}
+        self.copies = []           # (descriptor, destination buffer) in statement order
+        self.bytes_written = 0
+        read_opp = {}
+        for st_i, st in enumerate(stmts):
+            for o in vtog.outputs_of(st):
+                read_opp[o] = vtog.Opportunity(o, tuple(i for i in st[2] if isinstance(i, str)), st_i, "read")
+        done = set()
+
+        def ensure(t):
+            """make sure tensor t (a physical intermediate) has a buffer and a copy that fills it"""
+            if t in done or t not in produced:
+                return
+            done.add(t)
+            forced = dict(chosen)
+            forced[t] = read_opp[t]
+            chain, sources = vtog.read_chain(stmts, forced, t)
+            for s in sources:
+                ensure(s)
+            d = self._build(chain, sources, t)
+            self.shapes[t] = d.shape
+            self.bufs[t] = torch.empty(d.shape, dtype=TORCH_DTYPE[wl.dtype], device=dw.device)
+            self.bytes_written += self.bufs[t].numel() * self.bufs[t].element_size()
+            self.copies.append((produced[t], d, self.bufs[t]))
+
+        descs = []
+        for name in operands:
+            chain, sources = vtog.read_chain(stmts, chosen, name)
+            for s in sources:
+                ensure(s)
+            descs.append(self._build(chain, sources, name))
+        self.copies.sort(key=lambda c: c[0])
+        self._set_operands(descs)
+
+    def _build(self, chain, sources, result):
+        wl = self.dw.wl
+        specs = {s: (self.shapes[s], wl.dtype, self.bufs[s].data_ptr()) for s in sources}
+        return vt.build_chain(chain, specs, result, wl.index_tables, self.dw.table_ptrs())
+
+    def _operand_names(self):
+        c = self.dw.wl.consumer
+        kind = c["kind"]
+        if kind == "add_rowsum":
+            return [c["x"], c["y"]]
+        if kind == "decode_attn":
+            return [c["q"], c["k"], c["v"]]
+        if kind == "grouped_gemm":
+            return list(c["a"]) + list(c["b"])
+        if kind == "ln_linear":
+            return [c["x"], c["w"]]
+        return [c["a"], c["b"]]
+
+    def _set_operands(self, descs):
+        p = self.consumer
+        if isinstance(p, AddRowsum):
+            p.x, p.y = descs
+        elif isinstance(p, DecodeAttention):
+            p.q, p.k, p.v = descs
+        else:
+            n = len(p.A)
+            p.A, p.B = descs[:n], descs[n:]
+        self.out = getattr(p, "out", None)
+
+    def run(self, stream=None):
+        for _, d, buf in self.copies:
+            vt.vt_materialize(d, buf, stream=stream)
+        return self.consumer.run(stream)
+
+
+def greedy_strategy(dw: DeviceWorkload, iters=10, warmup=2, **kw):
+    """Alg. 2 with w(e) measured on the GPU: builds the opportunity graph of the workload's chain
+    (read direction: the consumer-side opportunities this library can lower), times the workload
+    under each candidate strategy, and returns (chosen, report)."""
+    from . import vtog
+    wl = dw.wl
+    c = wl.consumer
+    g = vtog.build_vtog(list(wl.chain), tuple(wl.sources), (), directions=("read",))
+    times = {}
+
+    def latency(chosen):
+        key = frozenset((t, o.op_index) for t, o in chosen.items())
+        if key not in times:
+            try:
+                p = StrategyPipeline(dw, chosen, **kw)
+                times[key] = time_pipeline(p, iters, warmup)
+                del p
+            except vt.VtError as e:
+                # a layout the consumer kernel does not take is not an opportunity on this machine
+                if e.code != vt.ERR_UNSUPPORTED:
+                    raise
+                times[key] = float("inf")
+            torch.cuda.empty_cache()
+        return times[key]
+
+    def profile(o, chosen):
+        grown = dict(chosen)
+        grown[o.tensor] = o
+        t0, t1 = latency(chosen), latency(grown)
+        return float("-inf") if t1 == float("inf") else t0 - t1
+
+    chosen, total, trace = vtog.greedy(g, profile)
+    report = {"all_physical_us": latency({}), "chosen_us": latency(chosen), "saving_us": total,
+              "virtual_tensors": [o.tensor for o, _ in trace], "strategies_timed": len(times),
+              "opportunities": len(g.opportunities)}
+    return chosen, report

@@ -133,3 +133,25 @@ def test_repeated_launches_are_deterministic(gpu):
         assert bad == 0, (ns, bad)
     ref = run_workload(wl)
     check(tio.to_host_f64(first), ref["out"])
+
+
+def test_one_operand_broadcast_and_the_other_dense(gpu):
+    """K read through the map (4 query heads share a row) while V is a dense expanded copy, and
+    the reverse: the head group shrinks to what both share and the broadcast operand maps several
+    groups onto one stored head."""
+    vt, tio, pipelines, torch = gpu
+    wl = workloads.c2_decode_attention(seed=7, B=2, Hkv=2, G=4, S=300, D=128)
+    ref = run_workload(wl)["out"]
+    dw = tio.DeviceWorkload(wl)
+    pm = pipelines.DecodeAttention(dw, materialized=True)
+    pm.run()
+    torch.cuda.synchronize()
+    for mixed in ("k_virtual", "v_virtual"):
+        p = pipelines.DecodeAttention(dw, materialized=False)
+        if mixed == "k_virtual":
+            p.v = pm.v
+        else:
+            p.k = pm.k
+        p.run()
+        torch.cuda.synchronize()
+        check(tio.to_host_f64(p.out), ref)

@@ -1,0 +1,143 @@
+"""Opportunity graph (Alg. 1) and greedy points-to graph construction (Alg. 2): the paper's
+worked examples, and the greedy result against exhaustive search on small graphs."""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import strategy_search
+from paper_2604_09558_amd import vtog
+
+
+# Fig. 5: a = MatMul(x, w); b = Split(a)[k part]; c = Reshape(b); d = ScatterND(Kcache, idx, c); y = Attention(q, d)
+FIG5 = [
+    ("a", "matmul", ("x", "w"), {}),
+    (("b", "b_other"), "split", ("a",), {"dim": 1, "sizes": (4, 4)}),
+    ("c", "reshape", ("b",), {"shape": (2, 2, 2)}),
+    ("d", "scatter_nd", ("Kcache", "idx", "c"), {}),
+    ("y", "attention", ("q", "d"), {}),
+]
+FIG5_IN, FIG5_OUT = ("x", "w", "Kcache", "idx", "q"), ("y",)
+
+
+def bundles_of(g):
+    return {t: [o.targets for o in opps] for t, opps in g.by_tensor.items()}
+
+
+def test_fig5_opportunity_graph():
+    g = vtog.build_vtog(FIG5, FIG5_IN, FIG5_OUT)
+    edges = set(g.edges)
+    # Split gives the edges between a and b, Reshape between b and c, ScatterND between c, d and the K cache
+    assert {("b", "a"), ("c", "b"), ("b", "c"), ("c", "d"), ("d", "Kcache")} <= edges
+    assert ("a", "b") in edges and ("a", "b_other") in edges          # the split's input stitched from its outputs
+    # inputs and outputs of the graph stay physical: no edge leaves them
+    assert not any(s in FIG5_IN + FIG5_OUT for s, _ in edges)
+    assert set(g.nodes) >= {"a", "b", "c", "d", "Kcache", "y"}
+    # the conflict set: a tensor can take one bundle only
+    assert len(g.by_tensor["b"]) == 2 and len(g.by_tensor["c"]) == 2
+
+
+def test_fig7_strategies_are_points_to_graphs_and_conflicts_are_not():
+    g = vtog.build_vtog(FIG5, FIG5_IN, FIG5_OUT)
+    pick = lambda t, targets: next(o for o in g.by_tensor[t] if o.targets == targets)   # noqa: E731
+    s3 = {}
+    s2 = {"a": pick("a", ("b", "b_other")), "c": pick("c", ("b",)), "d": pick("d", ("Kcache",))}
+    s1 = {"a": pick("a", ("b", "b_other")), "b": pick("b", ("c",)), "c": pick("c", ("d",)), "d": pick("d", ("Kcache",))}
+    for s in (s1, s2, s3):
+        assert vtog.is_points_to_graph(g, s)
+        assert strategy_search.valid({t: o.targets for t, o in s.items()})
+    # b virtual of c and c virtual of b at once: a cycle, nobody holds the data
+    bad = {"b": pick("b", ("c",)), "c": pick("c", ("b",))}
+    assert not vtog.is_points_to_graph(g, bad)
+    assert not strategy_search.valid({t: o.targets for t, o in bad.items()})
+
+
+def test_greedy_reaches_strategy_1_when_every_elimination_pays():
+    g = vtog.build_vtog(FIG5, FIG5_IN, FIG5_OUT)
+    # every eliminated operator saves its copy (1 unit); the Type II store into the split's outputs costs more than it saves
+    w = lambda o, chosen: -0.5 if (o.tensor == "a") else 1.0     # noqa: E731
+    chosen, total, trace = vtog.greedy(g, w)
+    assert vtog.is_points_to_graph(g, chosen)
+    assert {t: o.targets for t, o in chosen.items()} == {"d": ("Kcache",), "c": ("d",), "b": ("c",)}
+    assert total == 3.0 and [o.tensor for o, _ in trace] == ["d", "c", "b"]      # anchors grow outwards from the K cache
+    # and stops at once when nothing pays
+    chosen, total, _ = vtog.greedy(g, lambda o, c: -1.0)
+    assert chosen == {} and total == 0.0
+
+
+def random_graph(seed):
+    """A small DAG of data-movement statements over two inputs, consumed by one compute operator."""
+    rng = np.random.default_rng(seed)
+    tensors, stmts = ["x0", "x1"], []
+    for k in range(int(rng.integers(3, 6))):
+        op = ["reshape", "permute", "slice", "concat", "expand"][int(rng.integers(0, 5))]
+        out = "t%d" % k
+        if op == "concat":
+            ins = tuple(rng.choice(tensors, size=2, replace=False))
+        else:
+            ins = (str(rng.choice(tensors)),)
+        stmts.append((out, op, tuple(str(i) for i in ins), {}))
+        tensors.append(out)
+    used = {i for _, _, ins, _ in stmts for i in ins}
+    leaves = [t for t in tensors[2:] if t not in used] or [tensors[-1]]
+    stmts.append(("y", "compute", tuple(leaves), {}))
+    return stmts, ("x0", "x1"), ("y",)
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_greedy_is_valid_and_never_beats_exhaustive_search(seed):
+    stmts, gin, gout = random_graph(seed)
+    g = vtog.build_vtog(stmts, gin, gout)
+    rng = np.random.default_rng(1000 + seed)
+    weight = {(o.tensor, o.targets): float(rng.normal(0.3, 1.0)) for o in g.opportunities}
+    # an additive saving function: l(C) = sum of the weights of the chosen bundles
+    chosen, total, _ = vtog.greedy(g, lambda o, c: weight[(o.tensor, o.targets)])
+    assert vtog.is_points_to_graph(g, chosen)
+    as_plain = {t: o.targets for t, o in chosen.items()}
+    assert strategy_search.valid(as_plain)
+    saving = lambda c: sum(weight[(t, tg)] for t, tg in c.items())      # noqa: E731
+    assert abs(total - saving(as_plain)) < 1e-12
+    best, best_s, n = strategy_search.best_strategy(bundles_of(g), saving)
+    assert n >= 1 and total <= best_s + 1e-12
+    assert total >= 0.0
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_greedy_is_optimal_on_chains(seed):
+    """One bundle per tensor (read direction only, a chain): greedy takes exactly the bundles with
+    a positive saving that can be grounded, which is the optimum of an additive saving."""
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(2, 7))
+    stmts = [("t%d" % k, "reshape", ("t%d" % (k - 1) if k else "x",), {}) for k in range(n)] + [("y", "compute", ("t%d" % (n - 1),), {})]
+    g = vtog.build_vtog(stmts, ("x",), ("y",), directions=("read",))
+    weight = {o.tensor: float(rng.normal(0.0, 1.0)) for o in g.opportunities}
+    chosen, total, _ = vtog.greedy(g, lambda o, c: weight[o.tensor])
+    saving = lambda c: sum(weight[t] for t in c)                      # noqa: E731
+    best, best_s, _ = strategy_search.best_strategy(bundles_of(g), saving)
+    # greedy stops at the first negative maximum; on a chain every tensor becomes eligible in order
+    # from the input, so it may stop before a later positive one: it is optimal when savings are all positive
+    assert total <= best_s + 1e-12
+    if all(v > 0 for v in weight.values()):
+        assert abs(total - best_s) < 1e-12 and len(chosen) == n
+
+
+def test_exhaustive_search_counts_strategies_of_a_known_case():
+    # two tensors that may point at each other or at a physical one: p->q, q->p, p->X
+    bundles = {"p": [("q",), ("X",)], "q": [("p",)]}
+    all_s = list(strategy_search.all_strategies(bundles))
+    # 3 x 2 assignments minus the cycle {p->q, q->p}
+    assert len(all_s) == 5
+    assert {"p": ("q",), "q": ("p",)} not in all_s
+
+
+def test_read_chain_extraction():
+    stmts = [("a", "slice", ("X",), {}), ("b", "permute", ("a",), {}), ("c", "reshape", ("b",), {}), ("y", "compute", ("c",), {})]
+    g = vtog.build_vtog(stmts, ("X",), ("y",), directions=("read",))
+    pick = lambda t: g.by_tensor[t][0]      # noqa: E731
+    # b physical, c virtual of b: the consumer's descriptor composes only the reshape, reading b
+    chain, sources = vtog.read_chain(stmts, {"c": pick("c")}, "c")
+    assert [s[0] for s in chain] == ["c"] and sources == ["b"]
+    chain, sources = vtog.read_chain(stmts, {"a": pick("a"), "b": pick("b"), "c": pick("c")}, "c")
+    assert [s[0] for s in chain] == ["a", "b", "c"] and sources == ["X"]
+    chain, sources = vtog.read_chain(stmts, {}, "c")
+    assert chain == [] and sources == ["c"]
