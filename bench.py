@@ -54,7 +54,7 @@ def parse():
     ap.add_argument("--context", type=int, default=4096, help="context length (the benchmark's is 4096; others are for tuning)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 128 MiB -> 128 MiB copy kernel 20 times (reference point for HBM byte counters)")
-    ap.add_argument("--extra", default="", help="comma list of further chains to time (c1,c3,c4,c5,qkv_store)")
+    ap.add_argument("--extra", default="", help="comma list of further chains to time (c1,c3,c4,c5,qkv_store,decode_segment)")
     return ap.parse_args()
 
 
@@ -126,6 +126,26 @@ def chain_stats(torch, name, steps):
     import workloads
     from paper_2604_09558_amd import pipelines
     from paper_2604_09558_amd import torch_io as tio
+    if name == "decode_segment":
+        # projection with a producer-side store + attention on the caches it wrote (Sec. 3.1)
+        mk = lambda p: (lambda stream: p.run(stream))      # noqa: E731
+        segs = [pipelines.DecodeSegment(*workloads.decode_segment(seed=s)) for s in range(4)]
+        torch.cuda.synchronize()
+        v_wall, v_ev = time_steps(torch, [mk(p) for p in segs], steps, max(2, steps // 10), True)
+        M, N, K = segs[0].store.shape
+        B, Hq, S, D = segs[0].attn.k.shape
+        alg = (K * N + M * K + M * N) * 2 + 2 * B * (Hq // 4) * S * D * 2 + 2 * B * Hq * D * 2
+        out = {"virtual_us": round(v_ev * 1e3, 2), "algorithmic_bytes": int(alg),
+               "hbm_pct_of_peak": round(100.0 * alg / (v_ev * 1e-3) / 1e9 / HBM_PEAK_GBS, 1)}
+        del segs
+        torch.cuda.empty_cache()
+        mat = pipelines.DecodeSegment(*workloads.decode_segment(seed=0), materialized=True)
+        torch.cuda.synchronize()
+        m_wall, m_ev = time_steps(torch, [mk(mat)], max(5, steps // 8), 2, False)
+        out["materialized_full_us"] = round(m_ev * 1e3, 2)
+        out["speedup_vs_materialized_full"] = round(m_ev / v_ev, 2)
+        out["intermediate_bytes_saved"] = int(mat.attn.mat.bytes_written + M * N * 2)
+        return out
     copies = {"c1": 1, "c3": 3, "c4": 6, "c5": 1, "qkv_store": 6}[name]
     wls = [workloads.CONFIGS[name](seed=s) for s in range(copies)]
     dws = [tio.DeviceWorkload(w) for w in wls]
@@ -263,7 +283,7 @@ def main():
         torch.cuda.empty_cache()
         out["chains"] = {}
         for name in a.extra.split(","):
-            out["chains"][name] = chain_stats(torch, name, {"c1": 200, "c3": 30, "c4": 100, "c5": 6, "qkv_store": 200}[name])
+            out["chains"][name] = chain_stats(torch, name, {"c1": 200, "c3": 30, "c4": 100, "c5": 6, "qkv_store": 200, "decode_segment": 120}[name])
             torch.cuda.empty_cache()
 
     if not a.no_cpu_baseline:

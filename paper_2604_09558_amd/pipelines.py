@@ -217,6 +217,24 @@ class GemmStore:
         return None
 
 
+class DecodeSegment:
+    """Projection with a producer-side store followed by decode attention on the same buffers
+    (Sec. 3.1 end to end).  virtual: two launches (vt_gemm_store, vt_decode_attn), no data
+    movement operator is executed.  materialized: dense product + scatter, then every operator
+    between the caches and the attention kernel as a copy."""
+
+    def __init__(self, wl_store, wl_attn, materialized=False, device="cuda:0"):
+        self.dw1 = DeviceWorkload(wl_store, device)
+        self.dw2 = DeviceWorkload(wl_attn, device, share=self.dw1)
+        self.store = GemmStore(self.dw1, materialized)
+        self.attn = DecodeAttention(self.dw2, materialized)
+        self.out, self.lse = self.attn.out, self.attn.lse
+
+    def run(self, stream=None):
+        self.store.run(stream)
+        return self.attn.run(stream)
+
+
 def make_pipeline(dw: DeviceWorkload, materialized=False, **kw):
     if dw.wl.consumer["kind"] == "gemm_store":
         return GemmStore(dw, materialized)

@@ -35,10 +35,13 @@ class DeviceWorkload:
     """Sources and index tables of a workload resident on the GPU, plus the specs the
     descriptor builder needs (shape, dtype, device address)."""
 
-    def __init__(self, wl, device="cuda:0"):
+    def __init__(self, wl, device="cuda:0", share=None):
+        """`share`: another DeviceWorkload whose device tensors are used for the sources of the
+        same name (two stages of one pipeline working on the same buffers)."""
         self.wl = wl
         self.device = device
-        self.tensors = {k: to_device(v, wl.dtype, device) for k, v in wl.sources.items()}
+        shared = share.tensors if share is not None else {}
+        self.tensors = {k: shared[k] if k in shared else to_device(v, wl.dtype, device) for k, v in wl.sources.items()}
         self.tables = {k: torch.from_numpy(np.ascontiguousarray(v, dtype=np.int32)).to(device)
                        for k, v in wl.index_tables.items()}
 

@@ -113,3 +113,43 @@ def test_store_rejects_maps_that_are_not_one_to_one(gpu):
     assert ei.value.code == vt.ERR_NOT_ONE_TO_ONE
     torch.cuda.synchronize()
     assert float(small.float().abs().sum()) == 0.0
+
+
+def oracle_segment(st1, st2):
+    """Stage 1 on the CPU, its stored tensors handed to stage 2."""
+    r1 = run_workload(st1)
+    st2.sources = {k: r1["stored"][k] for k in st2.sources}
+    return r1, run_workload(st2)
+
+
+@pytest.mark.parametrize("B,hidden,Hkv,G,cap,pos", [(2, 256, 2, 4, 64, 37), (3, 512, 1, 8, 300, 299)])
+def test_decode_segment_small(gpu, B, hidden, Hkv, G, cap, pos):
+    """Projection stores Q and the new K/V rows, attention reads slots 0..pos of the caches: the
+    new token's row must be the one the projection just wrote (a stale row would show)."""
+    vt, tio, pipelines, torch = gpu
+    st1, st2 = workloads.decode_segment(seed=4, B=B, hidden=hidden, Hkv=Hkv, G=G, D=128, cap=cap, pos=pos)
+    p = pipelines.DecodeSegment(st1, st2)
+    pm = pipelines.DecodeSegment(st1, st2, materialized=True)
+    r1, r2 = oracle_segment(st1, st2)
+    for q in (p, pm):
+        q.run()
+        torch.cuda.synchronize()
+        compare_stored(tio, q.dw1, st1, r1)
+        got = tio.to_host_f64(q.out)
+        assert (np.abs(got - r2["out"]) <= 1e-2 + 1e-2 * np.abs(r2["out"])).all()
+    # the oracle's stage 2 really depends on stage 1: with the caches as they were before the store it differs
+    st2.sources = {k: st1.sources[k] for k in st2.sources}
+    assert np.abs(run_workload(st2)["out"] - r2["out"]).max() > 1e-3
+
+
+def test_decode_segment_full_size(gpu):
+    vt, tio, pipelines, torch = gpu
+    st1, st2 = workloads.decode_segment()
+    p = pipelines.DecodeSegment(st1, st2)
+    r1, r2 = oracle_segment(st1, st2)
+    p.run()
+    torch.cuda.synchronize()
+    compare_stored(tio, p.dw1, st1, r1)
+    got = tio.to_host_f64(p.out)
+    err = np.abs(got - r2["out"])
+    assert (err <= 1e-2 + 1e-2 * np.abs(r2["out"])).all(), err.max()

@@ -18,6 +18,7 @@ from .inputs import (  # noqa: F401
     c4_window_ln_linear,
     c5_moe_dispatch,
     qkv_proj_store,
+    decode_segment,
     qkv_store_chain,
     random_chain,
     CONFIGS,

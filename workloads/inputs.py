@@ -241,6 +241,30 @@ def qkv_proj_store(seed: int = 0, B: int = 8, hidden: int = 4096, Hq: int = 32, 
                     {"kind": "gemm_store", "a": "X", "b": "W", "out": "Cout"})
 
 
+def decode_segment(seed: int = 0, B: int = 8, hidden: int = 4096, Hkv: int = 8, G: int = 4, D: int = 128,
+                   cap: int = 4096, pos: int = 4095, dtype: str = "bf16"):
+    """The paper's motivating example end to end (Sec. 3.1): the merged QKV projection stores Q
+    and the new K, V rows through a virtual tensor (stage 1), then decode attention reads the Q
+    buffer and slots 0..pos of the un-expanded caches (stage 2).  Returns the two workloads; they
+    name the same Qbuf / Kcache / Vcache, stage 2 sees what stage 1 stored."""
+    Hq = Hkv * G
+    S = pos + 1
+    st1 = qkv_proj_store(seed, B, hidden, Hq, Hkv, D, cap, pos, 1, dtype)
+    chain = [("q1", "reshape", ("Qbuf",), {"shape": (B, 1, Hq, D)}),
+             ("Q", "permute", ("q1",), {"perm": (0, 2, 1, 3)})]
+    for nm, cache in (("k", "Kcache"), ("v", "Vcache")):
+        chain += [
+            (nm + "s", "slice", (cache,), {"dim": 2, "start": 0, "stop": S, "step": 1}),
+            (nm + "u", "unsqueeze", (nm + "s",), {"dim": 2}),
+            (nm + "x", "expand", (nm + "u",), {"shape": (B, Hkv, G, S, D)}),
+            (nm.upper(), "reshape", (nm + "x",), {"shape": (B, Hq, S, D)}),
+        ]
+    src2 = {k: st1.sources[k] for k in ("Qbuf", "Kcache", "Vcache")}
+    st2 = Workload("decode_segment_attention", dtype, src2, chain,
+                   {"kind": "decode_attn", "q": "Q", "k": "K", "v": "V", "scale": 1.0 / float(np.sqrt(D))})
+    return st1, st2
+
+
 CONFIGS = {
     "c1": c1_tiny_chain,
     "c2": c2_decode_attention,
