@@ -4,9 +4,9 @@
 //
 // Tiling: one workgroup of 4 waves computes a 256 x 256 tile of C over K in steps of 64; each
 // wave owns a 128 x 128 quadrant (4 x 4 MFMA blocks, 256 accumulator registers per lane).
-// Both operands are staged in LDS with the contraction index contiguous ([row][k] and
-// [col][k], 16-byte units, XOR-swizzled) so that every fragment is one conflict-free
-// ds_read_b128 in the matrix-core operand layout; LDS is double buffered, one barrier per step.
+// A is staged in LDS with the contraction index contiguous ([row][k], 16-byte units,
+// XOR-swizzled: a fragment is one conflict-free ds_read_b128 in the matrix-core operand layout),
+// B as [k][n] with padded rows; LDS is double buffered, one barrier per step.
 //
 // Stage 1 through the map (block-wise virtual tensor I/O): the map of a 2-D operand separates
 // into row_offset(m) + col_offset(k).  A thread keeps the offsets of its 8 rows for the whole
@@ -14,9 +14,9 @@
 // evaluates the column offset of its 8-element chunk once per step.  Global loads stay
 // 16 bytes per lane and cover whole 128-byte lines whenever the map keeps runs of 64 elements.
 //   A ([M,K], K contiguous in runs of >= 8): chunk -> LDS directly.
-//   B ([K,N], N contiguous, the usual row-major weight): each thread loads an 8 (k) x 8 (n)
-//     block with 8 row loads, transposes it in registers (v_perm_b32) and writes 8 k-contiguous
-//     units, so B arrives in LDS as B^T without any strided access.
+//   B ([K,N], N contiguous, the usual row-major weight): rows go to LDS as they are loaded
+//     ([k][n], 16 bytes per lane); the transposition into the operand layout (8 consecutive k
+//     per lane) is done by the LDS itself on the way out (ds_read_b64_tr_b16, two per fragment).
 // Workgroup ids are remapped so that each XCD (own L2) works on a contiguous band of tiles,
 // walked in groups of 8 tile rows, which keeps the A and B panels of neighbouring tiles in
 // that L2.  A launch covers up to 8 groups (grouped GEMM: one tile list over all groups).
@@ -36,6 +36,7 @@ namespace {
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int kMaxGroups = 8;
 constexpr int kGroupRows = 8;      // tile rows walked together (L2 reuse of the B panel)
+constexpr int kBPitch = BN * 2 + 64;   // bytes between k-rows of the B tile in LDS
 
 struct GemmGroup {
   const char* a;
@@ -43,7 +44,8 @@ struct GemmGroup {
   char* c;
   AxisMap<5> a_row;
   AxisMap<3> a_col, b_row, b_col;
-  int32_t M, tile_begin, tiles_m, pad;
+  int32_t M, tile_begin, tiles_m;
+  int32_t k64;   // a K step of 64 never leaves the innermost K digit of A or of B: the step's offset is uniform
 };
 
 struct GemmParams {
@@ -56,7 +58,9 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P) {
   typedef Mma<T> M_;
   typedef typename M_::vec opvec;
   __shared__ uint4 ldsA[2][BM * 8];     // [row][8 chunks of 8 k], chunk c of row r at r*8 + (c ^ (r & 7))
-  __shared__ uint4 ldsB[2][BN * 8];     // [col][8 chunks of 8 k], chunk c of col n at n*8 + (c ^ ((n ^ (n >> 3)) & 7))
+  // B stays as loaded, [k][n] with n contiguous; rows are kBPitch bytes apart (64 bytes more than
+  // a row, so that the 4 rows one transposing read touches fall into different banks)
+  __shared__ __attribute__((aligned(16))) char ldsB[2][BK * kBPitch];
 
   // ---- which tile: XCD-contiguous bands, groups of kGroupRows tile rows
   const int wg = blockIdx.x;
@@ -107,9 +111,16 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P) {
   // clamped, valid address and are zeroed when they are written to LDS.  Columns past N need no
   // masking: they only feed C columns that are never stored.
   auto gload_prepare = [&](int k0) {
-    const int ka = k0 + a_c * 8, kb = k0 + b_kb * 8;
-    g_aco = (uint32_t)(axis_off(G.a_col, (uint32_t)(K_TAIL ? min(ka, K - 8) : ka)) * 2);
-    g_bp = b_colptr + axis_off(G.b_row, (uint32_t)(K_TAIL ? min(kb, K - 8) : kb)) * 2;
+    if (!K_TAIL && G.k64) {
+      // the part of the offsets that depends on the K step is the same for every lane: it is
+      // evaluated on the scalar unit; the lane's own part is a constant
+      g_aco = (uint32_t)(axis_off(G.a_col, (uint32_t)k0) * 2) + (uint32_t)(a_c * 16);
+      g_bp = b_colptr + axis_off(G.b_row, (uint32_t)k0) * 2 + (int64_t)(b_kb * 8) * b_kstride;
+    } else {
+      const int ka = k0 + a_c * 8, kb = k0 + b_kb * 8;
+      g_aco = (uint32_t)(axis_off(G.a_col, (uint32_t)(K_TAIL ? min(ka, K - 8) : ka)) * 2);
+      g_bp = b_colptr + axis_off(G.b_row, (uint32_t)(K_TAIL ? min(kb, K - 8) : kb)) * 2;
+    }
   };
   auto gload_a = [&](int i) { ra[i] = *reinterpret_cast<const uint4*>(G.a + (a_rowoff[i] + g_aco)); };
   auto gload_b = [&](int j) { rb[j] = *reinterpret_cast<const uint4*>(g_bp + j * b_kstride); };
@@ -119,16 +130,12 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P) {
     if (K_TAIL && k0 + a_c * 8 >= K) v = make_uint4(0, 0, 0, 0);
     ldsA[buf][r * 8 + (a_c ^ (r & 7))] = v;
   };
-  // column e of the thread's 8x8 block of B: gathered from the 8 row registers (v_perm_b32),
-  // its 8 k values written as one unit of B^T
-  auto store_b = [&](int buf, int e, int k0) {
-    const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-    uint32_t w[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) w[u] = __builtin_amdgcn_perm(word(rb[2 * u + 1], e >> 1), word(rb[2 * u], e >> 1), sel);
-    if (K_TAIL && k0 + b_kb * 8 >= K) w[0] = w[1] = w[2] = w[3] = 0u;
-    const int n = b_cn * 8 + e;
-    ldsB[buf][n * 8 + (b_kb ^ ((n ^ (n >> 3)) & 7))] = make_uint4(w[0], w[1], w[2], w[3]);
+  // row j of the thread's 8 (k) x 8 (n) block of B goes to LDS as it is (16 bytes, n contiguous);
+  // the transposition the matrix core needs happens in the LDS read (ds_read_b64_tr_b16)
+  auto store_b = [&](int buf, int j, int k0) {
+    uint4 v = rb[j];
+    if (K_TAIL && k0 + b_kb * 8 >= K) v = make_uint4(0, 0, 0, 0);
+    *reinterpret_cast<uint4*>(&ldsB[buf][(b_kb * 8 + j) * kBPitch + b_cn * 16]) = v;
   };
 
   f32x16 acc[4][4];
@@ -140,19 +147,18 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P) {
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   // fragment addresses (16-byte units) for k-chunk 0; chunk c is reached by XOR with c
-  int a_unit[4], b_unit[4], a_key[4], b_key[4];
+  int a_unit[4], a_key[4];
 #pragma unroll
   for (int mb = 0; mb < 4; ++mb) {
     const int r = wm * 128 + mb * 32 + l32;
     a_unit[mb] = r * 8;
     a_key[mb] = r & 7;
   }
-#pragma unroll
-  for (int nb = 0; nb < 4; ++nb) {
-    const int n = wn * 128 + nb * 32 + l32;
-    b_unit[nb] = n * 8;
-    b_key[nb] = (n ^ (n >> 3)) & 7;
-  }
+  // B fragments: a transposing LDS read hands lane i of a 16-lane group the 4 consecutive k of
+  // column n0 + i when lane L of the group points at row k0 + (L >> 2), columns n0 + 4 (L & 3) .. + 3.
+  // Lane group q = lane / 16: columns 16 (q & 1) .. + 15 of the 32-column block, k-half q >> 1.
+  const int lq = lane >> 4, ll = lane & 15;
+  const int b_lane_off = (8 * (lq >> 1) + (ll >> 2)) * kBPitch + (wn * 128 + 16 * (lq & 1) + 4 * (ll & 3)) * 2;
   opvec af[2][4], bf[2][4];
   // fragment f of k16 step ks (f = 0: A0, 1..4: B0..B3, 5..7: A1..A3: the order the MFMAs need them)
   auto read_frag = [&](int buf, int ks, int p, int f) {
@@ -162,7 +168,13 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P) {
       af[p][mb] = __builtin_bit_cast(opvec, ldsA[buf][a_unit[mb] + (chunk ^ a_key[mb])]);
     } else {
       const int nb = f - 1;
-      bf[p][nb] = __builtin_bit_cast(opvec, ldsB[buf][b_unit[nb] + (chunk ^ b_key[nb])]);
+      typedef short s16x4 __attribute__((ext_vector_type(4)));
+      typedef __attribute__((address_space(3))) s16x4* lds_s16x4;
+      const char* base = &ldsB[buf][b_lane_off + ks * 16 * kBPitch + nb * 64];
+      struct { s16x4 lo, hi; } v;
+      v.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(base));                  // k = 8 lh + 0..3
+      v.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(base + 4 * kBPitch));    // k = 8 lh + 4..7
+      bf[p][nb] = __builtin_bit_cast(opvec, v);
     }
   };
   auto mma = [&](int p, int m) { acc[m >> 2][m & 3] = M_::run(af[p][m >> 2], bf[p][m & 3], acc[m >> 2][m & 3]); };
@@ -378,6 +390,7 @@ extern "C" int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* c
       P.g[i].M = (int32_t)M;
       P.g[i].tiles_m = (int32_t)((M + BM - 1) / BM);
       P.g[i].tile_begin = tiles;
+      P.g[i].k64 = P.g[i].a_col.radix[2].d % 64 == 0 && P.g[i].b_row.radix[2].d % 64 == 0;
       tiles += P.g[i].tiles_m * (int32_t)((N + BN - 1) / BN);
     }
     P.n_groups = ng;
