@@ -37,6 +37,7 @@ constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int kMaxGroups = 8;
 constexpr int kGroupRows = 8;      // tile rows walked together (L2 reuse of the B panel)
 constexpr int kBPitch = BN * 2 + 64;   // bytes between k-rows of the B tile in LDS
+constexpr int kMaxSteps = 1024;        // K steps whose offsets are tabulated in LDS (K <= 65536)
 
 struct GemmGroup {
   const char* a;
@@ -61,6 +62,10 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P) {
   // B stays as loaded, [k][n] with n contiguous; rows are kBPitch bytes apart (64 bytes more than
   // a row, so that the 4 rows one transposing read touches fall into different banks)
   __shared__ __attribute__((aligned(16))) char ldsB[2][BK * kBPitch];
+  // byte offsets of every K step along A's columns and B's rows (the part of the map that depends
+  // on the step only), evaluated once per workgroup: nothing in the K loop reads kernel arguments
+  __shared__ uint32_t step_a[kMaxSteps];
+  __shared__ int64_t step_b[kMaxSteps];
 
   // ---- which tile: XCD-contiguous bands, groups of kGroupRows tile rows
   const int wg = blockIdx.x;
@@ -110,12 +115,30 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P) {
   // Chunks past K (only when K is not a multiple of 64: the K_TAIL instantiation) read a
   // clamped, valid address and are zeroed when they are written to LDS.  Columns past N need no
   // masking: they only feed C columns that are never stored.
+  const int nk = (K + BK - 1) / BK;
+  const bool tabulated = !K_TAIL && G.k64 && nk <= kMaxSteps;
+  if (tabulated) {
+    for (int st = t; st < nk; st += 256) {
+      step_a[st] = (uint32_t)(axis_off(G.a_col, (uint32_t)(st * BK)) * 2);
+      step_b[st] = axis_off(G.b_row, (uint32_t)(st * BK)) * 2;
+    }
+    __syncthreads();
+  }
+  const uint32_t a_lane = (uint32_t)(a_c * 16);
+  const char* b_lane = b_colptr + (int64_t)(b_kb * 8) * b_kstride;
+  uint32_t t_a = 0;              // table entries of the step about to be fetched, read well ahead of their use
+  int64_t t_b = 0;
+  auto gload_lookup = [&](int k0) {
+    if (tabulated) {
+      t_a = step_a[k0 / BK];
+      t_b = step_b[k0 / BK];
+    }
+  };
   auto gload_prepare = [&](int k0) {
-    if (!K_TAIL && G.k64) {
-      // the part of the offsets that depends on the K step is the same for every lane: it is
-      // evaluated on the scalar unit; the lane's own part is a constant
-      g_aco = (uint32_t)(axis_off(G.a_col, (uint32_t)k0) * 2) + (uint32_t)(a_c * 16);
-      g_bp = b_colptr + axis_off(G.b_row, (uint32_t)k0) * 2 + (int64_t)(b_kb * 8) * b_kstride;
+    if (tabulated) {
+      // a K step of 64 stays inside the innermost K digit of both operands: step offset + lane constant
+      g_aco = t_a + a_lane;
+      g_bp = b_lane + t_b;
     } else {
       const int ka = k0 + a_c * 8, kb = k0 + b_kb * 8;
       g_aco = (uint32_t)(axis_off(G.a_col, (uint32_t)(K_TAIL ? min(ka, K - 8) : ka)) * 2);
@@ -188,6 +211,7 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P) {
   auto k_step = [&](int it, auto do_store, auto do_load) {
     const int cur = it & 1, nxt = cur ^ 1;
     const int k_next = (it + 1) * BK;
+    if (do_load.value) gload_lookup((it + 2) * BK);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {            // k16 step 0 | read fragments of step 1
       mma(0, 2 * i);
@@ -225,7 +249,7 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P) {
     }
   };
 
-  const int nk = (K + BK - 1) / BK;
+  gload_lookup(0);
   gload_prepare(0);
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
@@ -238,6 +262,7 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P) {
     store_b(0, i, 0);
   }
   if (nk > 1) {
+    gload_lookup(BK);
     gload_prepare(BK);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
