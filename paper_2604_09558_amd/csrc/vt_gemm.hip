@@ -205,9 +205,11 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P) {
 
   // ---- one K step (64 MFMAs per wave).  Source order IS the issue order: each group between
   // two scheduling barriers holds two MFMAs and a little memory work that issues in the shadow
-  // of the matrix pipe.  Global loads run two K steps ahead, LDS stores of the next tile sit
-  // under k16 steps 1 and 2, fragments are read one k16 step ahead, and the only barrier comes
-  // before k16 step 3 so that the next tile's first fragments are in flight under its MFMAs.
+  // of the matrix pipe.  Global loads run two K steps ahead and are issued as soon as their
+  // registers are free (A under k16 step 2, B under k16 step 3), three quarters of a K step
+  // before the LDS stores that consume them (k16 steps 1 and 2 of the next K step); fragments are
+  // read one k16 step ahead, and the only barrier comes before k16 step 3 so that the next
+  // tile's first fragments are in flight under its MFMAs.
   auto k_step = [&](int it, auto do_store, auto do_load) {
     const int cur = it & 1, nxt = cur ^ 1;
     const int k_next = (it + 1) * BK;
@@ -227,22 +229,22 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P) {
       if (do_store.value) store_a(nxt, i, k_next);
       VT_SB();
     }
+    if (do_load.value) gload_prepare((it + 2) * BK);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {            // k16 step 2 | fragments of step 3, B tile transposed -> LDS
+    for (int i = 0; i < 8; ++i) {            // k16 step 2 | fragments of step 3, B tile -> LDS, A rows two K steps ahead
       mma(0, 2 * i);
       read_frag(cur, 3, 1, i);
+      if (do_load.value) gload_a(i);         // the A registers are free again: their tile went to LDS in k16 step 1
       mma(0, 2 * i + 1);
       if (do_store.value) store_b(nxt, i, k_next);
       VT_SB();
     }
     __syncthreads();
     VT_SB();
-    if (do_load.value) gload_prepare((it + 2) * BK);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {            // k16 step 3 | first fragments of the next tile, global loads two steps ahead
+    for (int i = 0; i < 8; ++i) {            // k16 step 3 | first fragments of the next tile, B rows two K steps ahead
       mma(1, 2 * i);
       if (do_store.value) read_frag(nxt, 0, 0, i);
-      if (do_load.value) gload_a(i);
       mma(1, 2 * i + 1);
       if (do_load.value) gload_b(i);
       VT_SB();
