@@ -116,36 +116,46 @@ __device__ __forceinline__ Regs16 load16(const char* base, uint32_t off) {
   return r;
 }
 
-// Tiles never straddle a segment: the i-th tile of the split [t_begin, t_end) is found by
-// walking the segments; all values are wave-uniform.
-struct TilePos {
-  int seg, r0, end;      // rows [r0, min(r0+32, end)) of segment seg are valid
+// Walks the 32-row tiles of a split [t_begin, t_end).  Tiles never straddle a segment, so the
+// walk goes segment by segment; everything the loads of a tile need from its segment (row
+// pointers of this (b, g), row pitches, the clipped range) is fetched from the kernel
+// arguments once, when the walk enters the segment, and then lives in scalar registers: the
+// loop over tiles reads no kernel argument.  All values are wave-uniform.
+struct TileWalk {
+  const char* k;         // K row t_lo of this (b, g) in the current segment
+  const char* v;
+  uint32_t k_st, v_st;   // bytes per context row
+  int t_lo;              // first row of the segment
+  int r0, end;           // current tile: rows [r0, min(r0 + 32, end)) ; end = clipped end of the segment
+  int seg;               // current segment, P.n_seg when the walk is over
 };
 
-__device__ __forceinline__ int count_tiles(const AttnParams& P, int t_begin, int t_end) {
-  int n = 0;
-  for (int s = 0; s < P.n_seg; ++s) {
-    int a = max(P.seg[s].t_lo, t_begin), e = min(P.seg[s].t_hi, t_end);
-    if (e > a) n += (e - a + kTile - 1) / kTile;
-  }
-  return n;
+__device__ __forceinline__ void walk_enter(const AttnParams& P, TileWalk& w, int seg, int b, int g, int t_begin, int t_end) {
+  // skip segments that do not meet the split
+  while (seg < P.n_seg && min(P.seg[seg].t_hi, t_end) <= max(P.seg[seg].t_lo, t_begin)) ++seg;
+  w.seg = seg;
+  if (seg >= P.n_seg) return;
+  const AttnSeg& sg = P.seg[seg];
+  w.k = sg.k + b * sg.k_sb + (g / sg.k_hdiv) * sg.k_sh;
+  w.v = sg.v + b * sg.v_sb + (g / sg.v_hdiv) * sg.v_sh;
+  w.k_st = sg.k_st;
+  w.v_st = sg.v_st;
+  w.t_lo = sg.t_lo;
+  w.r0 = max(sg.t_lo, t_begin);
+  w.end = min(sg.t_hi, t_end);
 }
 
-__device__ __forceinline__ TilePos locate_tile(const AttnParams& P, int t_begin, int t_end, int i) {
-  TilePos tp{0, t_begin, t_begin};
-  for (int s = 0; s < P.n_seg; ++s) {
-    int a = max(P.seg[s].t_lo, t_begin), e = min(P.seg[s].t_hi, t_end);
-    if (e <= a) continue;
-    int nt = (e - a + kTile - 1) / kTile;
-    if (i < nt) {
-      tp.seg = s;
-      tp.r0 = a + i * kTile;
-      tp.end = e;
-      return tp;
+// n tiles forward (n >= 0)
+__device__ __forceinline__ void walk_advance(const AttnParams& P, TileWalk& w, int n, int b, int g, int t_begin, int t_end) {
+  while (w.seg < P.n_seg) {
+    const int left = (w.end - w.r0 + kTile - 1) / kTile;      // tiles of this segment from r0 on
+    if (n < left) {
+      w.r0 += n * kTile;
+      return;
     }
-    i -= nt;
+    n -= left;
+    walk_enter(P, w, w.seg + 1, b, g, t_begin, t_end);
   }
-  return tp;
 }
 
 template <typename T, int WAVES, int OCC>
@@ -162,7 +172,6 @@ k_decode_attn(const AttnParams P) {
   const int l16 = lane & 15, lg = lane >> 4;
   const int t_begin = split * P.rows_per_split;
   const int t_end = min(P.S, t_begin + P.rows_per_split);
-  const int n_tiles = count_tiles(P, t_begin, t_end);
   const float c = P.scale_log2;
 
   // Q^T operand: lane (head l16, k-group lg) holds 8 consecutive d for each of the 4 k-steps
@@ -188,10 +197,9 @@ k_decode_attn(const AttnParams P) {
   // In a full tile the address is a wave-uniform base per instruction plus ONE per-lane
   // offset; a partial tile (last of a segment) clamps its rows onto the last valid one.
   Regs16 kst[8], vst[8];
-  auto issue_k = [&](const TilePos& tp) {
-    const AttnSeg& sg = P.seg[tp.seg];
-    const uint32_t st = sg.k_st;
-    const char* kb = sg.k + b * sg.k_sb + (g / sg.k_hdiv) * sg.k_sh + (int64_t)(tp.r0 - sg.t_lo) * st;
+  auto issue_k = [&](const TileWalk& tp) {
+    const uint32_t st = tp.k_st;
+    const char* kb = tp.k + (int64_t)(tp.r0 - tp.t_lo) * st;
     if (tp.r0 + kTile <= tp.end) {
       const uint32_t off = lg * st + l16 * 16;
 #pragma unroll
@@ -202,10 +210,9 @@ k_decode_attn(const AttnParams P) {
       for (int j = 0; j < 8; ++j) kst[j] = load16(kb, (uint32_t)min(4 * j + lg, span) * st + l16 * 16);
     }
   };
-  auto issue_v = [&](const TilePos& tp) {
-    const AttnSeg& sg = P.seg[tp.seg];
-    const uint32_t st = sg.v_st;
-    const char* vb = sg.v + b * sg.v_sb + (g / sg.v_hdiv) * sg.v_sh + (int64_t)(tp.r0 - sg.t_lo) * st;
+  auto issue_v = [&](const TileWalk& tp) {
+    const uint32_t st = tp.v_st;
+    const char* vb = tp.v + (int64_t)(tp.r0 - tp.t_lo) * st;
     if (tp.r0 + kTile <= tp.end) {
       const uint32_t off = lg * 4 * st + l16 * 16;
 #pragma unroll
@@ -219,25 +226,26 @@ k_decode_attn(const AttnParams P) {
   };
 
   uint4* my_lds = lds[wave];
-  TilePos cur = locate_tile(P, t_begin, t_end, wave);
-  if (wave < n_tiles) {
+  // this wave's tiles: wave, wave + WAVES, ... of the split
+  TileWalk cur;
+  walk_enter(P, cur, 0, b, g, t_begin, t_end);
+  walk_advance(P, cur, wave, b, g, t_begin, t_end);
+  if (cur.seg < P.n_seg) {
     issue_k(cur);
     issue_v(cur);
   }
-  for (int tile = wave; tile < n_tiles; tile += WAVES) {
+  while (cur.seg < P.n_seg) {
     const int r0 = cur.r0, r_end = cur.end;
     const bool partial = r0 + kTile > r_end;
-    const bool more = tile + WAVES < n_tiles;
+    walk_advance(P, cur, WAVES, b, g, t_begin, t_end);     // cur is now the next tile of this wave
+    const bool more = cur.seg < P.n_seg;
     // ---- stage K through LDS (swizzle: chunk c of row r sits at unit c ^ (r & 15))
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       int r = 4 * j + lg;
       my_lds[r * 16 + (l16 ^ (r & 15))] = make_uint4(kst[j].w[0], kst[j].w[1], kst[j].w[2], kst[j].w[3]);
     }
-    if (more) {
-      cur = locate_tile(P, t_begin, t_end, tile + WAVES);
-      issue_k(cur);                      // next tile's K is in flight during this tile's math
-    }
+    if (more) issue_k(cur);              // next tile's K is in flight during this tile's math
 
     // ---- S^T = K . Q^T : two 16-row blocks, 4 k-steps each
     f32x4 s[2];
