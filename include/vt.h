@@ -196,8 +196,10 @@ int vt_scatter(const vt_desc* src, const vt_desc* dst, void* stream);
  *      device pointer.  The map must be one to one: a broadcast digit or pieces whose ranges in
  *      one tensor may overlap give VT_ERR_NOT_ONE_TO_ONE; index tables and stacked stages on
  *      the output give VT_ERR_UNSUPPORTED.
- * N and K are multiples of 8.  The kernel is built for a handful of rows (a decode step:
- * M = batch); more rows are processed 16 at a time and B is read once per 16 rows.
+ * N and K are multiples of 8.  Up to 128 rows run on a kernel built for a handful of rows (a
+ * decode step: M = batch; rows are processed 16 at a time and B is read once per 16 rows); more
+ * rows run on the tiled kernel of vt_gemm with the map applied in its store stage (A and B then
+ * obey vt_gemm's layout rules; the workspace is not used).
  * workspace: device pointer (16-byte aligned), at least vt_gemm_store_workspace(M, N, K) bytes,
  * cleared once with vt_gemm_store_workspace_init (arrival counters, left at zero by every call,
  * and the partial sums of the K slices); calls that share a workspace must not overlap in time.

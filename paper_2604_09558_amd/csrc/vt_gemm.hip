@@ -54,8 +54,20 @@ struct GemmParams {
   int32_t n_groups, N, K, tiles_n, total_tiles, chunk, c_f32, pad;
 };
 
-template <typename T, bool C_F32, bool K_TAIL>
-__global__ void __launch_bounds__(256) k_gemm(const GemmParams P) {
+// Output written through a map (producer-side store, Sec. 4.2): columns [col_lo, col_hi) of C
+// live in one physical tensor, element (m, n) at base + 2 * (row(m) + col(n - col_lo)).
+struct OutPiece {
+  char* base;
+  int32_t col_lo, col_hi;
+  AxisMap<3> row, col;
+};
+struct OutMap {
+  OutPiece p[4];
+  int32_t n, pad;
+};
+
+template <typename T, bool C_F32, bool K_TAIL, bool MAPPED>
+__global__ void __launch_bounds__(256) k_gemm(const GemmParams P, const OutMap O) {
   typedef Mma<T> M_;
   typedef typename M_::vec opvec;
   __shared__ uint4 ldsA[2][BM * 8];     // [row][8 chunks of 8 k], chunk c of row r at r*8 + (c ^ (r & 7))
@@ -284,6 +296,36 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P) {
   k_step(it, std::false_type{}, std::false_type{});
 #undef VT_SB
 
+  if (MAPPED) {
+    // ---- stage 3 through the output map.  The row part of the map is evaluated once per row of
+    // the tile (one thread each, per piece) and parked in LDS, which the K loop no longer needs;
+    // the column part once per lane and column block.
+    __syncthreads();
+    int64_t* rowoff = reinterpret_cast<int64_t*>(&ldsA[0][0]);       // [pieces][BM]
+    for (int pc = 0; pc < O.n; ++pc) rowoff[pc * BM + t] = axis_off(O.p[pc].row, (uint32_t)min(tm * BM + t, Mg - 1));
+    __syncthreads();
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+      const int col = tn * BN + wn * 128 + nb * 32 + l32;
+      if (col >= N) continue;
+      int pc = 0;
+#pragma unroll
+      for (int i = 1; i < 4; ++i)
+        if (i < O.n && col >= O.p[i].col_lo) pc = i;
+      T* base = reinterpret_cast<T*>(O.p[pc].base) + axis_off(O.p[pc].col, (uint32_t)(col - O.p[pc].col_lo));
+      const int64_t* ro = rowoff + pc * BM;
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb) {
+        const int r0 = wm * 128 + mb * 32 + lh * 4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (tm * BM + r0 + 8 * j + i < Mg) base[ro[r0 + 8 * j + i]] = from_float<T>(acc[mb][nb][4 * j + i]);
+      }
+    }
+    return;
+  }
   // ---- stage 3: plain contiguous store of the tile (lanes 0..31 write 32 consecutive columns)
   typedef typename std::conditional<C_F32, float, T>::type CT;
   CT* cbase = reinterpret_cast<CT*>(G.c);
@@ -372,6 +414,69 @@ namespace vt {
 int ln_gemm_launch(const vt_desc& A, const vt_desc& B, void* C, int c_dtype, float eps, hipStream_t st);
 }
 
+namespace vt {
+
+// C = A . B with the result written through the output descriptor Cd (pieces split the columns;
+// the caller has checked that the map is one to one).  One group, operands' dtype for the output.
+int gemm_store_launch(const vt_desc& A, const vt_desc& B, const vt_desc& Cd, hipStream_t st) {
+  const int dt = A.dtype;
+  GemmParams P;
+  memset(&P, 0, sizeof(P));
+  int64_t M, Ka, Kb, N;
+  int rc = plan_a(A, &P.g[0], &M, &Ka);
+  if (rc != VT_OK) return rc;
+  rc = plan_b(B, &P.g[0], &Kb, &N);
+  if (rc != VT_OK) return rc;
+  if (Ka != Kb) return fail(VT_ERR_SHAPE, "vt_gemm_store: inner dims of A and B differ");
+  if (M >= (1ll << 31) || N >= (1ll << 31) || Ka >= (1ll << 31)) return fail(VT_ERR_UNSUPPORTED, "vt_gemm_store: extents too large");
+  OutMap O;
+  memset(&O, 0, sizeof(O));
+  if (Cd.pieces.size() > 4) return fail(VT_ERR_UNSUPPORTED, "vt_gemm_store: more than 4 output pieces");
+  std::vector<const Piece*> ps;
+  for (const Piece& p : Cd.pieces) ps.push_back(&p);
+  std::sort(ps.begin(), ps.end(), [](const Piece* x, const Piece* y) { return x->lo[1] < y->lo[1]; });
+  int64_t expect = 0;
+  for (size_t i = 0; i < ps.size(); ++i) {
+    const Piece& p = *ps[i];
+    if (p.lo[0] != 0 || p.hi[0] != M || p.lo[1] != expect) return fail(VT_ERR_UNSUPPORTED, "vt_gemm_store: output pieces must split the columns only");
+    expect = p.hi[1];
+    rc = make_axis(Cd, p, 0, 1, &O.p[i].row, "vt_gemm_store: output rows");
+    if (rc != VT_OK) return rc;
+    rc = make_axis(Cd, p, 1, 2, &O.p[i].col, "vt_gemm_store: output columns");
+    if (rc != VT_OK) return rc;
+    const vt_source& s = Cd.sources[p.src];
+    if (!s.ptr) return fail(VT_ERR_INVALID_ARG, "vt_gemm_store: output tensor without a device pointer");
+    O.p[i].base = static_cast<char*>(s.ptr) + p.v.base * 2;
+    O.p[i].col_lo = (int32_t)p.lo[1];
+    O.p[i].col_hi = (int32_t)p.hi[1];
+  }
+  if (expect != N) return fail(VT_ERR_UNSUPPORTED, "vt_gemm_store: output pieces do not cover the columns");
+  O.n = (int32_t)ps.size();
+  P.g[0].c = nullptr;
+  P.g[0].M = (int32_t)M;
+  P.g[0].tiles_m = (int32_t)((M + BM - 1) / BM);
+  P.g[0].tile_begin = 0;
+  P.g[0].k64 = P.g[0].a_col.radix[2].d % 64 == 0 && P.g[0].b_row.radix[2].d % 64 == 0;
+  P.n_groups = 1;
+  P.N = (int32_t)N;
+  P.K = (int32_t)Ka;
+  P.tiles_n = (int32_t)((N + BN - 1) / BN);
+  P.total_tiles = P.g[0].tiles_m * P.tiles_n;
+  P.chunk = (P.total_tiles + 7) / 8;
+  dim3 grid(P.chunk * 8);
+  const bool kt = Ka % BK != 0;
+  if (dt == VT_BF16) {
+    if (kt) hipLaunchKernelGGL((k_gemm<bf16_t, false, true, true>), grid, dim3(256), 0, st, P, O);
+    else hipLaunchKernelGGL((k_gemm<bf16_t, false, false, true>), grid, dim3(256), 0, st, P, O);
+  } else {
+    if (kt) hipLaunchKernelGGL((k_gemm<f16_t, false, true, true>), grid, dim3(256), 0, st, P, O);
+    else hipLaunchKernelGGL((k_gemm<f16_t, false, false, true>), grid, dim3(256), 0, st, P, O);
+  }
+  return check_launch("vt_gemm_store");
+}
+
+}  // namespace vt
+
 extern "C" int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* const* C, int n_groups, int c_dtype,
                        int prologue, float eps, void* stream) {
   if (!A || !B || !C || n_groups < 1) return fail(VT_ERR_INVALID_ARG, "vt_gemm: NULL argument");
@@ -429,7 +534,9 @@ extern "C" int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* c
     P.c_f32 = c_dtype == VT_F32;
     dim3 grid(P.chunk * 8);
     const bool kt = K % BK != 0;
-#define VT_GEMM_LAUNCH(TT, CF, KT) hipLaunchKernelGGL((k_gemm<TT, CF, KT>), grid, dim3(256), 0, st, P)
+    OutMap no_map;
+    memset(&no_map, 0, sizeof(no_map));
+#define VT_GEMM_LAUNCH(TT, CF, KT) hipLaunchKernelGGL((k_gemm<TT, CF, KT, false>), grid, dim3(256), 0, st, P, no_map)
     if (dt == VT_BF16) {
       if (P.c_f32) { if (kt) VT_GEMM_LAUNCH(bf16_t, true, true); else VT_GEMM_LAUNCH(bf16_t, true, false); }
       else { if (kt) VT_GEMM_LAUNCH(bf16_t, false, true); else VT_GEMM_LAUNCH(bf16_t, false, false); }

@@ -27,6 +27,10 @@
 using namespace vt;
 using namespace vt::gemm;
 
+namespace vt {
+int gemm_store_launch(const vt_desc& A, const vt_desc& B, const vt_desc& Cd, hipStream_t st);   // vt_gemm.hip
+}
+
 namespace {
 
 constexpr int kBN = 128;          // columns per workgroup
@@ -34,6 +38,7 @@ constexpr int kBM = 16;           // rows per workgroup (one MFMA block)
 constexpr int kTileK = 32;        // k-rows per wave step
 constexpr int kWaves = 4;
 constexpr int kMaxOutPieces = 4;
+constexpr int kTiledFrom = 128;   // more rows than this go to the 256 x 256 tiled kernel
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -284,6 +289,12 @@ int vt_gemm_store(const vt_desc* A, const vt_desc* B, const vt_desc* C, void* wo
   if (M < 1 || N < 8 || K < 8 || N % 8 || K % 8) return fail(VT_ERR_UNSUPPORTED, "vt_gemm_store: N and K must be multiples of 8");
   if (M >= (1ll << 20) || N >= (1ll << 30) || K >= (1ll << 30)) return fail(VT_ERR_UNSUPPORTED, "vt_gemm_store: extents too large");
 
+  int rc0 = check_store_map(*C, "vt_gemm_store");
+  if (rc0 != VT_OK) return rc0;
+  // many rows: the tiled GEMM with the map applied in its store stage (this kernel would read B
+  // once per 16 rows)
+  if (M > kTiledFrom) return gemm_store_launch(*A, *B, *C, (hipStream_t)stream);
+
   StoreParams P;
   memset(&P, 0, sizeof(P));
   // A: one piece, rows through a map, K contiguous
@@ -319,8 +330,7 @@ int vt_gemm_store(const vt_desc* A, const vt_desc* B, const vt_desc* C, void* wo
     if (P.ldb * 2 * 16 + N * 2 >= (1ll << 32)) return fail(VT_ERR_UNSUPPORTED, "vt_gemm_store: rows of B too far apart");
   }
   // the output: pieces that split the columns
-  int rc = check_store_map(*C, "vt_gemm_store");
-  if (rc != VT_OK) return rc;
+  int rc = VT_OK;
   if (C->pieces.size() > (size_t)kMaxOutPieces) return fail(VT_ERR_UNSUPPORTED, "vt_gemm_store: more than 4 output pieces");
   {
     std::vector<const Piece*> ps;

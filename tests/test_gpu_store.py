@@ -58,6 +58,26 @@ def test_qkv_store_small(gpu, B, T, hidden, Hq, Hkv, D, cap, pos, dtype):
     compare_stored(tio, dw, wl, ref)
 
 
+@pytest.mark.parametrize("B,T,hidden,Hq,Hkv,D,cap,pos", [(4, 64, 256, 4, 2, 64, 128, 10), (3, 100, 136, 2, 1, 128, 120, 20)])
+def test_qkv_store_many_rows_goes_through_the_tiled_kernel(gpu, B, T, hidden, Hq, Hkv, D, cap, pos):
+    """A chunk of T new tokens per sequence (M = B T > 128 rows): the 256 x 256 tiled GEMM applies
+    the output map in its store stage; K/V rows land in slots pos .. pos+T-1 of the caches."""
+    vt, tio, pipelines, torch = gpu
+    wl = workloads.qkv_proj_store(seed=5, B=B, hidden=hidden, Hq=Hq, Hkv=Hkv, D=D, cap=cap, pos=pos, T=T)
+    ref = run_workload(wl)
+    dw = tio.DeviceWorkload(wl)
+    p = pipelines.GemmStore(dw)
+    p.run()
+    torch.cuda.synchronize()
+    compare_stored(tio, dw, wl, ref)
+    # and equals the dense product + scatter bit for bit
+    dw2 = tio.DeviceWorkload(wl)
+    pipelines.GemmStore(dw2, materialized=True).run()
+    torch.cuda.synchronize()
+    for n in ("Qbuf", "Kcache", "Vcache"):
+        assert torch.equal(dw.tensors[n], dw2.tensors[n]), n
+
+
 def test_qkv_store_full_size_and_reproducible(gpu):
     """The decode step of the benchmark's model: X[8,4096] . W[4096,6144] -> Q buffer, cache slot 4095."""
     vt, tio, pipelines, torch = gpu
