@@ -224,6 +224,12 @@ def main():
     wls = [workloads.c2_decode_attention(seed=s, B=B, Hkv=Hkv, G=G, S=S, D=D) for s in range(a.copies)]
     dws = [tio.DeviceWorkload(w) for w in wls]
     virt = [pipelines.DecodeAttention(dw, materialized=False, n_splits=a.n_splits, want_lse=False) for dw in dws]
+    # host cost of composing the chain into descriptors (not part of a step: maps are built once, Sec. 4.1)
+    t0 = time.perf_counter()
+    for _ in range(20):
+        for n in ("Q", "K", "V"):
+            dws[0].build(n)
+    build_us = (time.perf_counter() - t0) / 20 * 1e6
     torch.cuda.synchronize()
 
     def mk(p):
@@ -255,6 +261,7 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
+        "descriptor_build_host_us": round(build_us, 1),
         "config": {"workload": "c2: Llama-3-8B decode segment, fused QKV [8,1,6144] + KV cache [8,8,4096,128] -> "
                                "GQA 4:1 flash-decode, context 4096, Q/K/V read through descriptors",
                    "batch": B, "context": S, "kv_heads": Hkv, "q_heads": Hkv * G, "head_dim": D,
