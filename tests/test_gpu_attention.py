@@ -155,3 +155,27 @@ def test_one_operand_broadcast_and_the_other_dense(gpu):
         p.run()
         torch.cuda.synchronize()
         check(tio.to_host_f64(p.out), ref)
+
+
+def test_sliding_window_is_one_more_slice_in_the_chain(gpu):
+    """Local attention over the last W cached rows plus the fresh one (the local layers of a
+    local-global model): the window is a Slice with a non-zero start in front of the same chain;
+    nothing outside the window may be read (rows before it are poisoned with NaN)."""
+    vt, tio, pipelines, torch = gpu
+    B, Hkv, G, D, cap, W = 2, 2, 4, 128, 1000, 200
+    wl = workloads.c2_decode_attention(seed=9, B=B, Hkv=Hkv, G=G, S=cap, D=D)
+    chain = workloads.c2_chain(B, Hkv, G, W + 1, D)           # the chain over W + 1 keys ...
+    for i, (out, op, ins, p) in enumerate(chain):
+        if op == "slice" and ins[0] in ("Kcache", "Vcache"):
+            chain[i] = (out, op, ins, {"dim": 2, "start": cap - 1 - W, "stop": cap - 1, "step": 1})   # ... taken from the end of the cache
+    wl.chain = chain
+    for name in ("Kcache", "Vcache"):
+        wl.sources[name] = wl.sources[name].copy()
+        wl.sources[name][:, :, :cap - 1 - W, :] = 0x7FC0        # bf16 NaN
+        wl.sources[name][:, :, cap - 1, :] = 0x7FC0
+    ref = run_workload(wl)
+    assert np.isfinite(ref["out"]).all()
+    res = pipelines.run_decode_attention(tio.DeviceWorkload(wl))
+    got = tio.to_host_f64(res["out"])
+    assert np.isfinite(got).all()
+    check(got, ref["out"])
