@@ -54,7 +54,7 @@ def parse():
     ap.add_argument("--context", type=int, default=4096, help="context length (the benchmark's is 4096; others are for tuning)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 128 MiB -> 128 MiB copy kernel 20 times (reference point for HBM byte counters)")
-    ap.add_argument("--extra", default="", help="comma list of further chains to time (c1,c3,c4,c5,qkv_store,decode_segment)")
+    ap.add_argument("--extra", default="", help="comma list of further chains to time (c1,c3,c4,c5,qkv_store,decode_segment,paged)")
     return ap.parse_args()
 
 
@@ -145,6 +145,26 @@ def chain_stats(torch, name, steps):
         out["materialized_full_us"] = round(m_ev * 1e3, 2)
         out["speedup_vs_materialized_full"] = round(m_ev / v_ev, 2)
         out["intermediate_bytes_saved"] = int(mat.attn.mat.bytes_written + M * N * 2)
+        return out
+    if name == "paged":
+        # config 2's attention over a paged KV cache (pages of 128 rows picked through a block table)
+        mk = lambda p: (lambda stream: p.run(stream))      # noqa: E731
+        dws = [tio.DeviceWorkload(workloads.paged_decode_attention(seed=s)) for s in range(4)]
+        ps = [pipelines.DecodeAttention(dw, want_lse=False) for dw in dws]
+        torch.cuda.synchronize()
+        v_wall, v_ev = time_steps(torch, [mk(p) for p in ps], steps, max(2, steps // 10), True)
+        B, Hq, S, D = ps[0].k.shape
+        alg = 2 * B * (Hq // 4) * S * D * 2 + 2 * B * Hq * D * 2
+        out = {"virtual_us": round(v_ev * 1e3, 2), "algorithmic_bytes": int(alg),
+               "hbm_pct_of_peak": round(100.0 * alg / (v_ev * 1e-3) / 1e9 / HBM_PEAK_GBS, 1)}
+        del ps, dws
+        torch.cuda.empty_cache()
+        mat = pipelines.DecodeAttention(tio.DeviceWorkload(workloads.paged_decode_attention(seed=0)), materialized=True, want_lse=False)
+        torch.cuda.synchronize()
+        m_wall, m_ev = time_steps(torch, [mk(mat)], max(5, steps // 8), 2, False)
+        out["materialized_full_us"] = round(m_ev * 1e3, 2)
+        out["speedup_vs_materialized_full"] = round(m_ev / v_ev, 2)
+        out["intermediate_bytes_saved"] = int(mat.mat.bytes_written)
         return out
     copies = {"c1": 1, "c3": 3, "c4": 6, "c5": 1, "qkv_store": 6}[name]
     wls = [workloads.CONFIGS[name](seed=s) for s in range(copies)]
@@ -290,7 +310,7 @@ def main():
         torch.cuda.empty_cache()
         out["chains"] = {}
         for name in a.extra.split(","):
-            out["chains"][name] = chain_stats(torch, name, {"c1": 200, "c3": 30, "c4": 100, "c5": 6, "qkv_store": 200, "decode_segment": 120}[name])
+            out["chains"][name] = chain_stats(torch, name, {"c1": 200, "c3": 30, "c4": 100, "c5": 6, "qkv_store": 200, "decode_segment": 120, "paged": 200}[name])
             torch.cuda.empty_cache()
 
     if not a.no_cpu_baseline:

@@ -55,9 +55,27 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 // A stretch of the context [t_lo, t_hi) in which K rows come from one source region and V
 // rows from one source region (the union of the piece boundaries of the two descriptors).
+// An operand whose rows sit in pages picked through an index table (paged KV cache: the map has
+// table digit, Sec. 4.1 / the table-driven part of b(I) in Eq. 1).  With (batch b, stored head
+// h, page pg, row-in-page o):
+//   L = L0 + b Lb + h Lh + pg Lp + o Lo          (what the table digit and its stage see)
+//   X = X0 + b Xb + h Xh + o Xo                  (strided terms outside the table's stage)
+//   element offset = tab[L / W] * ps + L % W + X
+// Two-stage form (the table dim was reshaped: the top stage builds a linear index that the second
+// stage cuts into table entry and remainder): X terms are 0 except X0 = the second stage's base.
+// One-stage form (the table digit sits in the context group itself): L = pg, W = 1.
+struct PagedOperand {
+  const int32_t* tab;    // NULL: the operand is not paged in this segment
+  int64_t L0, Lb, Lh, Lp, Lo;
+  int64_t X0, Xb, Xh, Xo;
+  int64_t ps;
+  FastDiv W, page;       // elements per table entry; rows per page (a multiple of 32, or the whole segment)
+};
+
 struct AttnSeg {
-  const char* k;         // K element (b=0, g=0, t=t_lo, d=0)
+  const char* k;         // K element (b=0, g=0, t=t_lo, d=0); for a paged operand: element 0 of its source
   const char* v;
+  PagedOperand kp, vp;
   int64_t k_sb, k_sh, v_sb, v_sh;   // bytes per batch / per stored head
   uint32_t k_st, v_st;              // bytes per context row
   int32_t k_hdiv, v_hdiv;           // head group g reads stored head g / hdiv (1 unless this operand is
@@ -130,6 +148,33 @@ struct TileWalk {
   int seg;               // current segment, P.n_seg when the walk is over
 };
 
+// One table entry, read on the scalar unit (the table is read-only for the kernel; a vector
+// load would queue behind the K/V rows already in flight).
+__device__ __forceinline__ int32_t table_entry(const int32_t* tab, uint32_t idx) {
+  int32_t v;
+  const uint32_t off = idx * 4u;
+  asm volatile("s_load_dword %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(tab), "s"(off) : "memory");
+  return v;
+}
+
+// Pointer p such that p + (r0 - t_lo) * st is row r0 of this (b, g): the form the loads use.
+__device__ __forceinline__ const char* paged_base(const PagedOperand& o, const char* src, uint32_t st, int b, int h, int rel) {
+  const uint32_t pg = fdiv((uint32_t)rel, o.page);
+  const int64_t row = rel - (int)(pg * o.page.d);
+  const int64_t L = o.L0 + b * o.Lb + h * o.Lh + (int64_t)pg * o.Lp + row * o.Lo;
+  const int64_t X = o.X0 + b * o.Xb + h * o.Xh + row * o.Xo;
+  const uint32_t j = fdiv((uint32_t)L, o.W);
+  const int64_t off = (int64_t)table_entry(o.tab, j) * o.ps + (L - (int64_t)j * o.W.d) + X;
+  return src + off * 2 - (int64_t)rel * st;
+}
+
+// the tile at w.r0 moved: paged operands look their page up again
+__device__ __forceinline__ void walk_locate(const AttnParams& P, TileWalk& w, int b, int g) {
+  const AttnSeg& sg = P.seg[w.seg];
+  if (sg.kp.tab) w.k = paged_base(sg.kp, sg.k, sg.k_st, b, g / sg.k_hdiv, w.r0 - sg.t_lo);
+  if (sg.vp.tab) w.v = paged_base(sg.vp, sg.v, sg.v_st, b, g / sg.v_hdiv, w.r0 - sg.t_lo);
+}
+
 __device__ __forceinline__ void walk_enter(const AttnParams& P, TileWalk& w, int seg, int b, int g, int t_begin, int t_end) {
   // skip segments that do not meet the split
   while (seg < P.n_seg && min(P.seg[seg].t_hi, t_end) <= max(P.seg[seg].t_lo, t_begin)) ++seg;
@@ -143,6 +188,7 @@ __device__ __forceinline__ void walk_enter(const AttnParams& P, TileWalk& w, int
   w.t_lo = sg.t_lo;
   w.r0 = max(sg.t_lo, t_begin);
   w.end = min(sg.t_hi, t_end);
+  if (sg.kp.tab || sg.vp.tab) walk_locate(P, w, b, g);
 }
 
 // n tiles forward (n >= 0)
@@ -151,6 +197,7 @@ __device__ __forceinline__ void walk_advance(const AttnParams& P, TileWalk& w, i
     const int left = (w.end - w.r0 + kTile - 1) / kTile;      // tiles of this segment from r0 on
     if (n < left) {
       w.r0 += n * kTile;
+      if (n > 0 && (P.seg[w.seg].kp.tab || P.seg[w.seg].vp.tab)) walk_locate(P, w, b, g);
       return;
     }
     n -= left;
@@ -456,6 +503,8 @@ struct PlanPiece {
   int32_t hdiv;
   uint32_t st;
   int32_t t_lo, t_hi;
+  PagedOperand pg;       // pg.tab != NULL: rows through a page table (ptr is then element 0 of the source)
+  int64_t page_rows;
 };
 struct AttnOperand {
   PlanPiece pc[kMaxAttnPieces];
@@ -476,10 +525,24 @@ int plan_operand(const vt_desc& d, const char* name, int64_t G, AttnOperand* out
       if (p.lo[dim] != 0 || p.hi[dim] != d.shape[dim]) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": pieces must split the context dim only");
     if (p.lo[2] != expect) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": pieces do not tile the context");
     expect = p.hi[2];
-    if (!p.v.lower.empty()) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": stacked index stages");
-    int64_t sb, st, sd;
-    if (!single_plain(p.v.groups[0], &sb) || !single_plain(p.v.groups[2], &st) || !single_plain(p.v.groups[3], &sd))
-      return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": batch, context and feature dims must each be one strided digit");
+    if (p.v.lower.size() > 1) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": more than two index stages");
+    const bool two_stage = p.v.lower.size() == 1;
+    bool paged = two_stage;
+    const Digit* ctx_table = nullptr;      // one-stage paged form: the table digit in the context group
+    int64_t sb, st, sd, lp = 0, page_rows = p.hi[2] - p.lo[2];
+    if (!single_plain(p.v.groups[0], &sb) || !single_plain(p.v.groups[3], &sd))
+      return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": batch and feature dims must each be one strided digit");
+    if (!single_plain(p.v.groups[2], &st)) {
+      // a paged context: [pages] x [rows of a page (stride st)]
+      const std::vector<Digit>& cg = p.v.groups[2];
+      if (cg.size() != 2 || cg[1].table >= 0 || (cg[0].table >= 0) == two_stage)
+        return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": the context dim must be one strided digit (or pages x rows under a page table)");
+      if (cg[0].table >= 0) ctx_table = &cg[0];
+      paged = true;
+      lp = cg[0].stride;
+      page_rows = cg[1].radix;
+      st = cg[1].stride;
+    }
     if (sd != 1) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": rows must be contiguous along the head dim");
     // head group: [kv heads (stride sh)] x [G broadcast]
     std::vector<Digit> hg = p.v.groups[1];
@@ -510,10 +573,65 @@ int plan_operand(const vt_desc& d, const char* name, int64_t G, AttnOperand* out
     const vt_source& src = d.sources[p.src];
     if (!src.ptr) return fail(VT_ERR_INVALID_ARG, std::string(name) + ": source without a device pointer");
     PlanPiece& a = out->pc[i];
+    memset(&a.pg, 0, sizeof(a.pg));
+    a.page_rows = page_rows;
     a.hdiv = a_hdiv;
     a.ptr = static_cast<const char*>(src.ptr) + p.v.base * esz;
     a.sb = sb * esz;
     a.sh = sh * esz;
+    if (paged) {
+      const int64_t rows = p.hi[2] - p.lo[2];
+      if (!(page_rows % kTile == 0 || page_rows >= rows)) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": pages must hold a multiple of 32 rows");
+      const Digit* T = ctx_table;
+      int64_t W = 1;
+      if (two_stage) {
+        // second stage: one table digit, then digits that together are the identity on [0, W)
+        const Stage& lo = p.v.lower[0];
+        if (lo.digits.empty() || lo.digits[0].table < 0) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": second index stage without a leading table digit");
+        for (size_t k = lo.digits.size(); k-- > 1;) {
+          if (lo.digits[k].table >= 0 || lo.digits[k].stride != W) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": second index stage must be a page table over dense pages");
+          W *= lo.digits[k].radix;
+        }
+        T = &lo.digits[0];
+        int64_t span = p.v.base;     // largest value of the top stage: must stay a 31-bit index
+        for (const auto& grp : p.v.groups)
+          for (const Digit& g : grp) span += (g.radix - 1) * (g.stride > 0 ? g.stride : 0);
+        if (span >= (1ll << 31) || W >= (1ll << 31)) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": paged index space too large");
+        if (p.v.base % 8 || lp % 8 || W % 8 || lo.base % 8) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": paged rows are not 16-byte aligned");
+        a.pg.L0 = p.v.base; a.pg.Lb = sb; a.pg.Lh = sh; a.pg.Lp = lp; a.pg.Lo = st;
+        a.pg.X0 = lo.base;
+      } else {
+        if (p.v.base % 8) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": paged rows are not 16-byte aligned");
+        a.pg.Lp = 1;                 // L = page number within the piece
+        a.pg.X0 = p.v.base; a.pg.Xb = sb; a.pg.Xh = sh; a.pg.Xo = st;
+      }
+      const Table& tb = d.tables[T->table];
+      if (!tb.dev) return fail(VT_ERR_INVALID_ARG, std::string(name) + ": page table without a device pointer");
+      if (sb % 8 || sh % 8 || T->stride % 8) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": paged rows are not 16-byte aligned");
+      a.ptr = static_cast<const char*>(src.ptr);
+      a.pg.tab = tb.dev + T->table_off;
+      a.pg.ps = T->stride;
+      a.pg.W = make_fastdiv((uint32_t)W);
+      a.pg.page = make_fastdiv((uint32_t)page_rows);
+      // the closed form above against the descriptor's own evaluator, on sampled rows
+      if (!tb.host.empty()) {
+        const int64_t Hq = d.shape[1];
+        uint64_t rng = 0x9E3779B97F4A7C15ull;
+        for (int smp = 0; smp < 48; ++smp) {
+          rng = rng * 6364136223846793005ull + 1442695040888963407ull;
+          const int64_t bb = (int64_t)((rng >> 33) % (uint64_t)d.shape[0]);
+          const int64_t hh = (int64_t)((rng >> 13) % (uint64_t)Hq);
+          const int64_t rr = smp == 0 ? rows - 1 : (int64_t)((rng >> 23) % (uint64_t)rows);
+          const int64_t local[4] = {bb, hh, rr, 0};
+          const int64_t want = eval_view(d, p.v, local);
+          const int64_t hs = hh / (G * a_hdiv), pgi = rr / page_rows, row = rr - pgi * page_rows;
+          const int64_t L = a.pg.L0 + bb * a.pg.Lb + hs * a.pg.Lh + pgi * a.pg.Lp + row * a.pg.Lo;
+          const int64_t X = a.pg.X0 + bb * a.pg.Xb + hs * a.pg.Xh + row * a.pg.Xo;
+          const int64_t got = (int64_t)tb.host[T->table_off + L / W] * T->stride + L % W + X;
+          if (got != want) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": paged map does not have the page-table form");
+        }
+      }
+    }
     if (st * esz >= (1ll << 32) || st < 0) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": context stride too large");
     a.st = (uint32_t)(st * esz);
     a.t_lo = (int32_t)p.lo[2];
@@ -601,6 +719,18 @@ int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float s
       sg.v_sb = vo.pc[iv].sb; sg.v_sh = vo.pc[iv].sh; sg.v_st = vo.pc[iv].st; sg.v_hdiv = vo.pc[iv].hdiv;
       sg.t_lo = t;
       sg.t_hi = e;
+      // paged operands: the segment must start on a page boundary and on the 32-row tile grid,
+      // so that no tile straddles two pages
+      for (int which = 0; which < 2; ++which) {
+        const PlanPiece& pc = which == 0 ? ko.pc[ik] : vo.pc[iv];
+        PagedOperand& dst = which == 0 ? sg.kp : sg.vp;
+        dst = pc.pg;
+        if (!pc.pg.tab) continue;
+        const int64_t rel = t - pc.t_lo;
+        if (rel % pc.page_rows || t % kTile) return fail(VT_ERR_UNSUPPORTED, "vt_decode_attn: a paged operand's segment does not start on a page boundary");
+        dst.L0 += rel / pc.page_rows * pc.pg.Lp;
+        (which == 0 ? sg.k : sg.v) = pc.ptr;
+      }
       t = e;
     }
     P.n_seg = n;

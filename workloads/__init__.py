@@ -19,6 +19,7 @@ from .inputs import (  # noqa: F401
     c5_moe_dispatch,
     qkv_proj_store,
     decode_segment,
+    paged_decode_attention,
     qkv_store_chain,
     random_chain,
     CONFIGS,

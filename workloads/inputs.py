@@ -241,6 +241,44 @@ def qkv_proj_store(seed: int = 0, B: int = 8, hidden: int = 4096, Hq: int = 32, 
                     {"kind": "gemm_store", "a": "X", "b": "W", "out": "Cout"})
 
 
+def paged_decode_attention(seed: int = 0, B: int = 8, Hkv: int = 8, G: int = 4, pages_per_seq: int = 32,
+                           page: int = 128, D: int = 128, pool_pages: int = 0, dtype: str = "bf16",
+                           poison_unused: bool = False) -> Workload:
+    """Decode attention over a paged KV cache: K and V live in pools [pool_pages, Hkv, page, D] and
+    sequence b owns the pages bt[b*P .. b*P+P) (distinct, in random order).  The chain gathers the
+    pages (index_select), puts them in context order and broadcasts the kv heads, as a framework
+    without paged kernels would; ``poison_unused`` fills the pages no sequence owns with NaN."""
+    Hq, P = Hkv * G, pages_per_seq
+    S = P * page
+    NP = pool_pages or (B * P + 3)
+    assert NP >= B * P
+    bt = _rng(seed, 5).permutation(NP)[:B * P].astype(np.int32)
+    pools = {}
+    for k, name in ((1, "Kpool"), (2, "Vpool")):
+        x = _rng(seed, k).standard_normal(size=(NP, Hkv, page, D), dtype=np.float32)
+        if poison_unused:
+            unused = np.setdiff1d(np.arange(NP), bt)
+            x[unused] = np.nan
+        pools[name] = encode(x, dtype)
+        del x
+    src = {"Qs": _normal(seed, 0, (B, 1, Hq * D), 1.0, dtype), **pools}
+    chain = [("q1", "reshape", ("Qs",), {"shape": (B, 1, Hq, D)}),
+             ("Q", "permute", ("q1",), {"perm": (0, 2, 1, 3)})]
+    for nm, pool in (("k", "Kpool"), ("v", "Vpool")):
+        chain += [
+            (nm + "g", "index_select", (pool,), {"dim": 0, "index": "bt"}),                 # [B*P, Hkv, page, D]
+            (nm + "r", "reshape", (nm + "g",), {"shape": (B, P, Hkv, page, D)}),
+            (nm + "t", "permute", (nm + "r",), {"perm": (0, 2, 1, 3, 4)}),                    # [B, Hkv, P, page, D]
+            (nm + "c", "reshape", (nm + "t",), {"shape": (B, Hkv, S, D)}),
+            (nm + "u", "unsqueeze", (nm + "c",), {"dim": 2}),
+            (nm + "x", "expand", (nm + "u",), {"shape": (B, Hkv, G, S, D)}),
+            (nm.upper(), "reshape", (nm + "x",), {"shape": (B, Hq, S, D)}),
+        ]
+    return Workload("paged_decode_attention", dtype, src, chain,
+                    {"kind": "decode_attn", "q": "Q", "k": "K", "v": "V", "scale": 1.0 / float(np.sqrt(D))},
+                    index_tables={"bt": bt})
+
+
 def decode_segment(seed: int = 0, B: int = 8, hidden: int = 4096, Hkv: int = 8, G: int = 4, D: int = 128,
                    cap: int = 4096, pos: int = 4095, dtype: str = "bf16"):
     """The paper's motivating example end to end (Sec. 3.1): the merged QKV projection stores Q
@@ -272,6 +310,7 @@ CONFIGS = {
     "c4": c4_window_ln_linear,
     "c5": c5_moe_dispatch,
     "qkv_store": qkv_proj_store,
+    "paged": paged_decode_attention,
 }
 
 
