@@ -92,19 +92,22 @@ k_ln_gemm(const LnGemmParams P) {
   constexpr int RPP = LTHREADS / LPR;        // rows staged per pass of the workgroup
   constexpr int PASSES = LBM / RPP;
   constexpr int CW = NB * 16;                // output columns per wave
-  constexpr int CPITCH = CW * 2 + 16;        // bytes per staged row (16-byte aligned, de-phased banks)
-  constexpr int kABytes = 2 * LBM * LPR * 16, kCBytes = LWAVES * LBM * CPITCH, kWBytes = LWAVES * CW * K * 2;
-  constexpr int kLdsBytes = kABytes + kCBytes > kWBytes ? kABytes + kCBytes : kWBytes;
+  constexpr int kTileUnits = LBM * LPR;      // 16-byte units of one A tile
+  constexpr int CPW = LWAVES * CW * 2 + 16;  // bytes per row of the staged C tile (16 more than a row: de-phased banks)
+  constexpr int kTilesBytes = 3 * kTileUnits * 16, kCBytes = C_F32 ? 0 : 2 * LBM * CPW, kWBytes = LWAVES * CW * K * 2;
+  constexpr int kRegion0 = kCBytes > kWBytes ? kCBytes : kWBytes;   // W^T during the prologue, then the C tiles
+  constexpr int kLdsBytes = kRegion0 + kTilesBytes;
   __shared__ __attribute__((aligned(16))) char lds_raw[kLdsBytes];
-  // steady state: two A tiles [row][LPR chunks of 8 k] (chunk c of row r at r*LPR + (c ^ (r & 7))) and
-  // one staging area per wave for its C sub-tile; during the prologue the same memory holds W^T
-  // Rows of A travel global -> LDS without touching registers (three blocks deep).  Each lane later
-  // reads back exactly the 16 bytes its own request delivered, so the memory needs no barrier; it
-  // is an object of its own, touched only by those requests and by the read below, so that no
-  // other LDS access is ordered against a request still in flight.
-  __shared__ __attribute__((aligned(16))) uint4 lds_rows[3][LBM * LPR];
-  uint4 (*ldsA)[LBM * LPR] = reinterpret_cast<uint4 (*)[LBM * LPR]>(lds_raw);
-  char (*ldsC)[LBM * CPITCH] = reinterpret_cast<char (*)[LBM * CPITCH]>(lds_raw + kABytes);
+  // Steady state: two C tiles [row][N] (16-bit outputs only; during the prologue their memory holds
+  // W^T) and three A tiles [row][LPR chunks of 8 k] (chunk c of row r at r*LPR + (c ^ (r & 7))), which
+  // W^T never overlaps: the first rows are already arriving while W is transposed.
+  // A tile goes through three states in place: rows arriving from global memory (requested two
+  // blocks ahead, global -> LDS without touching registers, already in the swizzled order: the lane
+  // that lands at position p of row r asks for chunk p ^ (r & 7)); normalised (each lane reads
+  // back exactly the 16 bytes its own request delivered, so this needs no barrier, and writes the
+  // result to the same place); multiplied.
+  uint4* tiles = reinterpret_cast<uint4*>(lds_raw + kRegion0);
+  char* cstage = lds_raw;
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int l16 = lane & 15, lg = lane >> 4;
@@ -143,17 +146,17 @@ k_ln_gemm(const LnGemmParams P) {
     ro32 = (uint32_t)(ro * 2);
   };
   typedef __attribute__((address_space(3))) void* lptr_t;
-  auto load_rows = [&](int j, int slot) {               // block j of the evaluated batch -> lds_rows[slot]
+  auto load_rows = [&](int j, int slot) {               // block j of the evaluated batch -> tile `slot`
 #pragma unroll
     for (int i = 0; i < PASSES; ++i) {
       const uint32_t o = (uint32_t)__shfl((int)ro32, j * 8 + i * RW + lane / LPR, 64);
-      // lane l of the wave lands at (wave base) + 16 l: rows wave*RW + RPP*i .. + RW, unswizzled
-      // Written as assembly so that the request stays unknown to the compiler, which would
-      // otherwise order every later LDS access of the kernel behind it; the waits for these
-      // requests are the explicit ones below.
-      const uint32_t dst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lptr_t)&lds_rows[slot][(wave * RW + RPP * i) * LPR]);
+      const int r = a_r0 + RPP * i;                     // row of the block this lane serves
+      // lane l of the wave lands at (wave base) + 16 l.  Written as assembly so that the request
+      // stays unknown to the compiler, which would otherwise order every later LDS access of the
+      // kernel behind it; the waits for these requests are the explicit ones below.
+      const uint32_t dst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lptr_t)&tiles[slot * kTileUnits + (wave * RW + RPP * i) * LPR]);
       asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                   :: "v"(o + a_c * 16), "s"(P.a), "s"(dst) : "memory", "m0");
+                   :: "v"(o + ((a_c ^ (r & 7)) * 16)), "s"(P.a), "s"(dst) : "memory", "m0");
     }
   };
   // the first two blocks' rows are requested before anything else: their latency hides behind the W prologue
@@ -245,12 +248,13 @@ k_ln_gemm(const LnGemmParams P) {
   constexpr int kInFlight = 2 * kStores + PASSES;
   constexpr int kWaitRows = (kInFlight & 15) | ((kInFlight >> 4) << 14) | 0x0F70;   // s_waitcnt vmcnt(kInFlight)
   static_assert(kInFlight < 64, "vmcnt has 6 bits");
-  // LayerNorm of the rows parked in lds_rows[slot] (each row spread over LPR consecutive lanes),
-  // then -> LDS tile `buf`
-  auto norm_store = [&](int buf, int slot) {
+  // LayerNorm in place of the rows that landed in tile `slot` (each row spread over LPR
+  // consecutive lanes; a lane reads the 16 bytes of its own request and writes them back normalised)
+  auto norm_tile = [&](int slot) {
     u32x4 raw[PASSES];
+    uint4* mine = &tiles[slot * kTileUnits + wave * RW * LPR + lane];
     {
-      const uint32_t addr = (uint32_t)(uintptr_t)(lptr_t)&lds_rows[slot][wave * RW * LPR + lane];
+      const uint32_t addr = (uint32_t)(uintptr_t)(lptr_t)mine;
       if constexpr (PASSES == 1)
         asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(raw[0]) : "v"(addr) : "memory");
       else
@@ -279,29 +283,53 @@ k_ln_gemm(const LnGemmParams P) {
       Vec<T, 8> o;
 #pragma unroll
       for (int j = 0; j < 8; ++j) o.v[j] = from_float<T>(x[j] * rstd);
-      const int r = a_r0 + RPP * i;
-      ldsA[buf][r * LPR + (a_c ^ (r & 7))] = __builtin_bit_cast(uint4, o);
+      mine[i * RPP * LPR] = __builtin_bit_cast(uint4, o);
     }
   };
   static_assert(PASSES <= 2, "the read-back above handles one or two passes");
 
-  int it = 0;
-  int slot_req = 2;                                   // where the next request lands: block it+2 -> slot (it+2) % 3
+  // 16-bit outputs leave through the staged C tile one step after they were computed: a wave
+  // writes 8 complete rows (6 x 1 KB, whole cache lines) with streaming stores.  The buffer
+  // descriptor ends with the block, so rows past it are dropped by the hardware; lanes whose
+  // columns are past N get an offset outside it.  No store is conditional: every step issues the
+  // same number of memory operations, which the explicit wait for the rows relies on (for the
+  // step that has no finished block yet the descriptor is empty).
+  auto store_block = [&](int cs, int64_t row0, int64_t r_end) {
+    const uint64_t c_skip = (uint64_t)row0 * (uint64_t)N * 2u;
+    const uint64_t c_left = (uint64_t)(r_end - row0) * (uint64_t)N * 2u;
+    const __amdgpu_buffer_rsrc_t c_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        P.c + c_skip, 0, (int)min(c_left, (uint64_t)0x7fffffffu), 0x00020000);
+    const char* sc = cstage + cs * (LBM * CPW);
+#pragma unroll
+    for (int q = 0; q < kStores; ++q) {
+      const int id = q * 64 + lane;
+      const int rl = id / CW, ch = id - rl * CW;          // CW 16-byte chunks per row of 8 waves x CW columns
+      const int r = wave * (LBM / LWAVES) + rl, col = ch * 8;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(sc + r * CPW + ch * 16);
+      const uint32_t off = col < N ? (uint32_t)(r * N + col) * 2u : 0x80000000u;
+      __builtin_amdgcn_raw_buffer_store_b128(v, c_rsrc, (int)off, 0, 2);   // streaming: no dirty lines left in L2
+    }
+  };
+
+  int it = 0, slot = 0;                               // block `it` is multiplied from tile `slot` = it % 3
+  int64_t prev_row0 = 0, prev_end = 0;                // the block whose outputs wait in the staged C tile
   __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): the first two blocks' rows are in LDS
-  norm_store(0, 0);
-  auto step = [&](auto parity) {
-    constexpr int buf = decltype(parity)::value;
+  norm_tile(0);
+  for (;;) {
     int64_t row0, r_end;
     block_rows(it, &row0, &r_end);
-    __syncthreads();                                  // tile `buf` is complete; tile buf^1 is free again
+    __syncthreads();                                  // tile `slot` is normalised; the staged C tile of the previous step is complete
     {
-      // request the rows two blocks ahead, unconditionally (past the end of the range they are not
-      // used): the explicit wait below counts on the same number of operations in every step
+      // request the rows two blocks ahead, unconditionally (past the end they are not used): the
+      // explicit wait below counts on the same number of operations in every step.  Their tile held
+      // block it - 1, which every wave finished multiplying before it arrived at the barrier.
       const int j = (it + 2) & 7;
       if (j == 0) eval_rows(it + 2);
-      load_rows(j, slot_req);
+      load_rows(j, slot == 0 ? 2 : slot - 1);
     }
+    if (!C_F32) store_block((it & 1) ^ 1, prev_row0, prev_end);
     f32x4 acc[LBM / 16][NB];
+    const uint4* tile = tiles + slot * kTileUnits;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       opvec af[LBM / 16];
@@ -309,7 +337,7 @@ k_ln_gemm(const LnGemmParams P) {
 #pragma unroll
       for (int mb = 0; mb < LBM / 16; ++mb) {
         const int r = mb * 16 + l16;
-        af[mb] = __builtin_bit_cast(opvec, ldsA[buf][r * LPR + (chunk ^ (r & 7))]);
+        af[mb] = __builtin_bit_cast(opvec, tile[r * LPR + (chunk ^ (r & 7))]);
       }
 #pragma unroll
       for (int mb = 0; mb < LBM / 16; ++mb)
@@ -319,17 +347,14 @@ k_ln_gemm(const LnGemmParams P) {
           acc[mb][nb] = M_::run(wf[ks][nb], af[mb], c0);   // C^T block: rows = n, cols = m
         }
     }
-    // ---- stage 3: lane holds row m = mb*16 + l16 and columns nb*16 + lg*4 + (0..3).
-    // C is written through a buffer descriptor that starts at this block's first row and ends with
-    // the block: rows past it fall outside and the hardware drops them; lanes whose
-    // columns are past N get an offset outside it.  No store is conditional: every step issues the
-    // same number of memory operations, which the explicit wait for the rows relies on.
-    constexpr int kEs = C_F32 ? 4 : 2;
-    const uint64_t c_skip = (uint64_t)row0 * (uint64_t)N * kEs;
-    const uint64_t c_left = (uint64_t)(r_end - row0) * (uint64_t)N * kEs;
-    const __amdgpu_buffer_rsrc_t c_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        P.c + c_skip, 0, (int)min(c_left, (uint64_t)0x7fffffffu), 0x00020000);
+    // ---- stage 3: lane holds row m = mb*16 + l16 and columns nb*16 + lg*4 + (0..3)
     if (C_F32) {
+      // fp32 outputs go straight from the accumulators (16 bytes per lane), through a buffer
+      // descriptor that ends with the block
+      const uint64_t c_skip = (uint64_t)row0 * (uint64_t)N * 4u;
+      const uint64_t c_left = (uint64_t)(r_end - row0) * (uint64_t)N * 4u;
+      const __amdgpu_buffer_rsrc_t c_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+          P.c + c_skip, 0, (int)min(c_left, (uint64_t)0x7fffffffu), 0x00020000);
 #pragma unroll
       for (int mb = 0; mb < LBM / 16; ++mb)
 #pragma unroll
@@ -339,7 +364,7 @@ k_ln_gemm(const LnGemmParams P) {
           __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[mb][nb]), c_rsrc, (int)off, 0, 0);
         }
     } else {
-      char* sc = ldsC[wave];
+      char* sc = cstage + (it & 1) * (LBM * CPW);
 #pragma unroll
       for (int mb = 0; mb < LBM / 16; ++mb)
 #pragma unroll
@@ -347,31 +372,22 @@ k_ln_gemm(const LnGemmParams P) {
           Vec<T, 4> o;
 #pragma unroll
           for (int i = 0; i < 4; ++i) o.v[i] = from_float<T>(acc[mb][nb][i]);
-          *reinterpret_cast<Vec<T, 4>*>(sc + (mb * 16 + l16) * CPITCH + (nb * 16 + lg * 4) * 2) = o;
+          *reinterpret_cast<Vec<T, 4>*>(sc + (mb * 16 + l16) * CPW + (wave * CW + nb * 16 + lg * 4) * 2) = o;
         }
-      // wave-local: the same wave reads back what it wrote (LDS operations of a wave stay in order)
-      constexpr int CH = CW / 8;             // 16-byte chunks per staged row
-#pragma unroll
-      for (int q = 0; q < LBM * CH / 64; ++q) {
-        const int id = q * 64 + lane;
-        const int r = id / CH, ch = id - r * CH;
-        const int col = wave * CW + ch * 8;
-        const u32x4 v = *reinterpret_cast<const u32x4*>(sc + r * CPITCH + ch * 16);
-        const uint32_t off = col < N ? (uint32_t)(r * N + col) * 2u : 0x80000000u;
-        __builtin_amdgcn_raw_buffer_store_b128(v, c_rsrc, (int)off, 0, 0);
-      }
+      prev_row0 = row0;
+      prev_end = r_end;
     }
+    const int nslot = slot == 2 ? 0 : slot + 1;
     if (it + 1 < n_it) {
       __builtin_amdgcn_s_waitcnt(kWaitRows);          // the rows requested one step ago have landed
-      norm_store(buf ^ 1, slot_req == 0 ? 2 : slot_req - 1);
+      norm_tile(nslot);
     }
-    slot_req = slot_req == 2 ? 0 : slot_req + 1;
-  };
-  for (;;) {
-    step(std::integral_constant<int, 0>{});
+    slot = nslot;
     if (++it >= n_it) break;
-    step(std::integral_constant<int, 1>{});
-    if (++it >= n_it) break;
+  }
+  if (!C_F32) {
+    __syncthreads();                                  // the last staged C tile is complete
+    store_block((it & 1) ^ 1, prev_row0, prev_end);
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);                 // requests past the last block still target this workgroup's LDS
 }
