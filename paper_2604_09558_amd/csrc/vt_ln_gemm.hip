@@ -79,6 +79,7 @@ struct LnGemmParams {
   float eps;
   int32_t w_rows_of_8;   // W has runs of 8 contiguous, 16-byte aligned elements along N: coalesced prologue
   int32_t w_k_runs_of_8; // rows 8i .. 8i+7 of W are equally spaced (innermost K digit has a radix that 8 divides)
+  FastDiv n8, nblk;      // N / 8 and (N / 8) * (K / 8): divisors of the W prologue
 };
 
 // LPR = lanes per row = K / 8; NB = 16-column blocks per wave
@@ -164,83 +165,6 @@ k_ln_gemm(const LnGemmParams P) {
   load_rows(0, 0);
   load_rows(1, 1);
 
-  // ---- this wave's slice of W as MFMA operands (lane: column n = wave*CW + nb*16 + l16, the 8
-  // consecutive k of its quarter), kept in registers for the whole kernel
-  opvec wf[KS][NB];
-  if (P.w_rows_of_8) {
-    // coalesced: 8x8 blocks of W are loaded row-wise (16 bytes per lane), transposed in registers
-    // and parked in LDS as W^T [n][k]; every wave then picks its operands with ds_read_b128
-    uint4* ldsW = reinterpret_cast<uint4*>(lds_raw);   // unit (n, kc) at n*LPR + (kc ^ ((n ^ (n >> 3)) & 7))
-    const int nblk = (N / 8) * LPR;                    // 8x8 blocks: N/8 across, K/8 down; at most 2 per thread
-    static_assert(48 * LPR <= 2 * LTHREADS, "two rounds cover W");
-    uint4 rb[2][8];
-    // Every workgroup reads all of W at the same moment; each starts at a different block so
-    // that they do not all queue on the same L2 channel.
-    const int rot = (int)((blockIdx.x * 61u) % (uint32_t)nblk);
-    int kbs[2], cns[2];
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {                      // all loads of both rounds are in flight together
-      const int idx = t + r * LTHREADS;
-      if (idx < nblk) {
-        int bidx = idx + rot;
-        bidx = bidx >= nblk ? bidx - nblk : bidx;
-        const int kb = bidx / (N / 8), cn = bidx - kb * (N / 8);
-        kbs[r] = kb, cns[r] = cn;
-        const char* bp = P.b + axis_off(P.b_col, (uint32_t)(cn * 8)) * 2;
-        if (P.w_k_runs_of_8) {                         // the 8 rows of a block are one stride apart
-          bp += axis_off(P.b_row, (uint32_t)(kb * 8)) * 2;
-          const int64_t rs = P.b_row.stride[2] * 2;
-#pragma unroll
-          for (int j = 0; j < 8; ++j) rb[r][j] = *reinterpret_cast<const uint4*>(bp + j * rs);
-        } else {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) rb[r][j] = *reinterpret_cast<const uint4*>(bp + axis_off(P.b_row, (uint32_t)(kb * 8 + j)) * 2);
-        }
-      }
-    }
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
-      if (t + r * LTHREADS < nblk) {
-        const int kb = kbs[r], cn = cns[r];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-          uint32_t w[4];
-#pragma unroll
-          for (int u = 0; u < 4; ++u) w[u] = __builtin_amdgcn_perm(word(rb[r][2 * u + 1], e >> 1), word(rb[r][2 * u], e >> 1), sel);
-          const int n = cn * 8 + e;
-          ldsW[n * LPR + (kb ^ ((n ^ (n >> 3)) & 7))] = make_uint4(w[0], w[1], w[2], w[3]);
-        }
-      }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      const int n = wave * CW + nb * 16 + l16;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (n < N) v = ldsW[n * LPR + ((ks * 4 + lg) ^ ((n ^ (n >> 3)) & 7))];
-        wf[ks][nb] = __builtin_bit_cast(opvec, v);
-      }
-    }
-    __syncthreads();                                   // W^T is no longer needed: the memory becomes tiles
-  } else {
-    const T* bp = reinterpret_cast<const T*>(P.b);
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      const int n = wave * CW + nb * 16 + l16;
-      const int64_t co = axis_off(P.b_col, (uint32_t)min(n, N - 1));
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        Vec<T, 8> e;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) e.v[j] = bp[axis_off(P.b_row, (uint32_t)(ks * 32 + lg * 8 + j)) + co];
-        wf[ks][nb] = __builtin_bit_cast(opvec, e);
-      }
-    }
-  }
-
   // Memory operations a step issues after its row requests; together with the next step's requests
   // they are what may still be in flight when the rows requested one step earlier are needed
   // (vector memory operations complete in the order they were issued).
@@ -288,6 +212,94 @@ k_ln_gemm(const LnGemmParams P) {
   };
   static_assert(PASSES <= 2, "the read-back above handles one or two passes");
 
+  bool normed0 = false;
+
+  // ---- this wave's slice of W as MFMA operands (lane: column n = wave*CW + nb*16 + l16, the 8
+  // consecutive k of its quarter), kept in registers for the whole kernel
+  opvec wf[KS][NB];
+  if (P.w_rows_of_8) {
+    // coalesced: 8x8 blocks of W are loaded row-wise (16 bytes per lane), transposed in registers
+    // and parked in LDS as W^T [n][k]; every wave then picks its operands with ds_read_b128
+    uint4* ldsW = reinterpret_cast<uint4*>(lds_raw);   // unit (n, kc) at n*LPR + (kc ^ ((n ^ (n >> 3)) & 7))
+    const int nblk = (N / 8) * LPR;                    // 8x8 blocks: N/8 across, K/8 down; at most 2 per thread
+    static_assert(48 * LPR <= 2 * LTHREADS, "two rounds cover W");
+    uint4 rb[2][8];
+    // Every workgroup reads all of W at the same moment; each starts at a different block so
+    // that they do not all queue on the same L2 channel.
+    const uint32_t rot61 = blockIdx.x * 61u;
+    const int rot = (int)(rot61 - fdiv(rot61, P.nblk) * P.nblk.d);
+    int kbs[2], cns[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {                      // all loads of both rounds are in flight together
+      const int idx = t + r * LTHREADS;
+      {
+        // every thread issues all 16 loads (a thread without a block of its own reads the last
+        // one again and drops it): the number of loads in flight is then the same everywhere,
+        // and the wait for the rows that were requested before them can be an exact count
+        int bidx = min(idx, nblk - 1) + rot;
+        bidx = bidx >= nblk ? bidx - nblk : bidx;
+        const int kb = (int)fdiv((uint32_t)bidx, P.n8), cn = bidx - kb * (N / 8);
+        kbs[r] = kb, cns[r] = cn;
+        const char* bp = P.b + axis_off(P.b_col, (uint32_t)(cn * 8)) * 2;
+        if (P.w_k_runs_of_8) {                         // the 8 rows of a block are one stride apart
+          bp += axis_off(P.b_row, (uint32_t)(kb * 8)) * 2;
+          const int64_t rs = P.b_row.stride[2] * 2;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) rb[r][j] = *reinterpret_cast<const uint4*>(bp + j * rs);
+        } else {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) rb[r][j] = *reinterpret_cast<const uint4*>(bp + axis_off(P.b_row, (uint32_t)(kb * 8 + j)) * 2);
+        }
+      }
+    }
+    // block 0's rows were requested before W and have landed by now: normalise them while W is
+    // still on its way (16 loads are in flight behind them)
+    __builtin_amdgcn_s_waitcnt(0x4F70);                // vmcnt(16)
+    norm_tile(0);
+    normed0 = true;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      if (t + r * LTHREADS < nblk) {
+        const int kb = kbs[r], cn = cns[r];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+          uint32_t w[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) w[u] = __builtin_amdgcn_perm(word(rb[r][2 * u + 1], e >> 1), word(rb[r][2 * u], e >> 1), sel);
+          const int n = cn * 8 + e;
+          ldsW[n * LPR + (kb ^ ((n ^ (n >> 3)) & 7))] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int n = wave * CW + nb * 16 + l16;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (n < N) v = ldsW[n * LPR + ((ks * 4 + lg) ^ ((n ^ (n >> 3)) & 7))];
+        wf[ks][nb] = __builtin_bit_cast(opvec, v);
+      }
+    }
+    __syncthreads();                                   // W^T is no longer needed: the memory becomes tiles
+  } else {
+    const T* bp = reinterpret_cast<const T*>(P.b);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int n = wave * CW + nb * 16 + l16;
+      const int64_t co = axis_off(P.b_col, (uint32_t)min(n, N - 1));
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        Vec<T, 8> e;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e.v[j] = bp[axis_off(P.b_row, (uint32_t)(ks * 32 + lg * 8 + j)) + co];
+        wf[ks][nb] = __builtin_bit_cast(opvec, e);
+      }
+    }
+  }
+
   // 16-bit outputs leave through the staged C tile one step after they were computed: a wave
   // writes 8 complete rows (6 x 1 KB, whole cache lines) with streaming stores.  The buffer
   // descriptor ends with the block, so rows past it are dropped by the hardware; lanes whose
@@ -314,7 +326,7 @@ k_ln_gemm(const LnGemmParams P) {
   int it = 0, slot = 0;                               // block `it` is multiplied from tile `slot` = it % 3
   int64_t prev_row0 = 0, prev_end = 0;                // the block whose outputs wait in the staged C tile
   __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): the first two blocks' rows are in LDS
-  norm_tile(0);
+  if (!normed0) norm_tile(0);
   for (;;) {
     int64_t row0, r_end;
     block_rows(it, &row0, &r_end);
@@ -470,6 +482,8 @@ int ln_gemm_launch(const vt_desc& A, const vt_desc& B, void* C, int c_dtype, flo
   P.w_rows_of_8 = (uintptr_t)P.b % 16 == 0 && P.b_col.stride[2] == 1 && P.b_col.radix[2].d % 8 == 0 &&
                   strides_multiple_of(P.b_col, 8, 1) && strides_multiple_of(P.b_row, 8, 0);
   P.w_k_runs_of_8 = P.b_row.radix[2].d % 8 == 0;
+  P.n8 = make_fastdiv((uint32_t)(N / 8));
+  P.nblk = make_fastdiv((uint32_t)((N / 8) * (K / 8)));
   P.c = static_cast<char*>(C);
   P.M = (int32_t)M;
   P.N = (int32_t)N;
