@@ -82,10 +82,12 @@ struct Regs16 {
   uint32_t w[4];
 };
 
+// B is read exactly once per launch: streaming (nontemporal) loads
 __device__ __forceinline__ Regs16 load16(const char* p) {
-  uint4 t = *reinterpret_cast<const uint4*>(p);
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
   Regs16 r;
-  r.w[0] = t.x; r.w[1] = t.y; r.w[2] = t.z; r.w[3] = t.w;
+  r.w[0] = t[0]; r.w[1] = t[1]; r.w[2] = t[2]; r.w[3] = t[3];
   return r;
 }
 
