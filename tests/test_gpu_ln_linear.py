@@ -89,3 +89,20 @@ def test_constant_rows_give_zero(gpu):
     p.run()
     torch.cuda.synchronize()
     assert np.all(tio.to_host_f64(p.out) == 0.0)
+
+
+def test_c4_one_full_round_plus_a_partial_one_and_f32_output(gpu):
+    """21 952 rows on 256 compute units: one round of full blocks, then 87 workgroups with one more
+    block (the last of them ragged); also the fp32-output path of the fused kernel."""
+    vt, tio, pipelines, torch = gpu
+    wl = workloads.c4_window_ln_linear(seed=4, B=7, R=56, win=7, C=128, N=384)
+    ref = run_workload(wl)["out"]
+    p = pipelines.Gemm(tio.DeviceWorkload(wl), fused=True)
+    p.run()
+    torch.cuda.synchronize()
+    check(tio.to_host_f64(p.out).reshape(ref.shape), ref)
+    out32 = torch.empty((ref.shape[0] * ref.shape[1], ref.shape[2]), dtype=torch.float32, device="cuda:0")
+    vt.vt_gemm(p.A, p.B, [out32.data_ptr()], "f32", vt.GEMM_LAYERNORM, p.eps)
+    torch.cuda.synchronize()
+    # no final rounding to fp16: only the fp16 rounding of the normalised rows remains
+    check(out32.cpu().numpy().astype(np.float64).reshape(ref.shape), ref, atol=2e-3, rtol=2e-3)
