@@ -119,7 +119,7 @@ def cpu_baseline_c2(wl, alg_bytes):
             "sample": "one full pass of config 2 (B=8, context 4096): %.2f s wall" % dt, "seconds": dt}
 
 
-def chain_stats(torch, name, steps):
+def chain_stats(torch, name, steps, a_no_graph=False):
     """Virtual and materialized (every operator an explicit copy kernel) timings of one of the
     other benchmark chains; inputs rotate over enough copies to defeat the Infinity Cache where
     the working set is small."""
@@ -173,7 +173,10 @@ def chain_stats(torch, name, steps):
     torch.cuda.synchronize()
     mk = lambda p: (lambda stream: p.run(stream))      # noqa: E731
     n = steps
-    v_wall, v_ev = time_steps(torch, [mk(p) for p in virt], n, max(2, n // 10), False)
+    # short kernels are launched from one HIP graph, like the main line (a Python launch costs more than they run)
+    graph_ok = name in ("c1", "c4", "qkv_store") and not a_no_graph
+    rep = 16 // len(virt) + 1 if graph_ok else 1     # a graph replay should hold a good number of launches
+    v_wall, v_ev = time_steps(torch, [mk(p) for p in virt] * rep, n, max(2, n // 10), graph_ok)
     out = {"virtual_us": round(v_ev * 1e3, 2)}
     p0 = virt[0]
     if name in ("c3", "c5", "c4"):
@@ -194,14 +197,15 @@ def chain_stats(torch, name, steps):
         out["hbm_pct_of_peak"] = round(100.0 * alg / (v_ev * 1e-3) / 1e9 / HBM_PEAK_GBS, 1)
         mats = [pipelines.make_pipeline(dw, materialized=True) for dw in dws]
         torch.cuda.synchronize()
-        m_wall, m_ev = time_steps(torch, [mk(p) for p in mats], n, max(2, n // 10), False)
+        m_wall, m_ev = time_steps(torch, [mk(p) for p in mats] * (1 if a_no_graph else 3), n, max(2, n // 10), not a_no_graph)
         out["materialized_full_us"] = round(m_ev * 1e3, 2)
         out["speedup_vs_materialized_full"] = round(m_ev / v_ev, 3)
         out["intermediate_bytes_saved"] = int(M * N * 2)
         return out
     mat = pipelines.make_pipeline(dws[0], materialized=True)
     torch.cuda.synchronize()
-    m_wall, m_ev = time_steps(torch, [mk(mat)], max(3, n // 4), 2, False)
+    m_graph = name == "c1" and not a_no_graph
+    m_wall, m_ev = time_steps(torch, [mk(mat)] * (16 if m_graph else 1), max(16 if m_graph else 3, n // 4), 2, m_graph)
     out["materialized_full_us"] = round(m_ev * 1e3, 2)
     out["speedup_vs_materialized_full"] = round(m_ev / v_ev, 3)
     out["intermediate_bytes_saved"] = int(mat.mat.bytes_written)
@@ -310,7 +314,7 @@ def main():
         torch.cuda.empty_cache()
         out["chains"] = {}
         for name in a.extra.split(","):
-            out["chains"][name] = chain_stats(torch, name, {"c1": 200, "c3": 30, "c4": 100, "c5": 6, "qkv_store": 200, "decode_segment": 120, "paged": 200}[name])
+            out["chains"][name] = chain_stats(torch, name, a_no_graph=a.no_graph, steps={"c1": 200, "c3": 30, "c4": 100, "c5": 6, "qkv_store": 200, "decode_segment": 120, "paged": 200}[name])
             torch.cuda.empty_cache()
 
     if not a.no_cpu_baseline:
