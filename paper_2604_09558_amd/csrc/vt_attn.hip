@@ -6,8 +6,9 @@
 // split's rows in tiles of 32.  All G query heads of the group are served from one read of
 // K and V (the broadcast digit of the descriptor, i.e. the Expand that is never executed).
 // The context is cut into segments at the piece boundaries of the two descriptors (the
-// Concat that is never executed); a tile never straddles a segment, so inside a tile a row
-// address is one wave-uniform base plus a per-lane constant.
+// Concat that is never executed).  Inside a segment a row address is one wave-uniform base
+// plus a per-lane constant; a tile in which a segment ends continues in the next one with
+// per-lane row addresses (so the fresh K/V row behind the cached ones costs no tile of its own).
 //
 // Per tile of 32 context rows and per wave:
 //   S^T = K . Q^T   on v_mfma_f32_16x16x32 (rows = context, cols = the group's heads, padded
@@ -137,18 +138,23 @@ __device__ __forceinline__ Regs16 load16(const char* base, uint32_t off) {
   return r;
 }
 
-// Walks the 32-row tiles of a split [t_begin, t_end).  Tiles never straddle a segment, so the
-// walk goes segment by segment; everything the loads of a tile need from its segment (row
-// pointers of this (b, g), row pitches, the clipped range) is fetched from the kernel
-// arguments once, when the walk enters the segment, and then lives in scalar registers: the
-// loop over tiles reads no kernel argument.  All values are wave-uniform.
+// The 32-row tiles of a split [t_begin, t_end) are taken one after the other.  A tile lies in one
+// segment, or - where a segment ends inside it - continues into the next one (rows >= cut come
+// from there): the fresh K/V row appended behind 4095 cached rows then costs no extra tile.
+// Tiles do not continue across a boundary with a paged operand (a tile has one page).  All
+// values are wave-uniform.
 struct TileWalk {
-  const char* k;         // K row t_lo of this (b, g) in the current segment
+  const char* k;         // K row t_lo of this (b, g) in the tile's (first) segment
   const char* v;
   uint32_t k_st, v_st;   // bytes per context row
-  int t_lo;              // first row of the segment
-  int r0, end;           // current tile: rows [r0, min(r0 + 32, end)) ; end = clipped end of the segment
-  int seg;               // current segment, P.n_seg when the walk is over
+  int t_lo;              // first row of that segment
+  int r0, end;           // the tile: rows [r0, end), at most 32
+  int seg_end;           // end of the tile's (first) segment, clipped to the split
+  int seg;               // its (first) segment, P.n_seg when the walk is over
+  int cut, seg2;         // rows >= cut belong to segment seg2 (cut = INT_MAX, seg2 = -1: one segment only)
+  const char* k2;        // K row `cut` of this (b, g) in segment seg2
+  const char* v2;
+  uint32_t k2_st, v2_st;
 };
 
 // One table entry, read on the scalar unit (the table is read-only for the kernel; a vector
@@ -178,34 +184,72 @@ __device__ __forceinline__ void walk_locate(const AttnParams& P, TileWalk& w, in
   if (sg.vp.tab) w.v = paged_base(sg.vp, sg.v, sg.v_st, b, g / sg.v_hdiv, w.r0 - sg.t_lo);
 }
 
-__device__ __forceinline__ void walk_enter(const AttnParams& P, TileWalk& w, int seg, int b, int g, int t_begin, int t_end) {
-  // skip segments that do not meet the split
-  while (seg < P.n_seg && min(P.seg[seg].t_hi, t_end) <= max(P.seg[seg].t_lo, t_begin)) ++seg;
+// The tile that starts at row r0 of segment seg (r0 inside the segment and the split).
+__device__ __forceinline__ void walk_place(const AttnParams& P, TileWalk& w, int seg, int r0, int t_end) {
   w.seg = seg;
-  if (seg >= P.n_seg) return;
-  const AttnSeg& sg = P.seg[seg];
+  w.r0 = r0;
+  w.cut = 0x7fffffff;
+  w.seg2 = -1;
+  const int seg_end = min(P.seg[seg].t_hi, t_end);
+  w.seg_end = seg_end;
+  w.end = min(r0 + kTile, seg_end);
+  if (w.end < r0 + kTile && seg_end < t_end && seg + 1 < P.n_seg) {
+    const AttnSeg& A = P.seg[seg];
+    const AttnSeg& B = P.seg[seg + 1];
+    if (!A.kp.tab && !A.vp.tab && !B.kp.tab && !B.vp.tab) {
+      w.cut = seg_end;
+      w.seg2 = seg + 1;
+      w.end = min(r0 + kTile, min(B.t_hi, t_end));
+    }
+  }
+}
+
+// The tile after the current one; w.seg = P.n_seg when there is none.
+__device__ __forceinline__ void walk_next(const AttnParams& P, TileWalk& w, int t_end) {
+  const int r0 = w.end;
+  int seg = w.seg2 >= 0 ? w.seg2 : w.seg;
+  while (seg < P.n_seg && r0 >= min(P.seg[seg].t_hi, t_end)) ++seg;
+  if (seg >= P.n_seg || r0 >= t_end) {
+    w.seg = P.n_seg;
+    return;
+  }
+  walk_place(P, w, seg, r0, t_end);
+}
+
+// Row pointers and pitches of the tile that walk_place / walk_next chose.
+__device__ __forceinline__ void walk_fetch(const AttnParams& P, TileWalk& w, int b, int g) {
+  const AttnSeg& sg = P.seg[w.seg];
   w.k = sg.k + b * sg.k_sb + (g / sg.k_hdiv) * sg.k_sh;
   w.v = sg.v + b * sg.v_sb + (g / sg.v_hdiv) * sg.v_sh;
   w.k_st = sg.k_st;
   w.v_st = sg.v_st;
   w.t_lo = sg.t_lo;
-  w.r0 = max(sg.t_lo, t_begin);
-  w.end = min(sg.t_hi, t_end);
   if (sg.kp.tab || sg.vp.tab) walk_locate(P, w, b, g);
+  if (w.seg2 >= 0) {
+    const AttnSeg& s2 = P.seg[w.seg2];
+    w.k2 = s2.k + b * s2.k_sb + (g / s2.k_hdiv) * s2.k_sh + (int64_t)(w.cut - s2.t_lo) * s2.k_st;
+    w.v2 = s2.v + b * s2.v_sb + (g / s2.v_hdiv) * s2.v_sh + (int64_t)(w.cut - s2.t_lo) * s2.v_st;
+    w.k2_st = s2.k_st;
+    w.v2_st = s2.v_st;
+  }
 }
 
-// n tiles forward (n >= 0)
-__device__ __forceinline__ void walk_advance(const AttnParams& P, TileWalk& w, int n, int b, int g, int t_begin, int t_end) {
-  while (w.seg < P.n_seg) {
-    const int left = (w.end - w.r0 + kTile - 1) / kTile;      // tiles of this segment from r0 on
-    if (n < left) {
-      w.r0 += n * kTile;
-      if (n > 0 && (P.seg[w.seg].kp.tab || P.seg[w.seg].vp.tab)) walk_locate(P, w, b, g);
+// n tiles forward (n >= 0), then the pointers of the tile reached
+__device__ __forceinline__ void walk_advance(const AttnParams& P, TileWalk& w, int n, int b, int g, int t_end) {
+  if (w.seg >= P.n_seg) return;
+  const bool fetched = n > 0 && w.k != nullptr;
+  if (w.seg2 < 0 && w.r0 + kTile * (n + 1) <= w.seg_end) {
+    // the usual case: n full tiles further inside the same segment
+    w.r0 += kTile * n;
+    w.end = w.r0 + kTile;
+    if (fetched) {                       // same segment: only a paged operand has to look its page up again
+      if (P.seg[w.seg].kp.tab || P.seg[w.seg].vp.tab) walk_locate(P, w, b, g);
       return;
     }
-    n -= left;
-    walk_enter(P, w, w.seg + 1, b, g, t_begin, t_end);
+  } else {
+    for (int i = 0; i < n && w.seg < P.n_seg; ++i) walk_next(P, w, t_end);
   }
+  if (w.seg < P.n_seg) walk_fetch(P, w, b, g);
 }
 
 template <typename T, int WAVES, int OCC>
@@ -250,36 +294,51 @@ k_decode_attn(const AttnParams P) {
   auto issue_k = [&](const TileWalk& tp) {
     const uint32_t st = tp.k_st;
     const char* kb = tp.k + (int64_t)(tp.r0 - tp.t_lo) * st;
-    if (tp.r0 + kTile <= tp.end) {
+    if (tp.r0 + kTile <= tp.end && tp.seg2 < 0) {
       const uint32_t off = lg * st + l16 * 16;
 #pragma unroll
       for (int j = 0; j < 8; ++j) kst[j] = load16(kb + (size_t)(4 * j) * st, off);
     } else {
-      const int span = tp.end - 1 - tp.r0;
+      // a short tile (rows past its end repeat the last valid one) or one that continues in the
+      // next segment: per-lane row addresses
+      const int span = tp.end - 1 - tp.r0, ncut = tp.cut - tp.r0;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) kst[j] = load16(kb, (uint32_t)min(4 * j + lg, span) * st + l16 * 16);
+      for (int j = 0; j < 8; ++j) {
+        const int rr = min(4 * j + lg, span);
+        const bool in2 = rr >= ncut;
+        kst[j] = load16(in2 ? tp.k2 : kb, (in2 ? (uint32_t)(rr - ncut) * tp.k2_st : (uint32_t)rr * st) + l16 * 16);
+      }
     }
   };
   auto issue_v = [&](const TileWalk& tp) {
     const uint32_t st = tp.v_st;
     const char* vb = tp.v + (int64_t)(tp.r0 - tp.t_lo) * st;
-    if (tp.r0 + kTile <= tp.end) {
+    if (tp.r0 + kTile <= tp.end && tp.seg2 < 0) {
       const uint32_t off = lg * 4 * st + l16 * 16;
 #pragma unroll
       for (int j = 0; j < 8; ++j) vst[j] = load16(vb + (size_t)((j >> 2) * 16 + (j & 3)) * st, off);
     } else {
-      const int span = tp.end - 1 - tp.r0;
+      const int span = tp.end - 1 - tp.r0, ncut = tp.cut - tp.r0;
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        vst[j] = load16(vb, (uint32_t)min((j >> 2) * 16 + lg * 4 + (j & 3), span) * st + l16 * 16);
+      for (int j = 0; j < 8; ++j) {
+        const int rr = min((j >> 2) * 16 + lg * 4 + (j & 3), span);
+        const bool in2 = rr >= ncut;
+        vst[j] = load16(in2 ? tp.v2 : vb, (in2 ? (uint32_t)(rr - ncut) * tp.v2_st : (uint32_t)rr * st) + l16 * 16);
+      }
     }
   };
 
   uint4* my_lds = lds[wave];
   // this wave's tiles: wave, wave + WAVES, ... of the split
   TileWalk cur;
-  walk_enter(P, cur, 0, b, g, t_begin, t_end);
-  walk_advance(P, cur, wave, b, g, t_begin, t_end);
+  {
+    int seg0 = 0;
+    while (seg0 < P.n_seg && t_begin >= min(P.seg[seg0].t_hi, t_end)) ++seg0;
+    cur.seg = P.n_seg;
+    cur.k = nullptr;                     // pointers not fetched yet
+    if (seg0 < P.n_seg && t_begin < t_end) walk_place(P, cur, seg0, t_begin, t_end);
+  }
+  walk_advance(P, cur, wave, b, g, t_end);
   if (cur.seg < P.n_seg) {
     issue_k(cur);
     issue_v(cur);
@@ -287,7 +346,7 @@ k_decode_attn(const AttnParams P) {
   while (cur.seg < P.n_seg) {
     const int r0 = cur.r0, r_end = cur.end;
     const bool partial = r0 + kTile > r_end;
-    walk_advance(P, cur, WAVES, b, g, t_begin, t_end);     // cur is now the next tile of this wave
+    walk_advance(P, cur, WAVES, b, g, t_end);              // cur is now the next tile of this wave
     const bool more = cur.seg < P.n_seg;
     // ---- stage K through LDS (swizzle: chunk c of row r sits at unit c ^ (r & 15))
 #pragma unroll
