@@ -174,6 +174,13 @@ int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* const* C, in
  * vt_decode_attn_workspace_init; the split that finishes last for a (batch, kv head) merges
  * the partial results inside the same launch.  n_splits = 0 lets the library choose.  lse (device, B*Hq floats,
  * may be NULL) receives the log-sum-exp of the scaled scores. */
+/* What vt_decode_attn would decide for these operands, without launching anything (host only; the
+ * sources need non-NULL, suitably aligned pointers but nothing is dereferenced): the number of
+ * query heads served by one read of K/V, the context segments, the context splits, and how many
+ * segments read an operand through a page table.  Same errors as vt_decode_attn.  Any output
+ * pointer may be NULL. */
+int vt_decode_attn_plan(const vt_desc* Q, const vt_desc* K, const vt_desc* V, int n_splits, int* group_size,
+                        int* n_segments, int* splits, int* paged_segments);
 size_t vt_decode_attn_workspace(int B, int Hq, int D, int S, int n_splits);
 /* Clears a freshly allocated workspace (its first bytes hold one arrival counter per (batch,
  * kv head), which must be zero when vt_decode_attn starts and which vt_decode_attn leaves at

@@ -75,6 +75,7 @@ def lib():
         L.vt_gemm_store_workspace.restype = C.c_size_t
         L.vt_gemm_store_workspace_init.argtypes = [P, C.c_size_t, P]
         L.vt_gemm_store.argtypes = [P, P, P, P, C.c_size_t, P]
+        L.vt_decode_attn_plan.argtypes = [P, P, P, C.c_int] + [C.POINTER(C.c_int)] * 4
         L.vt_decode_attn_workspace.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
         L.vt_decode_attn_workspace.restype = C.c_size_t
         L.vt_decode_attn_workspace_init.argtypes = [P, C.c_size_t, P]
@@ -322,3 +323,10 @@ def vt_gemm_store(A: Desc, B: Desc, Cout: Desc, workspace, workspace_bytes: int,
 
 def vt_scatter(src: Desc, dst: Desc, stream=None):
     _check(lib().vt_scatter(src.handle, dst.handle, _stream(stream)))
+
+
+def vt_decode_attn_plan(Q: Desc, K: Desc, V: Desc, n_splits=0):
+    """Host-side plan of vt_decode_attn: dict with group_size, n_segments, splits, paged_segments."""
+    g, ns, sp, pg = C.c_int(), C.c_int(), C.c_int(), C.c_int()
+    _check(lib().vt_decode_attn_plan(Q.handle, K.handle, V.handle, n_splits, C.byref(g), C.byref(ns), C.byref(sp), C.byref(pg)))
+    return {"group_size": g.value, "n_segments": ns.value, "splits": sp.value, "paged_segments": pg.value}

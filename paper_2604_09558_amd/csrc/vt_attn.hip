@@ -643,7 +643,6 @@ int plan_operand(const vt_desc& d, const char* name, int64_t G, AttnOperand* out
     a.sh = sh * esz;
     if (paged) {
       const int64_t rows = p.hi[2] - p.lo[2];
-      if (!(page_rows % kTile == 0 || page_rows >= rows)) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": pages must hold a multiple of 32 rows");
       const Digit* T = ctx_table;
       int64_t W = 1;
       if (two_stage) {
@@ -655,6 +654,19 @@ int plan_operand(const vt_desc& d, const char* name, int64_t G, AttnOperand* out
           W *= lo.digits[k].radix;
         }
         T = &lo.digits[0];
+        // a context dim that is ONE digit of the top stage (one kv head per page: page stride =
+        // rows x row stride) still walks through the table: W / st rows per entry
+        if (lp == 0 && st > 0 && W % st == 0 && W / st < rows) {
+          page_rows = W / st;
+          lp = W;
+        }
+        // No carries: the table entry must depend only on digits whose stride is a multiple of W,
+        // and everything else must add up to less than W - then the rows of a page are equally
+        // spaced in the source, which is what a tile relies on.
+        int64_t sub = p.v.base % W + (page_rows - 1) * st + d.shape[3];
+        if (sb % W) sub += (d.shape[0] - 1) * sb;
+        if (sh % W) sub += (d.shape[1] / (G * a_hdiv) - 1) * sh;
+        if (lp % W || sub > W) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": paged map: rows of a page are not equally spaced in the source");
         int64_t span = p.v.base;     // largest value of the top stage: must stay a 31-bit index
         for (const auto& grp : p.v.groups)
           for (const Digit& g : grp) span += (g.radix - 1) * (g.stride > 0 ? g.stride : 0);
@@ -667,6 +679,7 @@ int plan_operand(const vt_desc& d, const char* name, int64_t G, AttnOperand* out
         a.pg.Lp = 1;                 // L = page number within the piece
         a.pg.X0 = p.v.base; a.pg.Xb = sb; a.pg.Xh = sh; a.pg.Xo = st;
       }
+      if (!(page_rows % kTile == 0 || page_rows >= rows)) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": pages must hold a multiple of 32 rows");
       const Table& tb = d.tables[T->table];
       if (!tb.dev) return fail(VT_ERR_INVALID_ARG, std::string(name) + ": page table without a device pointer");
       if (sb % 8 || sh % 8 || T->stride % 8) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": paged rows are not 16-byte aligned");
@@ -694,6 +707,7 @@ int plan_operand(const vt_desc& d, const char* name, int64_t G, AttnOperand* out
         }
       }
     }
+    a.page_rows = page_rows;
     if (st * esz >= (1ll << 32) || st < 0) return fail(VT_ERR_UNSUPPORTED, std::string(name) + ": context stride too large");
     a.st = (uint32_t)(st * esz);
     a.t_lo = (int32_t)p.lo[2];
@@ -737,9 +751,10 @@ int vt_decode_attn_workspace_init(void* workspace, size_t workspace_bytes, void*
   return check_launch("vt_decode_attn_workspace_init");
 }
 
-int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float scale, void* out, float* lse,
-                   void* workspace, size_t workspace_bytes, int n_splits, void* stream) {
-  if (!Q || !K || !V || !out || !workspace) return fail(VT_ERR_INVALID_ARG, "vt_decode_attn: NULL argument");
+// Everything vt_decode_attn decides on the host: group size, segments, paged operands, splits.
+// Fills P except for the workspace, output and scale fields.
+static int plan_attention(const vt_desc* Q, const vt_desc* K, const vt_desc* V, int n_splits, AttnParams& P) {
+  if (!Q || !K || !V) return fail(VT_ERR_INVALID_ARG, "vt_decode_attn: NULL argument");
   if (Q->dtype == VT_F32 || K->dtype != Q->dtype || V->dtype != Q->dtype)
     return fail(VT_ERR_INVALID_ARG, "vt_decode_attn: Q, K, V must share a 16-bit dtype");
   if (Q->shape.size() != 4 || K->shape.size() != 4 || V->shape != K->shape)
@@ -760,7 +775,6 @@ int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float s
     }
   if (G < 1) G = 1;
   while (G > 16 || Hq % G) --G;      // the matrix-core tile holds at most 16 heads
-  AttnParams P;
   memset(&P, 0, sizeof(P));
   AttnOperand ko, vo;
   int rc = plan_operand(*K, "K", G, &ko);
@@ -817,15 +831,41 @@ int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float s
   rows = (rows + kTile - 1) / kTile * kTile;
   const int ns_eff = (int)((S + rows - 1) / rows);
   if ((int64_t)ns_eff * G * 2 > kWaves * kTile * 64) return fail(VT_ERR_UNSUPPORTED, "vt_decode_attn: too many splits");
-  const size_t need = ticket_bytes(B, Hq) + (size_t)B * Hq * ns_eff * ((size_t)kD + 2) * sizeof(float);
-  if (workspace_bytes < need) return fail(VT_ERR_INVALID_ARG, "vt_decode_attn: workspace too small");
-  if ((uintptr_t)workspace % 16 || (uintptr_t)out % 8) return fail(VT_ERR_INVALID_ARG, "vt_decode_attn: misaligned workspace or out (16 and 8 bytes)");
   P.B = (int)B;
   P.Hkv = Hkv;
   P.G = (int)G;
   P.S = (int)S;
   P.n_splits = ns_eff;
   P.rows_per_split = rows;
+  return VT_OK;
+}
+
+int vt_decode_attn_plan(const vt_desc* Q, const vt_desc* K, const vt_desc* V, int n_splits, int* group_size,
+                        int* n_segments, int* splits, int* paged_segments) {
+  AttnParams P;
+  int rc = plan_attention(Q, K, V, n_splits, P);
+  if (rc != VT_OK) return rc;
+  if (group_size) *group_size = P.G;
+  if (n_segments) *n_segments = P.n_seg;
+  if (splits) *splits = P.n_splits;
+  if (paged_segments) {
+    *paged_segments = 0;
+    for (int i = 0; i < P.n_seg; ++i) *paged_segments += (P.seg[i].kp.tab || P.seg[i].vp.tab) ? 1 : 0;
+  }
+  return VT_OK;
+}
+
+int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float scale, void* out, float* lse,
+                   void* workspace, size_t workspace_bytes, int n_splits, void* stream) {
+  if (!out || !workspace) return fail(VT_ERR_INVALID_ARG, "vt_decode_attn: NULL argument");
+  AttnParams P;
+  int rc = plan_attention(Q, K, V, n_splits, P);
+  if (rc != VT_OK) return rc;
+  const int64_t B = P.B, Hq = (int64_t)P.Hkv * P.G;
+  const int ns_eff = P.n_splits, Hkv = P.Hkv;
+  const size_t need = ticket_bytes(B, Hq) + (size_t)B * Hq * ns_eff * ((size_t)kD + 2) * sizeof(float);
+  if (workspace_bytes < need) return fail(VT_ERR_INVALID_ARG, "vt_decode_attn: workspace too small");
+  if ((uintptr_t)workspace % 16 || (uintptr_t)out % 8) return fail(VT_ERR_INVALID_ARG, "vt_decode_attn: misaligned workspace or out (16 and 8 bytes)");
   P.scale_log2 = scale * 1.4426950408889634f;
   P.tickets = static_cast<uint32_t*>(workspace);
   P.ws_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + ticket_bytes(B, Hq));

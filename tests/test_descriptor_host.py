@@ -361,3 +361,52 @@ def test_store_maps_must_be_one_to_one():
     with pytest.raises(vt.VtError) as ei:
         vt.vt_scatter(src, vt.build_chain([], {"S": ((6, 4), "f32", fake)}, "S"))
     assert ei.value.code == vt.ERR_SHAPE
+
+
+# ------------------------------------------------------------------ host plan of the attention consumer
+FAKE = 0x100000       # a 16-byte aligned address that is never dereferenced
+
+
+def attn_descs(wl):
+    spec = {k: (v.shape, wl.dtype, FAKE) for k, v in wl.sources.items()}
+    tabs = {k: FAKE for k in wl.index_tables}
+    c = wl.consumer
+    return [vt.build_chain(wl.chain, spec, c[n], wl.index_tables, tabs) for n in ("q", "k", "v")]
+
+
+def test_attention_plan_of_the_decode_chain():
+    wl = workloads.c2_decode_attention(seed=0, B=8, Hkv=8, G=4, S=4096, D=128)
+    plan = vt.vt_decode_attn_plan(*attn_descs(wl))
+    # 4 query heads share a read; the context splits into cached rows | fresh row; 8 splits fill the chip
+    assert plan == {"group_size": 4, "n_segments": 2, "splits": 8, "paged_segments": 0}
+    assert vt.vt_decode_attn_plan(*attn_descs(wl), n_splits=3)["splits"] == 3
+    small = workloads.c2_decode_attention(seed=0, B=1, Hkv=1, G=16, S=70, D=128)
+    assert vt.vt_decode_attn_plan(*attn_descs(small)) == {"group_size": 16, "n_segments": 2, "splits": 1, "paged_segments": 0}
+
+
+def test_attention_plan_recognises_page_tables():
+    two_stage = workloads.paged_decode_attention(seed=1, B=2, Hkv=2, G=4, pages_per_seq=3, page=32)
+    assert vt.vt_decode_attn_plan(*attn_descs(two_stage)) == {"group_size": 4, "n_segments": 1, "splits": 1, "paged_segments": 1}
+    one_stage = workloads.paged_decode_attention(seed=1, B=1, Hkv=2, G=1, pages_per_seq=2, page=128)   # B = 1: the table digit stays in the context group
+    assert vt.vt_decode_attn_plan(*attn_descs(one_stage))["paged_segments"] == 1
+    # pages that do not hold a multiple of 32 rows cannot be tiled
+    odd = workloads.paged_decode_attention(seed=1, B=2, Hkv=1, G=2, pages_per_seq=3, page=24)
+    with pytest.raises(vt.VtError) as ei:
+        vt.vt_decode_attn_plan(*attn_descs(odd))
+    assert ei.value.code == vt.ERR_UNSUPPORTED
+
+
+def test_attention_plan_rejects_what_the_kernel_cannot_read():
+    wl = workloads.c2_decode_attention(seed=0, B=1, Hkv=1, G=2, S=8, D=64)          # head dim 64
+    with pytest.raises(vt.VtError) as ei:
+        vt.vt_decode_attn_plan(*attn_descs(wl))
+    assert ei.value.code == vt.ERR_UNSUPPORTED
+    # K transposed so that the head dim is not contiguous
+    wl = workloads.c2_decode_attention(seed=0, B=1, Hkv=1, G=2, S=128, D=128)
+    q, k, v = attn_descs(wl)
+    spec = {"X": ((1, 2, 128, 128), "bf16", FAKE)}
+    kt = vt.build_chain([("t", "permute", ("X",), {"perm": (0, 1, 3, 2)})], spec, "t")
+    with pytest.raises(vt.VtError) as ei:
+        vt.vt_decode_attn_plan(q, kt, v)
+    assert ei.value.code == vt.ERR_UNSUPPORTED
+    assert vt.lib().vt_decode_attn_plan(None, None, None, 0, None, None, None, None) == vt.ERR_INVALID_ARG
