@@ -229,13 +229,14 @@ k_ln_gemm(const LnGemmParams P) {
     const uint32_t rot61 = blockIdx.x * 61u;
     const int rot = (int)(rot61 - fdiv(rot61, P.nblk) * P.nblk.d);
     int kbs[2], cns[2];
+    const bool wave_r1 = LTHREADS + wave * 64 < nblk;  // this wave has blocks in the second round
 #pragma unroll
     for (int r = 0; r < 2; ++r) {                      // all loads of both rounds are in flight together
       const int idx = t + r * LTHREADS;
-      {
-        // every thread issues all 16 loads (a thread without a block of its own reads the last
-        // one again and drops it): the number of loads in flight is then the same everywhere,
-        // and the wait for the rows that were requested before them can be an exact count
+      if (r == 0 || wave_r1) {
+        // a wave issues a round for all its lanes or not at all (a lane without a block of its own
+        // reads the last one again and drops it): the number of loads in flight is then uniform
+        // in the wave, and the wait for the rows requested before them can be an exact count
         int bidx = min(idx, nblk - 1) + rot;
         bidx = bidx >= nblk ? bidx - nblk : bidx;
         const int kb = (int)fdiv((uint32_t)bidx, P.n8), cn = bidx - kb * (N / 8);
@@ -253,8 +254,9 @@ k_ln_gemm(const LnGemmParams P) {
       }
     }
     // block 0's rows were requested before W and have landed by now: normalise them while W is
-    // still on its way (16 loads are in flight behind them)
-    __builtin_amdgcn_s_waitcnt(0x4F70);                // vmcnt(16)
+    // still on its way (8 or 16 loads are in flight behind them)
+    if (wave_r1) __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16)
+    else __builtin_amdgcn_s_waitcnt(0x0F78);           // vmcnt(8)
     norm_tile(0);
     normed0 = true;
 #pragma unroll
