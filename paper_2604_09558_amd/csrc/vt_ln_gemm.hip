@@ -156,8 +156,10 @@ k_ln_gemm(const LnGemmParams P) {
       // stays unknown to the compiler, which would otherwise order every later LDS access of the
       // kernel behind it; the waits for these requests are the explicit ones below.
       const uint32_t dst = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lptr_t)&tiles[slot * kTileUnits + (wave * RW + RPP * i) * LPR]);
-      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                   :: "v"(o + ((a_c ^ (r & 7)) * 16)), "s"(P.a), "s"(dst) : "memory", "m0");
+      // (M0 holds the LDS destination; it is saved and put back, so nothing is clobbered)
+      uint32_t m0_saved;
+      asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_nop 0\n\ts_mov_b32 m0, %0"
+                   : "=&s"(m0_saved) : "v"(o + ((a_c ^ (r & 7)) * 16)), "s"(P.a), "s"(dst) : "memory");
     }
   };
   // the first two blocks' rows are requested before anything else: their latency hides behind the W prologue
