@@ -412,7 +412,7 @@ template <typename T, bool C_F32>
 int launch_t(const LnGemmParams& P, int lpr, int nb, hipStream_t st) {
   static const int n_cu = [] {
     int dev = 0, n = 256;
-    if (hipGetDevice(&dev) == hipSuccess) hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 256;
     return n > 0 ? n : 256;
   }();
   // One workgroup per compute unit: full rounds of blocks, then one more block for as many
