@@ -172,7 +172,8 @@ int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* const* C, in
  * workspace: device pointer (16-byte aligned) of at least vt_decode_attn_workspace(...) bytes,
  * holding arrival counters and the per-split partial results, prepared once with
  * vt_decode_attn_workspace_init; the split that finishes last for a (batch, kv head) merges
- * the partial results inside the same launch.  n_splits = 0 lets the library choose.  lse (device, B*Hq floats,
+ * the partial results inside the same launch, in split order: results are bitwise reproducible
+ * from launch to launch.  n_splits = 0 lets the library choose.  lse (device, B*Hq floats,
  * may be NULL) receives the log-sum-exp of the scaled scores. */
 /* What vt_decode_attn would decide for these operands, without launching anything (host only; the
  * sources need non-NULL, suitably aligned pointers but nothing is dereferenced): the number of
