@@ -135,3 +135,31 @@ def test_rejects_unsupported_operands(gpu):
     with pytest.raises(vt.VtError) as ei:
         vt.vt_gemm([a], [bt], [out], "bf16")
     assert ei.value.code == vt.ERR_UNSUPPORTED
+
+
+def test_c5_full_size_sampled_outputs(gpu):
+    """Config 5 at the benchmark's size and launch configuration (8 experts in one grouped launch,
+    rows gathered through the routing tables): for every expert 16 sampled rows (first, last,
+    random) are compared with the oracle on 1024 sampled columns; row and column sums over the
+    whole output would need the full product on the CPU (3.85 TFLOP) and are left out."""
+    vt, tio, pipelines, torch = gpu
+    print("generating config 5", flush=True)
+    wl = workloads.c5_moe_dispatch()
+    p = run(pipelines, tio, torch, wl)
+    print("config 5 launched", flush=True)
+    tokens, W = wl.sources["tokens"], wl.sources["W"]
+    cols = np.arange(0, W.shape[2], 14)
+    rng = np.random.default_rng(0)
+    row0 = 0
+    for e in range(W.shape[0]):
+        idx = wl.index_tables["idx%d" % e]
+        n_e = len(idx)
+        assert np.all(np.diff(idx) > 0)
+        pick = np.unique(np.concatenate([[0, n_e - 1], rng.integers(0, n_e, size=14)]))
+        a = consumers.decode(tokens[idx[pick]], "bf16")                     # the gathered rows, by definition of index_select
+        w = consumers.decode(np.ascontiguousarray(W[e][:, cols]), "bf16")
+        ref = consumers.gemm(a, w)
+        got = tio.to_host_f64(p.out[torch.from_numpy(row0 + pick).cuda()][:, torch.from_numpy(cols).cuda()])
+        check(got, ref)
+        row0 += n_e
+    assert row0 == p.out.shape[0] == 2 * tokens.shape[0]
