@@ -199,3 +199,17 @@ def test_paged_kv_cache_through_a_two_stage_descriptor(gpu, B, Hkv, G, P, page, 
     m = pipelines.run_decode_attention(tio.DeviceWorkload(wl), materialized=True, n_splits=ns)
     if page * P % 32 == 0:
         assert np.max(np.abs(tio.to_host_f64(m["out"]) - got)) <= 1e-3
+
+
+def test_paged_kv_cache_full_size(gpu):
+    """The benchmark's decode step over a paged cache (8 sequences x 32 pages of 128 rows out of a
+    pool of 259), in the launch configuration bench.py times: every output compared."""
+    vt, tio, pipelines, torch = gpu
+    wl = workloads.paged_decode_attention(poison_unused=True)
+    ref = run_workload(wl)
+    res = pipelines.run_decode_attention(tio.DeviceWorkload(wl))
+    got = tio.to_host_f64(res["out"])
+    assert np.isfinite(got).all()
+    mx = check(got, ref["out"])
+    assert mx <= 2e-3, mx
+    assert np.max(np.abs(tio.to_host_f64(res["lse"]) - ref["lse"])) <= 1e-3
