@@ -106,3 +106,10 @@ def round_to(x: np.ndarray, dtype: str) -> np.ndarray:
         r = np.where(nan, keep | np.uint32(0x40), keep + up.astype(np.uint32))
         return r.astype(np.uint16)
     raise ValueError(dtype)
+
+
+def weighted_sum(x: np.ndarray, y: np.ndarray, w: np.ndarray) -> np.ndarray:
+    """out[r, :] = w[r, 0] x[r, :] + w[r, 1] y[r, :] in float64 (the combine of a mixture of
+    experts: x, y the two expert outputs of token r, w its routing weights)."""
+    w = w.astype(np.float64)
+    return w[:, 0:1] * x + w[:, 1:2] * y

@@ -40,6 +40,8 @@ def run_workload(wl, keep_intermediates: bool = False):
     elif kind == "ln_linear":
         res["out"] = consumers.ln_linear(dec(c["x"]), dec(c["w"]), c["eps"], wl.dtype)
         res["ln"] = consumers.layernorm(dec(c["x"]), c["eps"])
+    elif kind == "weighted_sum":
+        res["out"] = consumers.weighted_sum(dec(c["x"]), dec(c["y"]), c["weights"])
     elif kind == "decode_attn":
         out, lse = consumers.decode_attention(dec(c["q"]), dec(c["k"]), dec(c["v"]), c["scale"])
         res["out"], res["lse"] = out, lse

@@ -463,3 +463,36 @@ def test_round_to_bf16_is_round_to_nearest_even():
     # agrees with the input generator's rounding on random float32 values
     y = np.random.default_rng(1).standard_normal(4096).astype(np.float32)
     assert np.array_equal(consumers.round_to(y.astype(np.float64), "bf16"), workloads.encode(y, "bf16"))
+
+
+# ------------------------------------------------------------------ mixture-of-experts combine
+def test_moe_combine_routing_is_the_inverse_of_the_dispatch():
+    """pos0/pos1 must name, in the expert-major buffer config 5 writes, exactly the two rows that
+    hold token t: rebuilding that buffer's token ids from config 5's own tables pins them."""
+    T, E = 500, 8
+    wl = workloads.moe_combine(seed=7, T=T, E=E, N=16)
+    d5 = workloads.c5_moe_dispatch(seed=7, T=T, Hd=8, E=E, N=8)
+    token_of_row = np.concatenate([d5.index_tables["idx%d" % e] for e in range(E)])   # row of Y -> token
+    assert token_of_row.shape == (2 * T,)
+    p0, p1 = wl.index_tables["pos0"], wl.index_tables["pos1"]
+    assert np.array_equal(token_of_row[p0], np.arange(T)) and np.array_equal(token_of_row[p1], np.arange(T))
+    assert (p0 < p1).all()                                       # lower expert id first: distinct rows
+    assert len(np.unique(np.concatenate([p0, p1]))) == 2 * T     # every row of Y is used exactly once
+    w = wl.consumer["weights"]
+    assert np.allclose(w.sum(axis=1), 1.0, atol=1e-6) and (w > 0).all()
+
+
+def test_weighted_sum_against_a_plain_loop_and_special_weights():
+    wl = workloads.moe_combine(seed=8, T=40, E=4, N=24)
+    out = run_workload(wl)["out"]
+    Y = consumers.decode(wl.sources["Y"], "bf16")
+    w = wl.consumer["weights"].astype(np.float64)
+    for t in (0, 17, 39):
+        for c in (0, 23):
+            want = w[t, 0] * Y[wl.index_tables["pos0"][t], c] + w[t, 1] * Y[wl.index_tables["pos1"][t], c]
+            assert abs(out[t, c] - want) < 1e-12
+    # weights (1, 0) return the first expert's row, (0, 1) the second's, (1, 1) on equal rows twice the row
+    x = np.arange(12.0).reshape(3, 4)
+    assert np.array_equal(consumers.weighted_sum(x, -x, np.array([[1, 0]] * 3, np.float32)), x)
+    assert np.array_equal(consumers.weighted_sum(x, -x, np.array([[0, 1]] * 3, np.float32)), -x)
+    assert np.array_equal(consumers.weighted_sum(x, x, np.array([[1, 1]] * 3, np.float32)), 2 * x)

@@ -20,6 +20,7 @@ from .inputs import (  # noqa: F401
     qkv_proj_store,
     decode_segment,
     paged_decode_attention,
+    moe_combine,
     qkv_store_chain,
     random_chain,
     CONFIGS,

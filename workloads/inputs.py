@@ -241,6 +241,35 @@ def qkv_proj_store(seed: int = 0, B: int = 8, hidden: int = 4096, Hq: int = 32, 
                     {"kind": "gemm_store", "a": "X", "b": "W", "out": "Cout"})
 
 
+def moe_combine(seed: int = 0, T: int = 16384, E: int = 8, N: int = 14336, dtype: str = "bf16") -> Workload:
+    """The step after config 5: the expert outputs Y[2T, N] (expert-major, tokens ascending inside
+    an expert, the layout config 5 writes) are read back per token and mixed with the two routing
+    weights.  Routing as in config 5 (two distinct experts per token, uniform); weights = softmax
+    of two N(0,1) logits, fp32."""
+    g = _rng(seed, 2)
+    first = g.integers(0, E, size=T)
+    second = (first + 1 + g.integers(0, E - 1, size=T)) % E
+    lo, hi = np.minimum(first, second), np.maximum(first, second)
+    counts = np.bincount(np.concatenate([first, second]), minlength=E)
+    offset = np.concatenate([[0], np.cumsum(counts)[:-1]])
+    rank = np.zeros((E, T), dtype=np.int64)                  # rank[e, t] = tokens < t routed to e
+    for e in range(E):
+        routed = ((first == e) | (second == e)).astype(np.int64)
+        rank[e] = np.cumsum(routed) - routed
+    t = np.arange(T)
+    pos0 = (offset[lo] + rank[lo, t]).astype(np.int32)
+    pos1 = (offset[hi] + rank[hi, t]).astype(np.int32)
+    logits = _rng(seed, 3).standard_normal(size=(T, 2)).astype(np.float32)
+    ex = np.exp(logits - logits.max(axis=1, keepdims=True))
+    weights = (ex / ex.sum(axis=1, keepdims=True)).astype(np.float32)
+    src = {"Y": _normal(seed, 0, (2 * T, N), 1.0, dtype)}
+    chain = [("x", "index_select", ("Y",), {"dim": 0, "index": "pos0"}),
+             ("y", "index_select", ("Y",), {"dim": 0, "index": "pos1"})]
+    return Workload("moe_combine", dtype, src, chain,
+                    {"kind": "weighted_sum", "x": "x", "y": "y", "weights": weights},
+                    {"pos0": pos0, "pos1": pos1})
+
+
 def paged_decode_attention(seed: int = 0, B: int = 8, Hkv: int = 8, G: int = 4, pages_per_seq: int = 32,
                            page: int = 128, D: int = 128, pool_pages: int = 0, dtype: str = "bf16",
                            poison_unused: bool = False) -> Workload:
@@ -311,6 +340,7 @@ CONFIGS = {
     "c5": c5_moe_dispatch,
     "qkv_store": qkv_proj_store,
     "paged": paged_decode_attention,
+    "moe_combine": moe_combine,
 }
 
 
