@@ -54,7 +54,7 @@ def parse():
     ap.add_argument("--context", type=int, default=4096, help="context length (the benchmark's is 4096; others are for tuning)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 128 MiB -> 128 MiB copy kernel 20 times (reference point for HBM byte counters)")
-    ap.add_argument("--extra", default="", help="comma list of further chains to time (c1,c3,c4,c5,qkv_store,decode_segment,paged)")
+    ap.add_argument("--extra", default="", help="comma list of further chains to time (c1,c3,c4,c5,qkv_store,decode_segment,paged,moe_combine)")
     return ap.parse_args()
 
 
@@ -145,6 +145,24 @@ def chain_stats(torch, name, steps, a_no_graph=False):
         out["materialized_full_us"] = round(m_ev * 1e3, 2)
         out["speedup_vs_materialized_full"] = round(m_ev / v_ev, 2)
         out["intermediate_bytes_saved"] = int(mat.attn.mat.bytes_written + M * N * 2)
+        return out
+    if name == "moe_combine":
+        # the combine after config 5: two gathered rows per token, mixed with the routing weights
+        mk = lambda p: (lambda stream: p.run(stream))      # noqa: E731
+        dw = tio.DeviceWorkload(workloads.moe_combine())
+        pv = pipelines.WeightedSum(dw)
+        torch.cuda.synchronize()
+        v_wall, v_ev = time_steps(torch, [mk(pv)], steps, max(2, steps // 10), False)
+        R, C = pv.x.shape
+        alg = 3 * R * C * 2 + R * 16
+        out = {"virtual_us": round(v_ev * 1e3, 2), "algorithmic_bytes": int(alg),
+               "hbm_pct_of_peak": round(100.0 * alg / (v_ev * 1e-3) / 1e9 / HBM_PEAK_GBS, 1)}
+        pm = pipelines.WeightedSum(dw, materialized=True)
+        torch.cuda.synchronize()
+        m_wall, m_ev = time_steps(torch, [mk(pm)], max(5, steps // 4), 2, False)
+        out["materialized_full_us"] = round(m_ev * 1e3, 2)
+        out["speedup_vs_materialized_full"] = round(m_ev / v_ev, 2)
+        out["intermediate_bytes_saved"] = int(pm.mat.bytes_written)
         return out
     if name == "paged":
         # config 2's attention over a paged KV cache (pages of 128 rows picked through a block table)
@@ -314,7 +332,7 @@ def main():
         torch.cuda.empty_cache()
         out["chains"] = {}
         for name in a.extra.split(","):
-            out["chains"][name] = chain_stats(torch, name, a_no_graph=a.no_graph, steps={"c1": 200, "c3": 30, "c4": 100, "c5": 6, "qkv_store": 200, "decode_segment": 120, "paged": 200}[name])
+            out["chains"][name] = chain_stats(torch, name, a_no_graph=a.no_graph, steps={"c1": 200, "c3": 30, "c4": 100, "c5": 6, "qkv_store": 200, "decode_segment": 120, "paged": 200, "moe_combine": 40}[name])
             torch.cuda.empty_cache()
 
     if not a.no_cpu_baseline:

@@ -146,6 +146,13 @@ int vt_copy_op(const vt_source* in, int n_in, const vt_op* op, void* dst, void* 
 typedef enum { VT_EW_ADD_ROWSUM = 0, VT_EW_LAYERNORM = 1 } vt_ew_kind;
 int vt_elementwise(int kind, const vt_desc* x, const vt_desc* y, float eps, void* out, void* stream);
 
+/* Weighted sum of two virtual tensors, the combine step after a mixture-of-experts layer
+ * (the consumer that reads the expert outputs back in token order; the gathers are index_select
+ * operators in the chains of x and y and are never executed): out[r,:] = w[r][0] x[r,:] +
+ * w[r][1] y[r,:].  x, y virtual [R,C], f16 or bf16; weights dense device [R,2] fp32; out dense
+ * [R,C] of the operands' dtype; fp32 arithmetic, one rounding.  Asynchronous on `stream`. */
+int vt_weighted_sum(const vt_desc* x, const vt_desc* y, const float* weights, void* out, void* stream);
+
 /* GEMM consumer on the matrix cores (Sec. 2.3 Listing 1's three stages with a virtual stage
  * 1): C[g] = A[g] . B[g] for g in [0, n_groups).  A[g] virtual [M_g, K] (trailing dims may be
  * folded: [.., K] counts as rows x K), B[g] virtual [K, N]; f16 or bf16 operands, fp32

@@ -71,6 +71,7 @@ def lib():
         L.vt_elementwise.argtypes = [C.c_int, P, P, C.c_float, P, P]
         L.vt_gemm.argtypes = [C.POINTER(P), C.POINTER(P), C.POINTER(P), C.c_int, C.c_int, C.c_int, C.c_float, P]
         L.vt_scatter.argtypes = [P, P, P]
+        L.vt_weighted_sum.argtypes = [P, P, P, P, P]
         L.vt_gemm_store_workspace.argtypes = [C.c_int64, C.c_int64, C.c_int64]
         L.vt_gemm_store_workspace.restype = C.c_size_t
         L.vt_gemm_store_workspace_init.argtypes = [P, C.c_size_t, P]
@@ -330,3 +331,7 @@ def vt_decode_attn_plan(Q: Desc, K: Desc, V: Desc, n_splits=0):
     g, ns, sp, pg = C.c_int(), C.c_int(), C.c_int(), C.c_int()
     _check(lib().vt_decode_attn_plan(Q.handle, K.handle, V.handle, n_splits, C.byref(g), C.byref(ns), C.byref(sp), C.byref(pg)))
     return {"group_size": g.value, "n_segments": ns.value, "splits": sp.value, "paged_segments": pg.value}
+
+
+def vt_weighted_sum(x: Desc, y: Desc, weights, out, stream=None):
+    _check(lib().vt_weighted_sum(x.handle, y.handle, _ptr(weights), _ptr(out), _stream(stream)))

@@ -216,6 +216,68 @@ static int launch_layernorm_t(const vt_desc& d, const DevDesc& D, void* out, flo
   return check_launch("vt_elementwise(layernorm)");
 }
 
+// ------------------------------------------------------------------------------------------
+// out[r, :] = w[r][0] * x[r, :] + w[r][1] * y[r, :]   (the combine step of a mixture of experts:
+// x and y are the two expert outputs of token r, gathered through row tables).  fp32 arithmetic,
+// 16-bit storage.  Rows that are contiguous in their sources (the usual case: whole rows are
+// gathered) take the row kernel: the map is applied once per row, on values that are uniform in
+// the workgroup, and the row streams through 16-byte nontemporal loads and stores (every byte is
+// touched once).  Anything else goes through the generic evaluator per vector.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) k_weighted_sum_rows(const DevDesc X, const DevDesc Y, const float* __restrict__ w,
+                                                           T* __restrict__ out, uint32_t R, uint32_t C) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  for (uint32_t row = blockIdx.x; row < R; row += gridDim.x) {
+    int64_t ox, oy;
+    const void *px, *py;
+    vtd_eval(X, 0, row * C, &ox, &px);
+    vtd_eval(Y, 0, row * C, &oy, &py);
+    const u32x4* xr = reinterpret_cast<const u32x4*>(static_cast<const T*>(px) + ox);
+    const u32x4* yr = reinterpret_cast<const u32x4*>(static_cast<const T*>(py) + oy);
+    u32x4* orow = reinterpret_cast<u32x4*>(out + (size_t)row * C);
+    const float wx = w[2 * row], wy = w[2 * row + 1];
+    for (uint32_t v = threadIdx.x; v < C / 8; v += 256) {
+      const Vec<T, 8> a = __builtin_bit_cast(Vec<T, 8>, __builtin_nontemporal_load(xr + v));
+      const Vec<T, 8> b = __builtin_bit_cast(Vec<T, 8>, __builtin_nontemporal_load(yr + v));
+      Vec<T, 8> o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o.v[e] = from_float<T>(wx * to_float(a.v[e]) + wy * to_float(b.v[e]));
+      __builtin_nontemporal_store(__builtin_bit_cast(u32x4, o), orow + v);
+    }
+  }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) k_weighted_sum_generic(const DevDesc X, const DevDesc Y, const float* __restrict__ w,
+                                                              T* __restrict__ out, uint32_t n, uint32_t C) {
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i >= n) return;
+  int64_t ox, oy;
+  const void *px, *py;
+  vtd_eval(X, 0, i, &ox, &px);
+  vtd_eval(Y, 0, i, &oy, &py);
+  const uint32_t row = i / C;
+  out[i] = from_float<T>(w[2 * row] * to_float(static_cast<const T*>(px)[ox]) + w[2 * row + 1] * to_float(static_cast<const T*>(py)[oy]));
+}
+
+template <typename T>
+static int launch_weighted_sum(const vt_desc& x, const vt_desc& y, const DevDesc& X, const DevDesc& Y, const float* w, void* out,
+                               hipStream_t st) {
+  const uint32_t R = (uint32_t)x.shape[0], C = (uint32_t)x.shape[1];
+  bool rows_ok = C % 8 == 0 && (uintptr_t)out % 16 == 0 && vector_width(x) == 8 && vector_width(y) == 8;
+  for (const vt_desc* d : {&x, &y})
+    for (const Piece& p : d->pieces)
+      rows_ok = rows_ok && p.run % C == 0 && p.lo[1] == 0 && p.hi[1] == (int64_t)C;   // whole rows, each contiguous in its source
+  if (rows_ok) {
+    hipLaunchKernelGGL((k_weighted_sum_rows<T>), dim3(std::min<uint32_t>(R, 65535u * 16u)), dim3(256), 0, st, X, Y, w, (T*)out, R, C);
+  } else {
+    const uint32_t n = R * C;
+    hipLaunchKernelGGL((k_weighted_sum_generic<T>), dim3((n + 255) / 256), dim3(256), 0, st, X, Y, w, (T*)out, n, C);
+  }
+  return check_launch("vt_weighted_sum");
+}
+
 extern "C" {
 
 int vt_materialize(const vt_desc* d, void* dst, void* stream) {
@@ -231,6 +293,21 @@ int vt_scatter(const vt_desc* src, const vt_desc* dst, void* stream) {
   for (const Piece& p : dst->pieces)
     if (!dst->sources[p.src].ptr) return fail(VT_ERR_INVALID_ARG, "vt_scatter: destination tensor without a device pointer");
   return launch_scatter(*src, *dst, (hipStream_t)stream);
+}
+
+int vt_weighted_sum(const vt_desc* x, const vt_desc* y, const float* weights, void* out, void* stream) {
+  if (!x || !y || !weights || !out) return fail(VT_ERR_INVALID_ARG, "vt_weighted_sum: NULL argument");
+  if (x->dtype == VT_F32 || y->dtype != x->dtype) return fail(VT_ERR_INVALID_ARG, "vt_weighted_sum: x and y must share a 16-bit dtype");
+  if (x->shape.size() != 2 || x->shape != y->shape) return fail(VT_ERR_SHAPE, "vt_weighted_sum: x and y must be [R,C] of equal shape");
+  DevDesc X, Y;
+  int64_t ox, ix, oy, iy;
+  int rc = to_device(*x, &X, &ox, &ix);
+  if (rc != VT_OK) return rc;
+  rc = to_device(*y, &Y, &oy, &iy);
+  if (rc != VT_OK) return rc;
+  if (ox != 1 || oy != 1) return fail(VT_ERR_UNSUPPORTED, "vt_weighted_sum: 2^31 elements or more");
+  if (x->dtype == VT_BF16) return launch_weighted_sum<bf16_t>(*x, *y, X, Y, weights, out, (hipStream_t)stream);
+  return launch_weighted_sum<f16_t>(*x, *y, X, Y, weights, out, (hipStream_t)stream);
 }
 
 int vt_copy_op(const vt_source* in, int n_in, const vt_op* op, void* dst, void* stream) {

@@ -217,6 +217,27 @@ class GemmStore:
         return None
 
 
+class WeightedSum:
+    """consumer kind "weighted_sum" (mixture-of-experts combine): x and y are gathered through row
+    tables; virtual: one launch reads the expert-major buffer in place; materialized: two gather
+    copies, then the same consumer on the dense copies."""
+
+    def __init__(self, dw: DeviceWorkload, materialized=False):
+        c = dw.wl.consumer
+        self.dw = dw
+        self.mat = Materialized(dw, [c["x"], c["y"]]) if materialized else None
+        get = self.mat.identity_desc if materialized else dw.build
+        self.x, self.y = get(c["x"]), get(c["y"])
+        self.w = torch.from_numpy(c["weights"]).to(dw.device)
+        self.out = torch.empty(self.x.shape, dtype=TORCH_DTYPE[dw.wl.dtype], device=dw.device)
+
+    def run(self, stream=None):
+        if self.mat:
+            self.mat.run(stream)
+        vt.vt_weighted_sum(self.x, self.y, self.w, self.out, stream=stream)
+        return self.out
+
+
 class DecodeSegment:
     """Projection with a producer-side store followed by decode attention on the same buffers
     (Sec. 3.1 end to end).  virtual: two launches (vt_gemm_store, vt_decode_attn), no data
@@ -238,6 +259,8 @@ class DecodeSegment:
 def make_pipeline(dw: DeviceWorkload, materialized=False, **kw):
     if dw.wl.consumer["kind"] == "gemm_store":
         return GemmStore(dw, materialized)
+    if dw.wl.consumer["kind"] == "weighted_sum":
+        return WeightedSum(dw, materialized)
     kind = dw.wl.consumer["kind"]
     if kind == "add_rowsum":
         return AddRowsum(dw, materialized)
@@ -251,7 +274,7 @@ def make_pipeline(dw: DeviceWorkload, materialized=False, **kw):
 # ------------------------------------------------------------------------------------------
 def consumer_operands(p):
     """Descriptors the consumer of pipeline `p` reads."""
-    if isinstance(p, AddRowsum):
+    if isinstance(p, (AddRowsum, WeightedSum)):
         return [p.x, p.y]
     if isinstance(p, DecodeAttention):
         return [p.q, p.k, p.v]
