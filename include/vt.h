@@ -198,6 +198,20 @@ int vt_decode_attn_workspace_init(void* workspace, size_t workspace_bytes, void*
 int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float scale, void* out,
                    float* lse, void* workspace, size_t workspace_bytes, int n_splits, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): vt_decode_attn without the workspace argument.  The
+ * partial results and arrival counters live in a fixed array inside the library's own device
+ * memory, vt_decode_attn_static_capacity() bytes (4 MiB) per GPU, held until the process ends.
+ * The call allocates nothing and frees nothing; it queues a small fill kernel that clears the
+ * arrival counters, then the same kernel as vt_decode_attn, and gives the same bits.  Problems
+ * whose workspace (vt_decode_attn_workspace) exceeds the capacity return VT_ERR_INVALID_ARG with a
+ * message naming both sizes; all other arguments and errors are those of vt_decode_attn.  All
+ * calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams,
+ * two threads) race and give wrong results. */
+size_t vt_decode_attn_static_capacity(void);
+int vt_decode_attn_static(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float scale, void* out,
+                          float* lse, int n_splits, void* stream);
+
 /* Copy kernel in the store direction: every element of the virtual tensor src is written to the
  * physical place that dst's map names; other elements of dst's tensors are left alone.  This is
  * the explicit Split / Reshape / ScatterND of the materialized comparison path.  src and dst have

@@ -81,6 +81,9 @@ def lib():
         L.vt_decode_attn_workspace.restype = C.c_size_t
         L.vt_decode_attn_workspace_init.argtypes = [P, C.c_size_t, P]
         L.vt_decode_attn.argtypes = [P, P, P, C.c_float, P, P, P, C.c_size_t, C.c_int, P]
+        L.vt_decode_attn_static_capacity.argtypes = []
+        L.vt_decode_attn_static_capacity.restype = C.c_size_t
+        L.vt_decode_attn_static.argtypes = [P, P, P, C.c_float, P, P, C.c_int, P]
         L.vt_last_error.restype = C.c_char_p
         L.vt_version.restype = C.c_char_p
         _lib = L
@@ -308,6 +311,15 @@ def vt_decode_attn(Q: Desc, K: Desc, V: Desc, scale: float, out, workspace, work
                    lse=None, stream=None):
     _check(lib().vt_decode_attn(Q.handle, K.handle, V.handle, C.c_float(scale), _ptr(out), _ptr(lse),
                                 _ptr(workspace), workspace_bytes, n_splits, _stream(stream)))
+
+
+def vt_decode_attn_static_capacity() -> int:
+    return int(lib().vt_decode_attn_static_capacity())
+
+
+def vt_decode_attn_static(Q: Desc, K: Desc, V: Desc, scale: float, out, n_splits=0, lse=None, stream=None):
+    _check(lib().vt_decode_attn_static(Q.handle, K.handle, V.handle, C.c_float(scale), _ptr(out), _ptr(lse),
+                                       n_splits, _stream(stream)))
 
 
 def vt_gemm_store_workspace(M, N, K) -> int:

@@ -32,7 +32,9 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <numeric>
+#include <string>
 
 #include "vt_coherent.h"
 #include "vt_device.h"
@@ -733,6 +735,32 @@ constexpr int kWaves = 4;
 
 static size_t ticket_bytes(int64_t B, int64_t Hq) { return (size_t)((B * Hq * 4 + 255) / 256 * 256); }
 
+// Workspace of vt_decode_attn_static: a fixed array in the code object's own device memory, so
+// that the call needs no allocation.  Every GPU the library runs on holds its own copy at its
+// own address; the name below is only a host-side handle, the address is asked from the runtime
+// once per device and kept.
+constexpr size_t kScratchBytes = 4u << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+static int scratch_address(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+    return fail(VT_ERR_DEVICE, "vt_decode_attn_static: no current device (or device number above 63)");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p)
+      return fail(VT_ERR_DEVICE, std::string("vt_decode_attn_static: hipGetSymbolAddress failed: ") + hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return VT_OK;
+}
+
 extern "C" {
 
 size_t vt_decode_attn_workspace(int B, int Hq, int D, int S, int n_splits) {
@@ -855,17 +883,23 @@ int vt_decode_attn_plan(const vt_desc* Q, const vt_desc* K, const vt_desc* V, in
   return VT_OK;
 }
 
-int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float scale, void* out, float* lse,
-                   void* workspace, size_t workspace_bytes, int n_splits, void* stream) {
-  if (!out || !workspace) return fail(VT_ERR_INVALID_ARG, "vt_decode_attn: NULL argument");
+// Everything after the plan: workspace carving, launch.  `clear_tickets` queues a small fill
+// kernel over the arrival counters first (for a workspace whose previous contents are not known
+// to be zero).
+static int launch_attention(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float scale, void* out, float* lse,
+                            void* workspace, size_t workspace_bytes, int n_splits, bool clear_tickets,
+                            const char* who, void* stream) {
+  if (!out || !workspace) return fail(VT_ERR_INVALID_ARG, std::string(who) + ": NULL argument");
   AttnParams P;
   int rc = plan_attention(Q, K, V, n_splits, P);
   if (rc != VT_OK) return rc;
   const int64_t B = P.B, Hq = (int64_t)P.Hkv * P.G;
   const int ns_eff = P.n_splits, Hkv = P.Hkv;
   const size_t need = ticket_bytes(B, Hq) + (size_t)B * Hq * ns_eff * ((size_t)kD + 2) * sizeof(float);
-  if (workspace_bytes < need) return fail(VT_ERR_INVALID_ARG, "vt_decode_attn: workspace too small");
-  if ((uintptr_t)workspace % 16 || (uintptr_t)out % 8) return fail(VT_ERR_INVALID_ARG, "vt_decode_attn: misaligned workspace or out (16 and 8 bytes)");
+  if (workspace_bytes < need)
+    return fail(VT_ERR_INVALID_ARG, std::string(who) + ": workspace too small (" + std::to_string(need) + " bytes needed, " +
+                                        std::to_string(workspace_bytes) + " available)");
+  if ((uintptr_t)workspace % 16 || (uintptr_t)out % 8) return fail(VT_ERR_INVALID_ARG, std::string(who) + ": misaligned workspace or out (16 and 8 bytes)");
   P.scale_log2 = scale * 1.4426950408889634f;
   P.tickets = static_cast<uint32_t*>(workspace);
   P.ws_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + ticket_bytes(B, Hq));
@@ -873,6 +907,12 @@ int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float s
   P.out = out;
   P.lse = lse;
   hipStream_t st = (hipStream_t)stream;
+  if (clear_tickets) {
+    const size_t words = ticket_bytes(B, Hq) / 4;
+    hipLaunchKernelGGL(k_zero_words, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, P.tickets, words);
+    rc = check_launch(who);
+    if (rc != VT_OK) return rc;
+  }
   dim3 grid(ns_eff, Hkv, (unsigned)B);
   static const int occ = [] {
     const char* e = getenv("VT_ATTN_OCC");     // tuning knob: waves per SIMD the kernel is compiled for
@@ -885,7 +925,22 @@ int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float s
     if (occ == 2) hipLaunchKernelGGL((k_decode_attn<f16_t, kWaves, 2>), grid, dim3(kWaves * 64), 0, st, P);
     else hipLaunchKernelGGL((k_decode_attn<f16_t, kWaves, 3>), grid, dim3(kWaves * 64), 0, st, P);
   }
-  return check_launch("vt_decode_attn");
+  return check_launch(who);
+}
+
+int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float scale, void* out, float* lse,
+                   void* workspace, size_t workspace_bytes, int n_splits, void* stream) {
+  return launch_attention(Q, K, V, scale, out, lse, workspace, workspace_bytes, n_splits, false, "vt_decode_attn", stream);
+}
+
+size_t vt_decode_attn_static_capacity(void) { return kScratchBytes; }
+
+int vt_decode_attn_static(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float scale, void* out, float* lse,
+                          int n_splits, void* stream) {
+  void* ws = nullptr;
+  int rc = scratch_address(&ws);
+  if (rc != VT_OK) return rc;
+  return launch_attention(Q, K, V, scale, out, lse, ws, kScratchBytes, n_splits, true, "vt_decode_attn_static", stream);
 }
 
 }  // extern "C"
