@@ -57,16 +57,12 @@ def gemm(a: np.ndarray, w: np.ndarray) -> np.ndarray:
 
 
 def ln_linear(x: np.ndarray, w: np.ndarray, eps: float, store_dtype: str = "f16") -> np.ndarray:
-    """LayerNorm, rounded to the storage type (the tensor that a fp16 graph would hand to the
-    linear layer and that the matrix units consume), then the linear layer without bias."""
+    """LayerNorm, rounded to the storage type (the tensor that a 16-bit graph would hand to the
+    linear layer and that the matrix units consume), then the linear layer without bias.  The
+    rounding is the one every 16-bit output takes: round_to below."""
     y = layernorm(x, eps)
-    if store_dtype == "f16":
-        y = y.astype(np.float16).astype(np.float64)
-    elif store_dtype == "bf16":
-        y32 = y.astype(np.float32)
-        bits = y32.view(np.uint32)
-        bits = (bits + np.uint32(0x7FFF) + ((bits >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)
-        y = bits.view(np.float32).astype(np.float64)
+    if store_dtype in ("f16", "bf16"):
+        y = decode(round_to(y, store_dtype), store_dtype)
     lead = y.shape[:-1]
     out = gemm(y.reshape(-1, y.shape[-1]), w)
     return out.reshape(lead + (w.shape[1],))

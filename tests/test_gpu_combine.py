@@ -4,6 +4,7 @@ import numpy as np
 import pytest
 
 import workloads
+from oracle import consumers, dm_ops
 from oracle.run import run_workload
 
 pytestmark = pytest.mark.gpu
@@ -47,3 +48,20 @@ def test_moe_combine_virtual_equals_materialized_bitwise_and_mid_size(gpu):
     torch.cuda.synchronize()
     assert torch.equal(a.out, b.out)
     check(tio.to_host_f64(a.out), run_workload(wl)["out"], 2.0 ** -8)
+
+
+def test_moe_combine_full_size_every_output(gpu):
+    """The combine at the benchmarked size (16384 tokens x 14336 columns), every output; the oracle
+    gathers both operands as dense copies and mixes them in float64, in row blocks to bound memory."""
+    vt, tio, pipelines, torch = gpu
+    wl = workloads.moe_combine()
+    p = pipelines.WeightedSum(tio.DeviceWorkload(wl))
+    p.run()
+    torch.cuda.synchronize()
+    env = dm_ops.run_chain(wl.chain, wl.sources, wl.index_tables, keep={"x", "y"})
+    w = wl.consumer["weights"]
+    assert env["x"].shape == (16384, 14336)
+    for r in range(0, 16384, 2048):
+        ref = consumers.weighted_sum(consumers.decode(env["x"][r:r + 2048], "bf16"),
+                                     consumers.decode(env["y"][r:r + 2048], "bf16"), w[r:r + 2048])
+        check(tio.to_host_f64(p.out[r:r + 2048]), ref, 2.0 ** -8)

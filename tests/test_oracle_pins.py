@@ -307,13 +307,57 @@ def test_gemm_special_cases():
     np.testing.assert_allclose(consumers.gemm(2 * a, w) + consumers.gemm(a, w), 3 * consumers.gemm(a, w), rtol=1e-12)
 
 
-def test_ln_linear_rounds_between():
-    rng = np.random.default_rng(4)
-    x = rng.normal(size=(6, 128)).astype(np.float16)
-    w = (rng.normal(size=(128, 16)) * 0.02).astype(np.float16)
-    out = consumers.ln_linear(x.astype(np.float64), w.astype(np.float64), 1e-5, "f16")
-    y16 = consumers.layernorm(x.astype(np.float64), 1e-5).astype(np.float16).astype(np.float64)
-    np.testing.assert_allclose(out, y16 @ w.astype(np.float64), rtol=1e-13)
+def test_ln_linear_rounds_between_hand_case():
+    """A row whose normalised values are known by hand, with weights that make the rounding
+    between LayerNorm and the product visible.  Row [0,0,0,4]: mean 1, deviations [-1,-1,-1,3],
+    biased variance 3, so y = [-1,-1,-1,3] / sqrt(3) = [-0.57735.., 1.73205..] (eps = 1e-5 moves
+    them by 2e-6 relative, far from any rounding boundary).
+      f16  (ulp 2^-11 below 1, 2^-10 above):  -1182/2048 = -0.5771484375,  1774/1024 = 1.732421875
+      bf16 (ulp 2^-8 below 1, 2^-7 above):    -148/256   = -0.578125,      222/128   = 1.734375
+    Column 0 of W picks y[0]; column 1 = 1024 * (sum of the row): 0 without rounding, and
+    1024 * (1.732421875 - 3 * 0.5771484375) = 1.0 in f16, 1024 * (1.734375 - 3 * 0.578125) = 0 in bf16."""
+    x = np.array([[0.0, 0.0, 0.0, 4.0]])
+    w = np.array([[1.0, 1024.0], [0.0, 1024.0], [0.0, 1024.0], [0.0, 1024.0]])
+    f16 = consumers.ln_linear(x, w, 1e-5, "f16")
+    bf16 = consumers.ln_linear(x, w, 1e-5, "bf16")
+    assert f16.tolist() == [[-0.5771484375, 1.0]]
+    assert bf16.tolist() == [[-0.578125, 0.0]]
+    # the unrounded product differs from both in column 0 and is (nearly) 0 in column 1
+    plain = consumers.gemm(consumers.layernorm(x, 1e-5), w)
+    assert abs(plain[0, 0] + 0.5773493) < 1e-6 and abs(plain[0, 1]) < 1e-9
+    # leading dims are kept: [2,1,4] -> [2,1,2]
+    assert consumers.ln_linear(np.stack([x, 2 * x]), w, 1e-5, "bf16").shape == (2, 1, 2)
+
+
+def test_ln_linear_rounding_is_round_to_nearest_even_on_ties():
+    """Values that sit exactly between two bf16 / f16 numbers after LayerNorm cannot be made by
+    hand (the normalisation is irrational), so ties are checked on the rounding itself, which
+    ln_linear shares with every 16-bit output: 1 + 2^-8 -> 1 (even), 1 + 3 * 2^-8 -> 1 + 2^-6."""
+    v = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -(1.0 + 2.0 ** -8), 1.0 + 2.0 ** -8 + 2.0 ** -20])
+    got = consumers.decode(consumers.round_to(v, "bf16"), "bf16")
+    assert got.tolist() == [1.0, 1.0 + 2.0 ** -6, -1.0, 1.0 + 2.0 ** -7]
+
+
+def test_grouped_gemm_rows_are_expert_major():
+    """Config 5's output buffer: expert 0's rows first (its tokens in ascending id), then expert
+    1's, ...; row r of expert e's block is tokens[idx_e[r]] . W[e].  Checked on a tiny case with
+    plain loops over the routing tables, values chosen so that every product is exact."""
+    wl = workloads.c5_moe_dispatch(seed=7, T=12, Hd=4, E=3, N=5)
+    rng = np.random.default_rng(0)
+    tok = rng.integers(-3, 4, size=(12, 4)).astype(np.float32)
+    W = rng.integers(-2, 3, size=(3, 4, 5)).astype(np.float32)
+    wl.sources["tokens"], wl.sources["W"] = workloads.encode(tok, "bf16"), workloads.encode(W, "bf16")
+    out = run_workload(wl)["out"]
+    assert out.shape == (24, 5)
+    r = 0
+    for e in range(3):
+        idx = wl.index_tables["idx%d" % e]
+        assert list(idx) == sorted(set(idx))
+        for t in idx:
+            want = [sum(float(tok[t, k]) * float(W[e, k, n]) for k in range(4)) for n in range(5)]
+            assert out[r].tolist() == want, (e, t, r)
+            r += 1
+    assert r == 24
 
 
 def _naive_attention(q, k, v, scale):

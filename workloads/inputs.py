@@ -46,10 +46,17 @@ def encode(x32: np.ndarray, dtype: str) -> np.ndarray:
     if dtype == "f16":
         return x32.astype(np.float16)
     if dtype == "bf16":
-        bits = x32.view(np.uint32)
-        lsb = (bits >> np.uint32(16)) & np.uint32(1)
-        rounded = bits + np.uint32(0x7FFF) + lsb
-        return (rounded >> np.uint32(16)).astype(np.uint16)
+        out = np.empty(x32.shape, dtype=np.uint16)
+        src, dst = x32.reshape(-1).view(np.uint32), out.reshape(-1)
+        step = 1 << 22                         # in slices: the temporaries stay in cache
+        for i in range(0, src.size, step):
+            bits = src[i:i + step]
+            t = (bits >> np.uint32(16)) & np.uint32(1)
+            t += bits
+            t += np.uint32(0x7FFF)
+            t >>= np.uint32(16)
+            dst[i:i + step] = t
+        return out
     raise ValueError(dtype)
 
 
@@ -62,11 +69,25 @@ def _uniform(seed, k, shape, dtype):
 
 
 def _normal(seed, k, shape, std, dtype):
+    """N(0, std) in float32 from stream (seed, k), rounded to `dtype`.  Large tensors are drawn in
+    slices from the one generator (the stream, and so every value, is that of a single draw)."""
     g = _rng(seed, k)
-    x = g.standard_normal(size=shape, dtype=np.float32)
-    if std != 1.0:
-        x *= np.float32(std)
-    return encode(x, dtype)
+    n = int(np.prod(shape))
+    step = 1 << 22
+    if n <= step:
+        x = g.standard_normal(size=shape, dtype=np.float32)
+        if std != 1.0:
+            x *= np.float32(std)
+        return encode(x, dtype)
+    out = np.empty(n, dtype={"f32": np.float32, "f16": np.float16, "bf16": np.uint16}[dtype])
+    buf = np.empty(step, dtype=np.float32)
+    for i in range(0, n, step):
+        x = buf[:min(step, n - i)]
+        g.standard_normal(out=x, dtype=np.float32)
+        if std != 1.0:
+            x *= np.float32(std)
+        out[i:i + x.size] = encode(x, dtype)
+    return out.reshape(shape)
 
 
 # ----------------------------------------------------------------------------------------
