@@ -9,6 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libvt.so")
+LIB_PROFILE = os.path.join(HERE, "libvt_profile.so")   # same sources with -DVT_PROFILE: per-workgroup timestamps
 
 HOST_SOURCES = ["vt_build.cpp", "vt_device_host.cpp"]
 HIP_SOURCES = ["vt_kernels.hip", "vt_attn.hip", "vt_gemm.hip", "vt_ln_gemm.hip", "vt_gemm_store.hip"]
@@ -17,20 +18,40 @@ COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC, "-Wall", "-Wn
 # gfx950 only; packed-fp32 instructions are switched off (they have given wrong results on
 # the target machines), the compiler still emits ordinary fp32 code.
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-          "-Wno-unknown-warning-option"]
+          "-Wno-unknown-warning-option", "-Rpass-analysis=kernel-resource-usage", "-fno-caret-diagnostics"]
+# Kernels whose waits count vector memory operations by hand, or whose speed depends on their
+# register budget: a spill (scratch) would add memory operations the counts do not know of.
+# The build fails if the compiler reports scratch for any of them.
+NO_SCRATCH = ("k_decode_attn", "k_ln_gemm", "k_gemm_store", "k_gemm")
+
+
+def scratch_report(compiler_output: str):
+    """[(kernel, scratch bytes per lane)] from the compiler's kernel-resource-usage remarks."""
+    res, name = [], None
+    for line in compiler_output.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].split("[")[0].strip()
+        elif "ScratchSize [bytes/lane]:" in line and name:
+            res.append((name, int(line.split("ScratchSize [bytes/lane]:")[1].split("[")[0])))
+            name = None
+    return res
 
 
 def hipcc() -> str:
     return os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
-def build(verbose: bool = True, jobs: int = 4) -> str:
+def build(verbose: bool = True, jobs: int = 4, profile: bool = False) -> str:
+    """Compile and link libvt.so, or with profile=True libvt_profile.so (the kernels record
+    per-workgroup timestamps that profile_trace.py reads; load it through VT_LIB_PATH)."""
     objs = []
     procs = []
     os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
+    tag = ".prof" if profile else ""
+    lib = LIB_PROFILE if profile else LIB
     for src in HOST_SOURCES + HIP_SOURCES:
-        obj = os.path.join(HERE, "_build", src + ".o")
-        cmd = [hipcc()] + COMMON + (DEVICE if src.endswith(".hip") else []) + ["-c", os.path.join(CSRC, src), "-o", obj]
+        obj = os.path.join(HERE, "_build", src + tag + ".o")
+        cmd = [hipcc()] + COMMON + (["-DVT_PROFILE"] if profile else []) + (DEVICE if src.endswith(".hip") else []) + ["-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print("[build]", " ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -43,6 +64,12 @@ def build(verbose: bool = True, jobs: int = 4) -> str:
     failed = False
     for src, p in procs:
         out, _ = p.communicate()
+        for kernel, scratch in scratch_report(out):
+            if scratch and any(k in kernel for k in NO_SCRATCH):
+                print("[build] FAILED: %s uses %d bytes of scratch per lane (%s)" % (kernel, scratch, src), file=sys.stderr)
+                failed = True
+        out = "\n".join(l for l in out.splitlines() if "-Rpass-analysis=kernel-resource-usage" not in l
+                        and "is not a recognized feature" not in l)
         if out.strip() and verbose:
             print(out)
         if p.returncode != 0:
@@ -52,12 +79,12 @@ def build(verbose: bool = True, jobs: int = 4) -> str:
             failed = True
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs
+    cmd = [hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", lib] + objs
     if verbose:
         print("[build]", " ".join(cmd), flush=True)
     subprocess.check_call(cmd)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
-    build()
+    build(profile="--profile" in sys.argv)

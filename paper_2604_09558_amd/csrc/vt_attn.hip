@@ -39,8 +39,14 @@
 #include "vt_coherent.h"
 #include "vt_device.h"
 #include "vt_numeric.h"
+#include "vt_profile.h"
 
 using namespace vt;
+
+// profile marks: 0 start, 1 first K tile staged, 2 tile loop done (all waves), 3 partial results
+// stored, 4 ticket taken, 5 merge written, 6 merge loads landed, 7 compute die
+VT_PROF_DECLARE(attn)
+#define ATTN_WG (blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z))
 
 namespace {
 
@@ -91,6 +97,7 @@ struct AttnParams {
   const char* q_ptr;
   int64_t q_sb, q_sh;    // bytes
   int32_t B, Hkv, G, S, n_splits, rows_per_split;
+  int32_t unit_major;    // 1: 1-D grid, all splits of a (batch, kv head) unit on one compute die
   float scale_log2;      // softmax scale * log2(e)
   uint32_t* tickets;     // [B, Hkv], zero between launches
   float* ws_ml;          // [B, Hkv, n_splits, G, 2]
@@ -162,9 +169,14 @@ struct TileWalk {
 // One table entry, read on the scalar unit (the table is read-only for the kernel; a vector
 // load would queue behind the K/V rows already in flight).
 __device__ __forceinline__ int32_t table_entry(const int32_t* tab, uint32_t idx) {
+  // table and index are wave-uniform by construction; readfirstlane states it, so that the scalar
+  // operands below do not depend on what the compiler's uniformity analysis can prove
+  const uint64_t t = reinterpret_cast<uint64_t>(tab);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)t), hi = __builtin_amdgcn_readfirstlane((uint32_t)(t >> 32));
+  const int32_t* utab = reinterpret_cast<const int32_t*>(((uint64_t)hi << 32) | lo);
+  const uint32_t off = __builtin_amdgcn_readfirstlane(idx * 4u);
   int32_t v;
-  const uint32_t off = idx * 4u;
-  asm volatile("s_load_dword %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(tab), "s"(off) : "memory");
+  asm volatile("s_load_dword %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(utab), "s"(off) : "memory");
   return v;
 }
 
@@ -263,7 +275,18 @@ k_decode_attn(const AttnParams P) {
   __shared__ float red_ml[WAVES * 16 * 2];   // [WAVES][16][2]
   __shared__ uint32_t ticket_sh;
 
-  const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+  VT_PROF_BEGIN();
+  VT_PROF(0);
+  int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+  if (P.unit_major) {
+    // workgroups go to the compute dies round-robin by linear id: die = id % 8.  Unit u runs on
+    // die u % 8, its splits one after the other in that die's share of the ids.
+    const int id = blockIdx.x, slot = id >> 3;
+    const int unit = (slot / P.n_splits) * 8 + (id & 7);
+    split = slot % P.n_splits;
+    g = unit % P.Hkv;
+    b = unit / P.Hkv;
+  }
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int l16 = lane & 15, lg = lane >> 4;
   const int t_begin = split * P.rows_per_split;
@@ -356,6 +379,7 @@ k_decode_attn(const AttnParams P) {
       int r = 4 * j + lg;
       my_lds[r * 16 + (l16 ^ (r & 15))] = make_uint4(kst[j].w[0], kst[j].w[1], kst[j].w[2], kst[j].w[3]);
     }
+    VT_PROF_ONCE(1);
     if (more) issue_k(cur);              // next tile's K is in flight during this tile's math
 
     // ---- S^T = K . Q^T : two 16-row blocks, 4 k-steps each
@@ -419,6 +443,7 @@ k_decode_attn(const AttnParams P) {
   l_run += __shfl_xor(l_run, 16, 64);
   l_run += __shfl_xor(l_run, 32, 64);
   __syncthreads();                       // every wave is done with its K tile
+  VT_PROF(2);
   float* red_o = reinterpret_cast<float*>(&lds[0][0]);    // [WAVES][G][D] floats: at most the K tiles' 32 KB
   const int G = P.G;
   if (l16 < G) {
@@ -464,9 +489,14 @@ k_decode_attn(const AttnParams P) {
   // ready for the next launch.  No wave ever waits for another workgroup.
   __builtin_amdgcn_s_waitcnt(0);         // this wave's stores have completed (vmcnt = 0)
   __syncthreads();
+  VT_PROF(3);
   if (threadIdx.x == 0) ticket_sh = atomicInc(&P.tickets[bg], (uint32_t)(P.n_splits - 1));
   __syncthreads();
-  if (ticket_sh != (uint32_t)(P.n_splits - 1)) return;
+  VT_PROF(4);
+  if (ticket_sh != (uint32_t)(P.n_splits - 1)) {
+    VT_PROF_FLUSH(attn, ATTN_WG);
+    return;
+  }
   const size_t u0 = (size_t)bg * P.n_splits;
   const int ns = P.n_splits;
   T* out = static_cast<T*>(P.out);
@@ -488,6 +518,7 @@ k_decode_attn(const AttnParams P) {
     for (int u = 0; u < 8; ++u) q[u] = &P.ws_o[((u0 + min(u, ns - 1)) * G + h0) * kD + d0];
     load_device_8xb128(q, v0);
   }
+  VT_PROF(6);
   if (i_ml < ns * G * 2) ml_sh[i_ml] = ml_first;
   for (int i = i_ml + WAVES * 64; i < ns * G * 2; i += WAVES * 64) ml_sh[i] = ld(&P.ws_ml[u0 * G * 2 + i]);
   __syncthreads();
@@ -525,6 +556,11 @@ k_decode_attn(const AttnParams P) {
     *reinterpret_cast<Vec<T, 4>*>(&out[hq * kD + d]) = r;
     if (P.lse && d == 0) P.lse[hq] = (mx + log2f(l)) * 0.6931471805599453f;
   }
+#ifdef VT_PROFILE
+  __builtin_amdgcn_s_waitcnt(0);
+  VT_PROF(5);
+  VT_PROF_FLUSH(attn, ATTN_WG);
+#endif
 }
 
 __global__ void k_zero_words(uint32_t* p, size_t n) {
@@ -914,6 +950,14 @@ static int launch_attention(const vt_desc* Q, const vt_desc* K, const vt_desc* V
     if (rc != VT_OK) return rc;
   }
   dim3 grid(ns_eff, Hkv, (unsigned)B);
+  static const int unit_major = [] {
+    const char* e = getenv("VT_ATTN_UNIT_MAJOR");
+    return e ? atoi(e) : 0;
+  }();
+  if (unit_major && (B * Hkv) % 8 == 0) {
+    P.unit_major = 1;
+    grid = dim3((unsigned)(ns_eff * Hkv * B), 1, 1);
+  }
   static const int occ = [] {
     const char* e = getenv("VT_ATTN_OCC");     // tuning knob: waves per SIMD the kernel is compiled for
     return e && atoi(e) == 2 ? 2 : 3;

@@ -1,0 +1,113 @@
+"""Per-workgroup timelines of the hand-scheduled kernels on the benchmark's workloads.
+
+Needs the profiling build of the library (`python -m paper_2604_09558_amd.build --profile`, which
+compiles the same sources with -DVT_PROFILE into libvt_profile.so): its kernels mark a few points
+per workgroup with the 100 MHz wall clock, and this script prints when those points are reached
+(min / median / max over the workgroups, microseconds from the first workgroup's start) and how
+the compute dies compare.  The marks cost a little time: read the ordinary library's duration
+from rocprofv3, and the shape of the timeline from here.
+
+    python -m paper_2604_09558_amd.profile_trace attn [--n-splits N] [--reps R]
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import os
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+from paper_2604_09558_amd import binding  # noqa: E402
+
+assert binding._lib is None, "the library is already loaded"
+binding.LIB_PATH = os.path.join(HERE, "libvt_profile.so")       # every call below goes to the profiling build
+
+SLOTS = 8
+MARKS = {
+    "attn": ["start", "first K tile staged", "tile loop done", "partial results stored", "ticket taken",
+             "merge written", "merge loads landed"],
+}
+
+
+def read_marks(lib, kernel, n_wg):
+    buf = (C.c_longlong * (n_wg * SLOTS))()
+    fn = getattr(lib, "vt_profile_read_" + kernel)
+    fn.argtypes = [C.POINTER(C.c_longlong), C.c_int]
+    rc = fn(buf, n_wg)
+    if rc != 0:
+        raise RuntimeError("vt_profile_read_%s failed (%d)" % (kernel, rc))
+    rate = getattr(lib, "vt_profile_ticks_per_us_" + kernel)
+    rate.restype = C.c_double
+    return np.array(buf[:], dtype=np.int64).reshape(n_wg, SLOTS), float(rate())
+
+
+def report(kernel, marks):
+    t, ticks_per_us = marks
+    xcc = t[:, 7]
+    t0 = t[:, 0][t[:, 0] > 0].min()
+    fresh = (t[:, :7] > 0) & (t[:, :7] >= t[:, 0:1])       # marks older than the workgroup's own start are a previous launch's
+    us = np.where(fresh, (t[:, :7] - t0) / ticks_per_us, np.nan)
+    for k, name in enumerate(MARKS[kernel]):
+        col = us[:, k][~np.isnan(us[:, k])]
+        if col.size:
+            print("  %-24s min %6.2f  median %6.2f  max %6.2f   (%d workgroups)" % (name, col.min(), np.median(col), col.max(), col.size))
+    if kernel == "attn":
+        m = ~np.isnan(us[:, 5])                       # the workgroups that merged
+        steps = [("tile loop done -> partial results stored", 2, 3), ("-> ticket taken", 3, 4), ("-> merge loads landed", 4, 6),
+                 ("-> merge written", 6, 5)]
+        print("  merging workgroups, median step: " + "; ".join("%s %.2f" % (n, np.median(us[m, b] - us[m, a])) for n, a, b in steps))
+        print("  last mark of the launch %.2f us = last tile loop done %.2f + %.2f" % (
+            np.nanmax(us[:, 5]), np.nanmax(us[:, 2]), np.nanmax(us[:, 5]) - np.nanmax(us[:, 2])))
+    k_done = 2
+    print("  '%s' by compute die (median / max): " % MARKS[kernel][k_done] +
+          "  ".join("%d: %.1f/%.1f" % (x, np.nanmedian(us[xcc == x, k_done]), np.nanmax(us[xcc == x, k_done]))
+                    for x in sorted(set(xcc.tolist()))))
+    print("  workgroups per compute die: " + " ".join("%d:%d" % (x, int((xcc == x).sum())) for x in sorted(set(xcc.tolist()))))
+
+
+def trace_attn(a):
+    import torch
+    import workloads
+    import paper_2604_09558_amd as vt
+    from paper_2604_09558_amd import pipelines, torch_io as tio
+    lib = vt.lib()
+    copies = [tio.DeviceWorkload(workloads.c2_decode_attention(seed=s)) for s in range(4)]
+    ps = [pipelines.DecodeAttention(dw, n_splits=a.n_splits, want_lse=False) for dw in copies]
+    plan = vt.vt_decode_attn_plan(ps[0].q, ps[0].k, ps[0].v, a.n_splits)
+    B, Hq, S, D = ps[0].k.shape
+    n_wg = plan["splits"] * (Hq // plan["group_size"]) * B
+    for _ in range(3):
+        for p in ps:
+            p.run()
+    torch.cuda.synchronize()
+    read_marks(lib, "attn", n_wg)
+    for rep in range(a.reps):
+        # three launches on other input copies push this one's K/V out of the caches; the marks kept are the last launch's
+        for p in (ps[2], ps[3], ps[0]):
+            p.run()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ps[1].run()
+        e1.record()
+        torch.cuda.synchronize()
+        print("config 2, %d workgroups (%d splits), launch %d: %.1f us between events" % (n_wg, plan["splits"], rep, e0.elapsed_time(e1) * 1e3))
+        report("attn", read_marks(lib, "attn", n_wg))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("kernel", choices=sorted(MARKS))
+    ap.add_argument("--n-splits", type=int, default=0)
+    ap.add_argument("--reps", type=int, default=3)
+    a = ap.parse_args()
+    {"attn": trace_attn}[a.kernel](a)
+
+
+if __name__ == "__main__":
+    main()
