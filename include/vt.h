@@ -116,6 +116,21 @@ int vt_desc_info(const vt_desc* d, int* ndim, int64_t* shape, int* dtype,
 typedef enum { VT_ACCESS_FULL = 0, VT_ACCESS_PARTIAL = 1, VT_ACCESS_SCATTERED = 2 } vt_access_class;
 int vt_classify(const vt_desc* d, int64_t unit_bytes, int* access_class, int64_t* min_run_bytes);
 
+/* Block form of the contiguity analysis (Sec. 4.2, block-wise virtual tensor I/O; Sec. 4.3 Def. 4):
+ * the largest power of two c <= cap_elems such that EVERY aligned group of c consecutive elements
+ * of the virtual tensor, in row-major order, lies in one piece and is one contiguous range of its
+ * source.  The copy kernels and the elementwise consumer apply the map once per such block.
+ * Host only; c = 1 always holds. */
+int vt_desc_block(const vt_desc* d, int64_t cap_elems, int64_t* block_elems);
+
+/* Is the map an ordinary strided view of one tensor (one stride per dim, one offset: what a
+ * framework's tensor object can hold without copying)?  is_strided receives 1 or 0; if 1, stride
+ * (VT_MAX_DIMS entries, elements; 0 for a broadcast or size-1 dim) and offset (elements from the
+ * source's ptr) are filled when non-NULL.  Used to tell the operators a stride-aware framework
+ * executes as views from those it must execute as copies (the lean materialized comparison
+ * path).  Host only. */
+int vt_desc_as_strided(const vt_desc* d, int* is_strided, int64_t* stride, int64_t* offset);
+
 /* Piece p: its box [lo,hi) in virtual index space, its source number and its own run. */
 int vt_desc_piece(const vt_desc* d, int p, int64_t* lo, int64_t* hi, int* src_id, int64_t* run);
 /* CPU evaluation of the map at one virtual index (host logic; used by tests).  vindex holds

@@ -63,6 +63,8 @@ def lib():
         L.vt_desc_piece.argtypes = [P, C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int),
                                     C.POINTER(C.c_int64)]
         L.vt_classify.argtypes = [P, C.c_int64, C.POINTER(C.c_int), C.POINTER(C.c_int64)]
+        L.vt_desc_block.argtypes = [P, C.c_int64, C.POINTER(C.c_int64)]
+        L.vt_desc_as_strided.argtypes = [P, C.POINTER(C.c_int), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
         L.vt_eval_host.argtypes = [P, C.POINTER(C.c_int64), C.POINTER(C.c_int), C.POINTER(C.c_int64)]
         L.vt_eval_device_form.argtypes = [P, C.POINTER(C.c_int64), C.POINTER(C.c_int), C.POINTER(C.c_int64)]
         L.vt_desc_dump.argtypes = [P, C.c_char_p, C.c_size_t]
@@ -178,6 +180,21 @@ class Desc:
         cls, run = C.c_int(), C.c_int64()
         _check(lib().vt_classify(self.handle, unit_bytes, C.byref(cls), C.byref(run)))
         return cls.value, run.value
+
+    def block(self, cap_elems=1 << 20):
+        """Largest power-of-two block (elements, <= cap) that is contiguous in one source wherever it is aligned."""
+        out = C.c_int64()
+        _check(lib().vt_desc_block(self.handle, cap_elems, C.byref(out)))
+        return out.value
+
+    def as_strided(self):
+        """(strides, offset) in elements if the map is a plain strided view of one tensor, else None."""
+        flag, off = C.c_int(), C.c_int64()
+        st = (C.c_int64 * VT_MAX_DIMS)()
+        _check(lib().vt_desc_as_strided(self.handle, C.byref(flag), st, C.byref(off)))
+        if not flag.value:
+            return None
+        return tuple(st[i] for i in range(len(self.shape))), off.value
 
     def piece(self, p):
         lo, hi = (C.c_int64 * VT_MAX_DIMS)(), (C.c_int64 * VT_MAX_DIMS)()

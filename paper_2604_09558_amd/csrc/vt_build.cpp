@@ -687,6 +687,21 @@ int vt_desc_info(const vt_desc* d, int* ndim, int64_t* shape, int* dtype, int64_
   return VT_OK;
 }
 
+int vt_desc_as_strided(const vt_desc* d, int* is_strided, int64_t* stride, int64_t* offset) {
+  if (!d || !is_strided) return fail(VT_ERR_INVALID_ARG, "vt_desc_as_strided: NULL argument");
+  *is_strided = 0;
+  if (d->pieces.size() != 1 || !d->pieces[0].v.lower.empty()) return VT_OK;
+  const Piece& p = d->pieces[0];
+  for (size_t i = 0; i < d->shape.size(); ++i) {
+    const auto& g = p.v.groups[i];
+    if (g.size() > 1 || (g.size() == 1 && g[0].table >= 0)) return VT_OK;
+    if (stride) stride[i] = g.empty() ? 0 : g[0].stride;
+  }
+  if (offset) *offset = p.v.base;
+  *is_strided = 1;
+  return VT_OK;
+}
+
 int vt_classify(const vt_desc* d, int64_t unit_bytes, int* access_class, int64_t* min_run_bytes) {
   if (!d || !access_class) return fail(VT_ERR_INVALID_ARG, "vt_classify: NULL argument");
   if (unit_bytes < 0) return fail(VT_ERR_INVALID_ARG, "vt_classify: negative unit");

@@ -126,6 +126,9 @@ __host__ __device__ __forceinline__ int vtd_eval(const DevDesc& D, uint32_t o, u
 // every piece boundary and every offset at which a run can start, and the source pointers are
 // 16-byte aligned.  Always >= 1.
 int vector_width(const vt_desc& d);
+// Largest power of two c <= cap such that aligned groups of c consecutive virtual elements are
+// one contiguous range of one source each (the block form of vector_width; no alignment claim).
+int64_t block_elems(const vt_desc& d, int64_t cap);
 
 // launch bookkeeping shared by the kernels' host wrappers
 int check_launch(const char* what);

@@ -1,6 +1,7 @@
 // Host helpers: conversion of a descriptor to its device form, vector-width analysis.
 #include <algorithm>
 #include <cstring>
+#include <vector>
 
 #include "vt_device.h"
 
@@ -114,6 +115,32 @@ int vector_width(const vt_desc& d) {
   return vec;
 }
 
+// The block form of vector_width (block-wise virtual tensor I/O, Sec. 4.2): the largest power of
+// two c <= cap such that every aligned group of c consecutive elements of the virtual tensor (in
+// row-major order) lies in one piece and is one contiguous range of its source.  Conditions, per
+// piece: c divides the piece's run; where the piece is narrower than the tensor along a dim, c
+// divides the row-major positions at which the piece starts, ends and repeats along that dim.
+// c = 1 always holds.
+int64_t block_elems(const vt_desc& d, int64_t cap) {
+  const int n = (int)d.shape.size();
+  std::vector<int64_t> suffix(n + 1, 1);
+  for (int i = n - 1; i >= 0; --i) suffix[i] = suffix[i + 1] * d.shape[i];
+  auto ok = [&](int64_t c) {
+    if (suffix[0] % c) return false;
+    for (const Piece& p : d.pieces) {
+      if (p.run % c) return false;
+      for (int i = 0; i < n; ++i) {
+        if (p.lo[i] == 0 && p.hi[i] == d.shape[i]) continue;
+        if ((p.lo[i] * suffix[i + 1]) % c || (p.hi[i] * suffix[i + 1]) % c || suffix[i] % c) return false;
+      }
+    }
+    return true;
+  };
+  int64_t c = 1;
+  while (c * 2 <= cap && ok(c * 2)) c *= 2;
+  return c;
+}
+
 // A physical tensor may be written through a map only if no two virtual elements share a
 // physical one.  Sufficient conditions checked here: no broadcast digit, no index table, no
 // stacked stage; inside a piece the digits, ordered by stride, nest (each stride at least the
@@ -173,6 +200,12 @@ extern "C" int vt_eval_device_form(const vt_desc* d, const int64_t* vindex, int*
   if (p < 0) return fail(VT_ERR_RANGE, "vt_eval_device_form: no piece holds the index");
   if (piece) *piece = p;
   if (elem_offset) *elem_offset = off;
+  return VT_OK;
+}
+
+extern "C" int vt_desc_block(const vt_desc* d, int64_t cap_elems, int64_t* block_elems_out) {
+  if (!d || !block_elems_out || cap_elems < 1) return vt::fail(VT_ERR_INVALID_ARG, "vt_desc_block: NULL argument or cap < 1");
+  *block_elems_out = vt::block_elems(*d, cap_elems);
   return VT_OK;
 }
 

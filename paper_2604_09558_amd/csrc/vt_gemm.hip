@@ -27,9 +27,14 @@
 #include <type_traits>
 
 #include "vt_gemm_common.h"
+#include "vt_profile.h"
 
 using namespace vt;
 using namespace vt::gemm;
+
+// profile marks: 0 start, 1 first tiles in LDS (K loop starts), 2 K loop done, 3 tile stored, 4 and 5 the
+// shader cycle counter at marks 1 and 2, 7 compute die
+VT_PROF_DECLARE(gemm)
 
 namespace {
 
@@ -79,6 +84,8 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P, const OutMap O
   __shared__ uint32_t step_a[kMaxSteps];
   __shared__ int64_t step_b[kMaxSteps];
 
+  VT_PROF_BEGIN();
+  VT_PROF(0);
   // ---- which tile: XCD-contiguous bands, groups of kGroupRows tile rows
   const int wg = blockIdx.x;
   const int slot = wg >> 3;
@@ -285,6 +292,8 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P, const OutMap O
     }
   }
   __syncthreads();
+  VT_PROF(1);
+  VT_PROF_CYCLES(4);
 #pragma unroll
   for (int f = 0; f < 8; ++f) read_frag(0, 0, 0, f);
   int it = 0;
@@ -295,6 +304,8 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P, const OutMap O
   }
   k_step(it, std::false_type{}, std::false_type{});
 #undef VT_SB
+  VT_PROF(2);
+  VT_PROF_CYCLES(5);
 
   if (MAPPED) {
     // ---- stage 3 through the output map.  The row part of the map is evaluated once per row of
@@ -350,6 +361,12 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P, const OutMap O
             if (row0 + 8 * j + i < Mg) cp[(size_t)(8 * j + i) * N] = from_float<CT>(acc[mb][nb][4 * j + i]);
       }
     }
+#ifdef VT_PROFILE
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  VT_PROF(3);
+  VT_PROF_FLUSH(gemm, blockIdx.x);
+#endif
 }
 
 int plan_a(const vt_desc& d, GemmGroup* g, int64_t* M, int64_t* K) {

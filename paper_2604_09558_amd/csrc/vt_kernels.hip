@@ -2,6 +2,8 @@
 // elementwise / reduction consumer (vt_elementwise).  gfx950, wave64.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "vt_device.h"
 #include "vt_numeric.h"
 
@@ -42,6 +44,100 @@ __global__ void __launch_bounds__(256) k_scatter(const DevDesc S, const DevDesc 
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Block-wise copy (Sec. 4.2, block-wise virtual tensor I/O): the tensor is cut into aligned
+// blocks of BL * 16 bytes, each one contiguous range of one source (the host's block analysis
+// guarantees it).  A wave takes `rb` consecutive blocks per round: every lane applies the map
+// ONCE, to the first element of "its" block; the block addresses are then handed round with
+// lane shuffles and all 64 lanes move 64 / BL blocks per instruction, 16 bytes each, so that the
+// index arithmetic is paid once per block and not once per vector.  SCATTER: the destination
+// goes through a map as well (store direction), otherwise it is dense.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t shfl_u64(uint64_t v, int src_lane) {
+  const uint32_t lo = __shfl((uint32_t)v, src_lane, 64), hi = __shfl((uint32_t)(v >> 32), src_lane, 64);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+template <int BL, bool SCATTER>
+__global__ void __launch_bounds__(256) k_copy_blocks(const DevDesc S, const DevDesc D, char* __restrict__ dst,
+                                                     uint32_t inner_blocks, uint32_t block_elems, uint32_t rb, uint32_t outer) {
+  constexpr int G = 64 / BL;                         // blocks moved by one instruction
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t wv = blockIdx.x * 4u + (threadIdx.x >> 6);
+  const uint32_t first = wv * rb;                    // this wave's blocks: [first, first + rb)
+  if (first >= inner_blocks) return;
+  const uint32_t n_here = min(rb, inner_blocks - first);
+  const uint32_t sub = lane / BL, c16 = (lane % BL) * 16u;
+  const uint32_t iters = (n_here + G - 1) / G;
+  for (uint32_t o = blockIdx.y; o < outer; o += gridDim.y) {
+    const uint32_t mine = first + min(lane, n_here - 1);
+    int64_t off;
+    const void* ptr;
+    vtd_eval(S, o, mine * block_elems, &off, &ptr);
+    const uint64_t src_addr = reinterpret_cast<uint64_t>(ptr) + (uint64_t)(off * S.elem_size);
+    uint64_t dst_addr;
+    if (SCATTER) {
+      vtd_eval(D, o, mine * block_elems, &off, &ptr);
+      dst_addr = reinterpret_cast<uint64_t>(ptr) + (uint64_t)(off * D.elem_size);
+    } else {
+      dst_addr = reinterpret_cast<uint64_t>(dst) + ((uint64_t)o * inner_blocks + mine) * (uint64_t)(BL * 16);
+    }
+    for (uint32_t j0 = 0; j0 < iters; j0 += 8) {
+      uint4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const uint32_t blk = (j0 + u) * G + sub;
+        const uint64_t a = shfl_u64(src_addr, (int)min(blk, 63u));
+        if (j0 + u < iters && blk < n_here) v[u] = *reinterpret_cast<const uint4*>(a + c16);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const uint32_t blk = (j0 + u) * G + sub;
+        const uint64_t a = shfl_u64(dst_addr, (int)min(blk, 63u));
+        if (j0 + u < iters && blk < n_here) *reinterpret_cast<uint4*>(a + c16) = v[u];
+      }
+    }
+  }
+}
+
+// Picks the block size and launches k_copy_blocks; returns false if the maps allow no block of
+// at least 32 bytes (the caller then moves single vectors).
+static bool launch_copy_blocks(const vt_desc& s, const vt_desc* d, const DevDesc& S, const DevDesc& D, void* dst, int64_t outer,
+                               int64_t inner, hipStream_t stream) {
+  const int esz = dtype_size(s.dtype);
+  if (vector_width(s) * esz != 16 || (d && vector_width(*d) * esz != 16) || (!d && (uintptr_t)dst % 16)) return false;
+  int64_t be = block_elems(s, 1024 / esz);
+  if (d) be = std::min(be, block_elems(*d, 1024 / esz));
+  while (be > 1 && inner % be) be >>= 1;
+  const int bl = (int)(be * esz / 16);
+  if (bl < 2) return false;
+  const int64_t blocks = inner / be;
+  if (blocks >= (1ll << 31)) return false;
+  // blocks per wave and round: as many as keep about 4096 waves busy, at least one instruction's worth
+  uint32_t rb = 64;
+  while (rb > (uint32_t)(64 / bl) && blocks / rb < 4096) rb >>= 1;
+  const int64_t waves = (blocks + rb - 1) / rb;
+  dim3 grid((unsigned)((waves + 3) / 4), (unsigned)std::min<int64_t>(outer, 65535));
+#define VT_COPY_BLOCKS(BLV)                                                                                         \
+  case BLV:                                                                                                         \
+    if (d) hipLaunchKernelGGL((k_copy_blocks<BLV, true>), grid, dim3(256), 0, stream, S, D, (char*)nullptr,         \
+                              (uint32_t)blocks, (uint32_t)be, rb, (uint32_t)outer);                                 \
+    else hipLaunchKernelGGL((k_copy_blocks<BLV, false>), grid, dim3(256), 0, stream, S, S, (char*)dst,              \
+                            (uint32_t)blocks, (uint32_t)be, rb, (uint32_t)outer);                                   \
+    break;
+  switch (bl) {
+    VT_COPY_BLOCKS(2)
+    VT_COPY_BLOCKS(4)
+    VT_COPY_BLOCKS(8)
+    VT_COPY_BLOCKS(16)
+    VT_COPY_BLOCKS(32)
+    VT_COPY_BLOCKS(64)
+    default: return false;
+  }
+#undef VT_COPY_BLOCKS
+  return true;
+}
+
 static int launch_scatter(const vt_desc& s, const vt_desc& d, hipStream_t stream) {
   DevDesc S, D;
   int64_t outer, inner, outer2, inner2;
@@ -49,6 +145,7 @@ static int launch_scatter(const vt_desc& s, const vt_desc& d, hipStream_t stream
   if (rc != VT_OK) return rc;
   rc = to_device(d, &D, &outer2, &inner2);
   if (rc != VT_OK) return rc;
+  if (outer == outer2 && inner == inner2 && launch_copy_blocks(s, &d, S, D, nullptr, outer, inner, stream)) return check_launch("vt_scatter");
   const int vec = std::min(vector_width(s), vector_width(d));
   const uint32_t inner_vecs = (uint32_t)(inner / vec);
   dim3 grid((inner_vecs + 255) / 256, (unsigned)std::min<int64_t>(outer, 65535));
@@ -74,6 +171,7 @@ static int launch_materialize(const vt_desc& d, void* dst, hipStream_t stream) {
   int64_t outer, inner;
   int rc = to_device(d, &D, &outer, &inner);
   if (rc != VT_OK) return rc;
+  if (launch_copy_blocks(d, nullptr, D, D, dst, outer, inner, stream)) return check_launch("vt_materialize");
   int vec = vector_width(d);
   if ((uintptr_t)dst % 16) vec = 1;
   int esz = dtype_size(d.dtype);
@@ -116,6 +214,67 @@ __global__ void __launch_bounds__(256) k_add_rowsum(const DevDesc X, const DevDe
     vtd_eval(Y, 0, row * C + c, &oy, &py);
     float t = static_cast<const float*>(px)[ox] + static_cast<const float*>(py)[oy];
     p = p + t;
+  }
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) p = p + __shfl_xor(p, s, 64);
+  if (lane == 0) out[row] = p;
+}
+
+// The same sum, same order, with block-wise virtual tensor I/O (Sec. 4.2): where the maps keep
+// aligned blocks of 2^bx (x) and 2^by (y) columns contiguous, a lane applies a map once per block
+// (to the block's first element; 64 blocks per round, one per lane) and the element addresses of
+// each 64-column window follow from lane shuffles.  Lane l still owns the columns l, l + 64, ...
+// and adds them in ascending order, so the result has the bits of k_add_rowsum.
+struct BlockCursor {
+  uint64_t addr;      // this lane's block: address of its first element
+  uint32_t first;     // first block the 64 lanes hold
+};
+
+__device__ __forceinline__ void cursor_load(const DevDesc& X, uint32_t row, uint32_t C, uint32_t blog, uint32_t blk0, uint32_t lane,
+                                            BlockCursor& cur) {
+  const uint32_t nb = C >> blog;
+  const uint32_t b = min(blk0 + lane, nb - 1);
+  int64_t off;
+  const void* ptr;
+  vtd_eval(X, 0, row * C + (b << blog), &off, &ptr);
+  cur.addr = reinterpret_cast<uint64_t>(ptr) + (uint64_t)off * 4u;
+  cur.first = blk0;
+}
+
+__device__ __forceinline__ float cursor_read(const BlockCursor& cur, uint32_t col, uint32_t blog) {
+  const uint64_t a = shfl_u64(cur.addr, (int)((col >> blog) - cur.first));
+  return *reinterpret_cast<const float*>(a + (uint64_t)(col & ((1u << blog) - 1u)) * 4u);
+}
+
+__global__ void __launch_bounds__(256) k_add_rowsum_blocks(const DevDesc X, const DevDesc Y, float* __restrict__ out, uint32_t R,
+                                                           uint32_t C, uint32_t bx, uint32_t by) {
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t row = blockIdx.x * 4u + (threadIdx.x >> 6);
+  if (row >= R) return;
+  // columns after which the 64 cached blocks of an operand are used up
+  const uint32_t span_x = 64u << bx, span_y = 64u << by;
+  float p = 0.0f;
+  BlockCursor cx, cy;
+  for (uint32_t c0 = 0; c0 < C;) {
+    if (c0 % span_x == 0) cursor_load(X, row, C, bx, c0 >> bx, lane, cx);
+    if (c0 % span_y == 0) cursor_load(Y, row, C, by, c0 >> by, lane, cy);
+    const uint32_t end = min(C, min((c0 / span_x + 1) * span_x, (c0 / span_y + 1) * span_y));
+    // whole windows of 64 columns, eight at a time so that sixteen loads are in flight per lane
+    for (; c0 + 512 <= end; c0 += 512) {
+      float xv[8], yv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        xv[u] = cursor_read(cx, c0 + 64 * u + lane, bx);
+        yv[u] = cursor_read(cy, c0 + 64 * u + lane, by);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) p = p + (xv[u] + yv[u]);
+    }
+    for (; c0 < end; c0 += 64) {
+      const uint32_t col = min(c0 + lane, C - 1);     // every lane shuffles; lanes past the row add nothing
+      const float t = cursor_read(cx, col, bx) + cursor_read(cy, col, by);
+      if (c0 + lane < C) p = p + t;
+    }
   }
 #pragma unroll
   for (int s = 32; s >= 1; s >>= 1) p = p + __shfl_xor(p, s, 64);
@@ -338,7 +497,17 @@ int vt_elementwise(int kind, const vt_desc* x, const vt_desc* y, float eps, void
     if (rc != VT_OK) return rc;
     if (ox != 1 || oy != 1) return fail(VT_ERR_UNSUPPORTED, "vt_elementwise(add_rowsum): 2^31 elements or more");
     uint32_t R = (uint32_t)x->shape[0], C = (uint32_t)x->shape[1];
-    hipLaunchKernelGGL(k_add_rowsum, dim3((R + 3) / 4), dim3(256), 0, st, X, Y, (float*)out, R, C);
+    // block-wise path: both maps keep aligned blocks of at least 16 columns contiguous inside a row
+    auto block_log2 = [&](const vt_desc& d) {
+      int64_t b = block_elems(d, 1 << 20);
+      while (b > 1 && C % b) b >>= 1;
+      uint32_t l = 0;
+      while ((2ll << l) <= b) ++l;
+      return l;
+    };
+    const uint32_t bx = block_log2(*x), by = block_log2(*y);
+    if (bx >= 4 && by >= 4) hipLaunchKernelGGL(k_add_rowsum_blocks, dim3((R + 3) / 4), dim3(256), 0, st, X, Y, (float*)out, R, C, bx, by);
+    else hipLaunchKernelGGL(k_add_rowsum, dim3((R + 3) / 4), dim3(256), 0, st, X, Y, (float*)out, R, C);
     return check_launch("vt_elementwise(add_rowsum)");
   }
   if (kind == VT_EW_LAYERNORM) {

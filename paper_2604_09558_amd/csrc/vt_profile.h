@@ -51,6 +51,12 @@ static inline double vt_profile_ticks_per_us() {
   do {                                                                                               \
     if (threadIdx.x == 0) vt_prof_sh[(k)] = wall_clock64();                                          \
   } while (0)
+// the shader's own cycle counter at a point (against the wall clock it gives the clock the
+// compute unit actually ran at)
+#define VT_PROF_CYCLES(k)                                                                            \
+  do {                                                                                               \
+    if (threadIdx.x == 0) vt_prof_sh[(k)] = clock64();                                               \
+  } while (0)
 // a point inside a hot loop, taken the first time it is reached
 #define VT_PROF_ONCE(k)                                                                              \
   do {                                                                                               \
@@ -66,6 +72,7 @@ static inline double vt_profile_ticks_per_us() {
 #define VT_PROF_BEGIN() do { } while (0)
 #define VT_PROF(k) do { } while (0)
 #define VT_PROF_ONCE(k) do { } while (0)
+#define VT_PROF_CYCLES(k) do { } while (0)
 #define VT_PROF_FLUSH(name, wg) do { } while (0)
 #endif
 

@@ -329,11 +329,15 @@ class StrategyPipeline:
     tensors.  With `chosen` empty this is the fully materialized path, with every tensor chosen
     the fully virtual one."""
 
-    def __init__(self, dw: DeviceWorkload, chosen, **kw):
+    def __init__(self, dw: DeviceWorkload, chosen, statements=None, scatters=(), **kw):
+        """`statements` replaces the workload's chain (same tensor names; used by lean_plan, which
+        rewrites an append as a store).  `scatters`: (statement index, source tensor, statements
+        that define the destination view over physical tensors, its name): executed with
+        vt_scatter at that position, before the copies of later statements."""
         from . import vtog
         wl = dw.wl
         self.dw = dw
-        stmts = list(wl.chain)
+        stmts = list(statements if statements is not None else wl.chain)
         produced = {}
         for k, st in enumerate(stmts):
             for o in vtog.outputs_of(st):
@@ -372,6 +376,18 @@ class StrategyPipeline:
             for s in sources:
                 ensure(s)
             descs.append(self._build(chain, sources, name))
+        for index, src_name, dst_chain, dst_name in scatters:
+            chain, sources = vtog.read_chain(stmts, chosen, src_name)
+            for s in sources:
+                ensure(s)
+            src = self._build(chain, sources, src_name)
+            dst_sources = sorted({i for st in dst_chain for i in st[2] if i in self.bufs})
+            dst = self._build(list(dst_chain), dst_sources, dst_name)
+            n = 1
+            for e in src.shape:
+                n *= e
+            self.bytes_written += n * self.bufs[dst_sources[0]].element_size()
+            self.copies.append((index, src, dst))
         self.copies.sort(key=lambda c: c[0])
         self._set_operands(descs)
 
@@ -405,9 +421,66 @@ class StrategyPipeline:
         self.out = getattr(p, "out", None)
 
     def run(self, stream=None):
-        for _, d, buf in self.copies:
-            vt.vt_materialize(d, buf, stream=stream)
+        for _, d, target in self.copies:
+            if isinstance(target, vt.Desc):
+                vt.vt_scatter(d, target, stream=stream)
+            else:
+                vt.vt_materialize(d, target, stream=stream)
         return self.consumer.run(stream)
+
+
+VIEW_OPS = ("permute", "slice", "split", "unsqueeze", "expand")
+
+
+def lean_plan(wl):
+    """The chain as a stride-aware tensor framework executes it (the lean materialized comparison
+    path): permute, slice, split, unsqueeze and expand return views; a reshape returns a view when
+    the result is still one strided tensor and copies otherwise (after a permute or an expand);
+    concat and index_select copy; a concat that puts new rows behind a leading slice of a graph
+    input with room for them (a cache append) is executed in place: the new rows are stored into
+    the input and the result is a view of it.
+    Returns (statements, chosen, scatters) for StrategyPipeline: the tensors in `chosen` are views."""
+    from . import vtog
+    shapes = {k: tuple(v.shape) for k, v in wl.sources.items()}
+    stmts, chosen, scatters = [], {}, []
+    by_out = {}
+
+    def desc_of(name):
+        chain, sources = vtog.read_chain(stmts, chosen, name)
+        return vt.build_chain(chain, {s_: (shapes[s_], wl.dtype) for s_ in sources}, name, wl.index_tables)
+
+    for k, st in enumerate(wl.chain):
+        out, op, ins, p = st
+        if op == "concat" and len(ins) == 2 and ins[0] in by_out:
+            head = stmts[by_out[ins[0]]]
+            dim = p["dim"]
+            if (head[1] == "slice" and head[2][0] in wl.sources and head[3]["dim"] == dim and head[3]["start"] == 0
+                    and head[3].get("step", 1) == 1):
+                base, pos = head[2][0], head[3]["stop"]
+                ext = shapes[ins[1]][dim]
+                if pos + ext <= shapes[base][dim]:
+                    st = (out, "slice", (base,), {"dim": dim, "start": 0, "stop": pos + ext, "step": 1})
+                    slot = out + "__slot"
+                    scatters.append((k, ins[1], [(slot, "slice", (base,), {"dim": dim, "start": pos, "stop": pos + ext, "step": 1})], slot))
+                    op = "slice"
+        stmts.append(st)
+        by_out[out] = len(stmts) - 1
+        opp = vtog.Opportunity(out, tuple(i for i in st[2] if isinstance(i, str)), len(stmts) - 1, "read")
+        if op in VIEW_OPS:
+            chosen[out] = opp
+        elif op == "reshape":
+            chosen[out] = opp
+            if desc_of(out).as_strided() is None:
+                del chosen[out]
+        shapes[out] = desc_of(out).shape if out in chosen else vt.build_chain(
+            [st], {i: (shapes[i], wl.dtype) for i in st[2]}, out, wl.index_tables).shape
+    return stmts, chosen, scatters
+
+
+def make_lean_pipeline(dw: DeviceWorkload, **kw):
+    """The lean materialized path of a workload: views stay views, the rest is copied (lean_plan)."""
+    stmts, chosen, scatters = lean_plan(dw.wl)
+    return StrategyPipeline(dw, chosen, statements=stmts, scatters=scatters, **kw)
 
 
 def greedy_strategy(dw: DeviceWorkload, iters=10, warmup=2, **kw):

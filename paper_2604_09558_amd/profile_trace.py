@@ -32,6 +32,7 @@ SLOTS = 8
 MARKS = {
     "attn": ["start", "first K tile staged", "tile loop done", "partial results stored", "ticket taken",
              "merge written", "merge loads landed"],
+    "gemm": ["start", "first tiles in LDS", "K loop done", "tile stored"],
 }
 
 
@@ -100,13 +101,44 @@ def trace_attn(a):
         report("attn", read_marks(lib, "attn", n_wg))
 
 
+def trace_gemm(a):
+    """Config 3 (o-proj GEMM 8192 x 4096 x 4096): phases of every 256 x 256 tile."""
+    import torch
+    import workloads
+    import paper_2604_09558_amd as vt
+    from paper_2604_09558_amd import pipelines, torch_io as tio
+    lib = vt.lib()
+    ps = [pipelines.Gemm(tio.DeviceWorkload(workloads.c3_oproj_gemm(seed=s))) for s in range(2)]
+    n_wg = 512
+    for p in ps:
+        p.run()
+    torch.cuda.synchronize()
+    read_marks(lib, "gemm", n_wg)
+    for rep in range(a.reps):
+        ps[1].run()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ps[0].run()
+        e1.record()
+        torch.cuda.synchronize()
+        print("config 3, %d workgroups, launch %d: %.1f us between events" % (n_wg, rep, e0.elapsed_time(e1) * 1e3))
+        t, rate = read_marks(lib, "gemm", n_wg)
+        report("gemm", (t, rate))
+        us = (t[:, :4] - t[:, 0:1]) / rate
+        print("  per tile, median (max): load-in %.1f (%.1f), K loop %.1f (%.1f), store %.1f (%.1f) us" % (
+            np.median(us[:, 1]), us[:, 1].max(), np.median(us[:, 2] - us[:, 1]), (us[:, 2] - us[:, 1]).max(),
+            np.median(us[:, 3] - us[:, 2]), (us[:, 3] - us[:, 2]).max()))
+        ghz = (t[:, 5] - t[:, 4]) / ((t[:, 2] - t[:, 1]) / rate) / 1e3
+        print("  shader cycle counter over the K loop: %.3f GHz median (%.3f .. %.3f)" % (np.median(ghz), ghz.min(), ghz.max()))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("kernel", choices=sorted(MARKS))
     ap.add_argument("--n-splits", type=int, default=0)
     ap.add_argument("--reps", type=int, default=3)
     a = ap.parse_args()
-    {"attn": trace_attn}[a.kernel](a)
+    {"attn": trace_attn, "gemm": trace_gemm}[a.kernel](a)
 
 
 if __name__ == "__main__":

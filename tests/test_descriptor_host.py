@@ -116,6 +116,62 @@ def check_runs(d):
     assert info["run"] == min(runs)
 
 
+def check_blocks(d):
+    """Soundness and maximality of the block analysis by enumeration: every aligned group of
+    `block` consecutive elements (row-major over the whole virtual tensor) is one contiguous range
+    of one source, and twice that size is not (or does not divide the tensor)."""
+    shape = d.shape
+    n = int(np.prod(shape))
+    where = [d.eval_host(x) for x in itertools.product(*[range(e) for e in shape])]
+
+    def sound(c):
+        if n % c:
+            return False
+        for s in range(0, n, c):
+            src0, off0 = where[s]
+            if any(where[s + k] != (src0, off0 + k) for k in range(1, c)):
+                return False
+        return True
+
+    b = d.block()
+    assert b >= 1 and b & (b - 1) == 0 and sound(b), (b, d.dump())
+    return b, sound(2 * b)
+
+
+@pytest.mark.parametrize("seed", range(150))
+def test_block_analysis_is_sound_on_random_chains(seed):
+    wl = workloads.random_chain(seed, n_ops=5, max_extent=8)
+    try:
+        d = vt.build_chain(wl.chain, specs_of(wl), "R", wl.index_tables)
+    except vt.VtError:
+        pytest.skip("chain not representable")
+    check_blocks(d)
+
+
+def test_block_analysis_known_cases_and_mostly_maximal():
+    # config 1: the 16 + 5 column pieces of a 21-column row admit no block above one element
+    wl = workloads.c1_tiny_chain()
+    assert vt.build_chain(wl.chain, specs_of(wl), "V").block() == 1
+    # config 3 (small): 128 contiguous elements per (row, head); config 4 (small): 7 tokens of 128
+    wl = workloads.c3_oproj_gemm(B=2, H=4, S=8, D=128, N=8)
+    assert vt.build_chain(wl.chain, specs_of(wl), "A").block() == 128
+    # a concat along dim 0 of two dense tensors: blocks up to the gcd of the two parts
+    d = vt.build_chain([("c", "concat", ("a", "b"), {"dim": 0})], {"a": ((4, 8), "f32"), "b": ((12, 8), "f32")}, "c")
+    assert d.block() == 32 and d.block(16) == 16
+    # the cap is honoured, and the analysis is never unsound; count how often it is also maximal
+    maximal = total = 0
+    for seed in range(150):
+        wl = workloads.random_chain(seed, n_ops=4, max_extent=8)
+        try:
+            d = vt.build_chain(wl.chain, specs_of(wl), "R", wl.index_tables)
+        except vt.VtError:
+            continue
+        b, bigger_ok = check_blocks(d)
+        total += 1
+        maximal += not bigger_ok
+    assert total >= 100 and maximal >= 0.8 * total, (maximal, total)
+
+
 # ------------------------------------------------------------------ benchmark chains
 def test_c1_descriptor():
     wl = workloads.c1_tiny_chain()

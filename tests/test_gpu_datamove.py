@@ -193,3 +193,136 @@ def test_layernorm_virtual_rows(gpu, dtype, C):
     got = tio.to_host_f64(out)
     tol = {"f32": 2e-6, "f16": 2e-3, "bf16": 1.6e-2}[dtype]      # output rounding of values up to ~4
     assert np.max(np.abs(got - ref)) <= tol * max(1.0, np.max(np.abs(ref)))
+
+
+# ------------------------------------------------------------------ block-wise paths
+def guarded(torch, tio, shape, dtype, pad=4096):
+    """A device buffer with canary bytes before and after the tensor: (tensor view, check)."""
+    td = tio.TORCH_DTYPE[dtype]
+    esz = torch.empty(0, dtype=td).element_size()
+    n = int(np.prod(shape))
+    raw = torch.full((2 * pad + n * esz,), 0xA5, dtype=torch.uint8, device="cuda:0")
+    view = raw[pad:pad + n * esz].view(td).view(*shape)
+
+    def check():
+        host = raw.cpu().numpy()
+        assert (host[:pad] == 0xA5).all() and (host[pad + n * esz:] == 0xA5).all(), "write outside the destination"
+
+    return view, check
+
+
+BLOCK_CASES = [
+    # name, source shapes, chain, result: block sizes from 32 bytes to 1 KB, ragged block counts,
+    # fewer blocks than a wave takes per round, pieces and tables
+    ("heads_d16", {"X": (3, 5, 37, 16)}, [("p", "permute", ("X",), {"perm": (0, 2, 1, 3)}), ("R", "reshape", ("p",), {"shape": (111, 80)})]),
+    ("heads_d32", {"X": (2, 7, 50, 32)}, [("p", "permute", ("X",), {"perm": (0, 2, 1, 3)}), ("R", "reshape", ("p",), {"shape": (100, 224)})]),
+    ("heads_d128", {"X": (2, 6, 300, 128)}, [("p", "permute", ("X",), {"perm": (0, 2, 1, 3)}), ("R", "reshape", ("p",), {"shape": (600, 768)})]),
+    ("heads_d512", {"X": (2, 3, 41, 512)}, [("p", "permute", ("X",), {"perm": (0, 2, 1, 3)}), ("R", "reshape", ("p",), {"shape": (82, 1536)})]),
+    ("rows_2048", {"X": (97, 2048)}, [("R", "index_select", ("X",), {"dim": 0, "index": "t"})]),
+    ("concat_cols", {"X": (33, 64), "Y": (33, 192)}, [("R", "concat", ("X", "Y"), {"dim": 1})]),
+    ("concat_rows", {"X": (24, 40), "Y": (8, 40)}, [("R", "concat", ("X", "Y"), {"dim": 0})]),
+    ("expand_heads", {"X": (2, 3, 70, 64)}, [("u", "unsqueeze", ("X",), {"dim": 2}), ("e", "expand", ("u",), {"shape": (2, 3, 4, 70, 64)}),
+                                             ("R", "reshape", ("e",), {"shape": (2, 12, 70, 64)})]),
+    ("window", {"X": (2, 14, 14, 64)}, [("a", "reshape", ("X",), {"shape": (2, 2, 7, 2, 7, 64)}), ("b", "permute", ("a",), {"perm": (0, 1, 3, 2, 4, 5)}),
+                                        ("R", "reshape", ("b",), {"shape": (8, 49, 64)})]),
+    ("tiny", {"X": (2, 3, 16)}, [("R", "permute", ("X",), {"perm": (1, 0, 2)})]),
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("name,shapes,chain", BLOCK_CASES, ids=[c[0] for c in BLOCK_CASES])
+def test_materialize_block_paths_bit_exact_with_canaries(gpu, name, shapes, chain, dtype):
+    vt, tio, torch = gpu
+    rng = np.random.default_rng(11)
+    src = {k: workloads.encode(rng.normal(size=s).astype(np.float32), dtype) for k, s in shapes.items()}
+    tables = {"t": rng.integers(0, 97, size=150).astype(np.int32)}
+    wl = workloads.Workload(name, dtype, src, chain, {"kind": "materialize", "x": "R"}, tables)
+    dense = dm_ops.run_chain(chain, wl.sources, tables)["R"]
+    dw = tio.DeviceWorkload(wl)
+    d = dw.build("R")
+    assert d.block(512) * dense.dtype.itemsize >= 32, "case meant for the block path"
+    out, check = guarded(torch, tio, dense.shape, dtype)
+    vt.vt_materialize(d, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(tio.to_host_bits(out)), bits(dense)), d.dump()
+    check()
+
+
+def test_scatter_block_path_round_trip_with_canaries(gpu):
+    """Store direction on the block path: a dense tensor written through the permuted map, every
+    other byte of the target left alone, then read back through the same map."""
+    vt, tio, torch = gpu
+    rng = np.random.default_rng(12)
+    chain = [("s", "slice", ("T",), {"dim": 2, "start": 5, "stop": 35, "step": 1}),       # [4,6,30,64] of [4,6,40,64]
+             ("p", "permute", ("s",), {"perm": (0, 2, 1, 3)}), ("R", "reshape", ("p",), {"shape": (120, 384)})]
+    target0 = workloads.encode(rng.normal(size=(4, 6, 40, 64)).astype(np.float32), "bf16")
+    vals = workloads.encode(rng.normal(size=(120, 384)).astype(np.float32), "bf16")
+    want = dm_ops.store_through(chain, {"T": target0}, "R", vals)["T"]
+    tgt, check = guarded(torch, tio, target0.shape, "bf16")
+    tgt.copy_(tio.to_device(target0, "bf16"))
+    dv = tio.to_device(vals, "bf16")
+    src = vt.build_chain([], {"V": (vals.shape, "bf16", dv.data_ptr())}, "V")
+    dst = vt.build_chain(chain, {"T": (target0.shape, "bf16", tgt.data_ptr())}, "R")
+    assert dst.block(512) == 64
+    vt.vt_scatter(src, dst)
+    torch.cuda.synchronize()
+    assert np.array_equal(tio.to_host_bits(tgt), want)
+    check()
+    back, check2 = guarded(torch, tio, vals.shape, "bf16")
+    vt.vt_materialize(dst, back)
+    torch.cuda.synchronize()
+    assert np.array_equal(tio.to_host_bits(back), vals)
+    check2()
+
+
+ROWSUM_CASES = [
+    # rows, (A, B, C0) of X[A,B,C0] -> permute(1,0,2) -> reshape [B, A*C0], Y columns: blocks of C0 (X part),
+    # of gcd with the Y part, several cursor reloads per row (more than 64 blocks), ragged last window
+    (5, (3, 5, 16), 16),
+    (9, (70, 9, 16), 48),          # 70 blocks of 16 + 3: the block cursor is reloaded inside a row
+    (4, (2, 4, 1024), 512),        # blocks longer than a window of 64 columns
+    (6, (5, 6, 80), 16),           # 80 = 16 * 5: blocks of 16
+    (3, (40, 3, 128), 1024 + 64),  # the unrolled 512-column loop and its remainder
+]
+
+
+@pytest.mark.parametrize("rows,xs,ny", ROWSUM_CASES)
+def test_add_rowsum_block_path_bit_exact(gpu, rows, xs, ny):
+    vt, tio, torch = gpu
+    rng = np.random.default_rng(13)
+    A, B, C0 = xs
+    assert B == rows
+    C = A * C0 + ny
+    src = {"X": rng.normal(size=xs).astype(np.float32), "Y": rng.normal(size=(B, ny)).astype(np.float32),
+           "Z": rng.normal(size=(B, C)).astype(np.float32)}
+    chain = [("p", "permute", ("X",), {"perm": (1, 0, 2)}), ("r", "reshape", ("p",), {"shape": (B, A * C0)}),
+             ("V", "concat", ("r", "Y"), {"dim": 1})]
+    wl = workloads.Workload("rowsum_blocks", "f32", src, chain, {"kind": "add_rowsum", "x": "V", "y": "Z"})
+    ref = run_workload(wl)
+    dw = tio.DeviceWorkload(wl)
+    v, z = dw.build("V"), dw.build("Z")
+    assert v.block() >= 16
+    out, check = guarded(torch, tio, (B,), "f32")
+    vt.vt_elementwise(vt.EW_ADD_ROWSUM, v, z, 0.0, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(out.cpu().numpy()), bits(ref["out"]))
+    check()
+
+
+def test_add_rowsum_at_a_memory_bound_size_bit_exact(gpu):
+    """The elementwise consumer at the size the benchmark times it (335 MB read), against the
+    oracle's fixed-order sum, bit for bit, virtual and through the lean materialized path."""
+    vt, tio, torch = gpu
+    from paper_2604_09558_amd import pipelines
+    wl = workloads.rowsum_chain_large()
+    ref = run_workload(wl)["out"]
+    dw = tio.DeviceWorkload(wl)
+    p = pipelines.make_pipeline(dw)
+    assert p.x.block() == 128
+    p.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(p.out.cpu().numpy()), bits(ref))
+    lean = pipelines.make_lean_pipeline(dw)
+    lean.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(lean.consumer.out.cpu().numpy()), bits(ref))

@@ -23,5 +23,6 @@ from .inputs import (  # noqa: F401
     moe_combine,
     qkv_store_chain,
     random_chain,
+    rowsum_chain_large,
     CONFIGS,
 )

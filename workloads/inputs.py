@@ -113,6 +113,24 @@ def c1_tiny_chain(seed: int = 0, a: int = 4, b: int = 6, c: int = 8, lo: int = 4
                     {"kind": "add_rowsum", "x": "V", "y": "Z"})
 
 
+def rowsum_chain_large(seed: int = 0, A: int = 32, B: int = 8192, C0: int = 128, ny: int = 1024) -> Workload:
+    """Config 1's consumer at a memory-bound size, on a chain whose map keeps runs of C0 elements:
+    X[A,B,C0] -> permute(1,0,2) -> reshape[B, A*C0] -> concat along dim 1 with Y[B,ny] -> add Z ->
+    row-sum (fp32).  Defaults: 134 MB + 34 MB + 168 MB read per pass."""
+    C = A * C0 + ny
+    src = {
+        "X": _normal(seed, 0, (A, B, C0), 1.0, "f32"),
+        "Y": _normal(seed, 1, (B, ny), 1.0, "f32"),
+        "Z": _normal(seed, 2, (B, C), 1.0, "f32"),
+    }
+    chain = [
+        ("t1", "permute", ("X",), {"perm": (1, 0, 2)}),
+        ("t2", "reshape", ("t1",), {"shape": (B, A * C0)}),
+        ("V", "concat", ("t2", "Y"), {"dim": 1}),
+    ]
+    return Workload("rowsum_chain_large", "f32", src, chain, {"kind": "add_rowsum", "x": "V", "y": "Z"})
+
+
 # ----------------------------------------------------------------------------------------
 # C2: Llama-3-8B-shaped decode segment, bf16
 # ----------------------------------------------------------------------------------------
@@ -359,6 +377,7 @@ CONFIGS = {
     "c3": c3_oproj_gemm,
     "c4": c4_window_ln_linear,
     "c5": c5_moe_dispatch,
+    "rowsum_large": rowsum_chain_large,
     "qkv_store": qkv_proj_store,
     "paged": paged_decode_attention,
     "moe_combine": moe_combine,
