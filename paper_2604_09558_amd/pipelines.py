@@ -399,7 +399,7 @@ class StrategyPipeline:
     def _operand_names(self):
         c = self.dw.wl.consumer
         kind = c["kind"]
-        if kind == "add_rowsum":
+        if kind in ("add_rowsum", "weighted_sum"):
             return [c["x"], c["y"]]
         if kind == "decode_attn":
             return [c["q"], c["k"], c["v"]]
@@ -411,7 +411,7 @@ class StrategyPipeline:
 
     def _set_operands(self, descs):
         p = self.consumer
-        if isinstance(p, AddRowsum):
+        if isinstance(p, (AddRowsum, WeightedSum)):
             p.x, p.y = descs
         elif isinstance(p, DecodeAttention):
             p.q, p.k, p.v = descs
