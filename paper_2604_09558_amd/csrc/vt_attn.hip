@@ -838,7 +838,13 @@ static int plan_attention(const vt_desc* Q, const vt_desc* K, const vt_desc* V, 
       G = G == 0 ? f : std::gcd(G, f);
     }
   if (G < 1) G = 1;
-  while (G > 16 || Hq % G) --G;      // the matrix-core tile holds at most 16 heads
+  {
+    // the matrix-core tile holds at most 16 heads: the largest group size that divides the
+    // broadcast factor every piece shares (so that a group never straddles two stored heads)
+    int64_t g = std::min<int64_t>(G, 16);
+    while (G % g || Hq % g) --g;
+    G = g;
+  }
   memset(&P, 0, sizeof(P));
   AttnOperand ko, vo;
   int rc = plan_operand(*K, "K", G, &ko);

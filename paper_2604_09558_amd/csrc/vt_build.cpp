@@ -367,13 +367,51 @@ static Value op_index_select(vt_desc& d, const Value& in, int dim, int table) {
   const std::vector<int32_t>& t = d.tables[table].host;
   for (int32_t x : t)
     if (x < 0 || x >= in.shape[dim]) raise(VT_ERR_RANGE, "index_select: index outside the dim");
+  const int64_t n = (int64_t)t.size();
   Value out = in;
-  out.shape[dim] = (int64_t)t.size();
-  for (Piece& p : out.pieces) {
-    if (p.lo[dim] != 0 || p.hi[dim] != in.shape[dim])
-      raise(VT_ERR_UNSUPPORTED, "index_select along a concatenated dim");
-    view_index_select(d, p.v, dim, table, (int64_t)t.size());
-    p.hi[dim] = (int64_t)t.size();
+  out.shape[dim] = n;
+  bool cut = false;
+  for (const Piece& p : in.pieces) cut = cut || p.lo[dim] != 0 || p.hi[dim] != in.shape[dim];
+  if (!cut) {
+    for (Piece& p : out.pieces) {
+      view_index_select(d, p.v, dim, table, n);
+      p.hi[dim] = n;
+    }
+    return out;
+  }
+  // The dim is cut into pieces (a Concat below): a table entry decides which piece an output
+  // index reads.  The pieces are boxes, so between two neighbouring cut points every piece spans
+  // the whole slab; consecutive output indices whose entries fall into one slab form a run, and
+  // each run becomes its own set of pieces [j0, j1) that read entries j0.. of the same table.  The
+  // entries stay global: entry * stride - lo * stride, the second term goes into the base.
+  std::vector<int64_t> cuts;
+  for (const Piece& p : in.pieces) {
+    cuts.push_back(p.lo[dim]);
+    cuts.push_back(p.hi[dim]);
+  }
+  std::sort(cuts.begin(), cuts.end());
+  cuts.erase(std::unique(cuts.begin(), cuts.end()), cuts.end());
+  auto slab_of = [&](int64_t x) { return (int)(std::upper_bound(cuts.begin(), cuts.end(), x) - cuts.begin()) - 1; };
+  out.pieces.clear();
+  for (int64_t j0 = 0; j0 < n;) {
+    const int slab = slab_of(t[j0]);
+    int64_t j1 = j0 + 1;
+    while (j1 < n && slab_of(t[j1]) == slab) ++j1;
+    for (const Piece& p0 : in.pieces) {
+      if (!(p0.lo[dim] <= cuts[slab] && cuts[slab + 1] <= p0.hi[dim])) continue;
+      Piece p = p0;
+      view_index_select(d, p.v, dim, table, j1 - j0);
+      auto& g = p.v.groups[dim];
+      if (!g.empty() && g[0].table >= 0) {
+        g[0].table_off = j0;
+        p.v.base -= p0.lo[dim] * g[0].stride;
+      }
+      p.lo[dim] = j0;
+      p.hi[dim] = j1;
+      out.pieces.push_back(p);
+      if ((int)out.pieces.size() > kMaxPieces) raise(VT_ERR_UNSUPPORTED, "index_select over a concatenated dim needs more than 16 pieces");
+    }
+    j0 = j1;
   }
   return out;
 }
@@ -412,36 +450,136 @@ static Value op_reshape(const vt_desc& d, const Value& in, const vt_op& op) {
     } while (po != pn);
     chunks.push_back(c);
   }
+  // A piece that a Concat made narrower than the tensor inside a chunk is, in the chunk's linear
+  // index, a set of intervals: one per choice of the indices of the old dims outside the innermost
+  // narrowed one.  Over the new dims an interval is a few boxes (the rest of a row, whole rows, the
+  // start of a row, recursively per new dim).  Each box becomes a piece of the result whose view
+  // is the old piece's view, cut down to the interval (slices of the old dims, then of the
+  // chunk's dims merged into one) and regrouped.
+  struct Part {
+    std::vector<int64_t> lo, hi;                       // over c.n
+    std::vector<std::pair<int, int64_t>> fix;          // old dims held at one local index
+    int64_t merged_len = 1, start = 0, len = -1;       // slice of the merged dim (len < 0: none)
+  };
   for (const Piece& p0 : in.pieces) {
-    Piece p = p0;
-    std::vector<int64_t> lo(ns.size(), 0), hi(ns.size(), 1), local(ns.size(), 1);
+    std::vector<std::vector<Part>> options;      // per chunk
     for (const Chunk& c : chunks) {
-      bool all_full = true;
-      for (int o : c.o) all_full = all_full && p0.lo[o] == 0 && p0.hi[o] == in.shape[o];
-      if (all_full) {
+      std::vector<Part> parts;
+      const size_t ko = c.o.size(), m = c.n.size();
+      int q = -1;                                      // innermost narrowed old dim of the chunk
+      for (size_t k = 0; k < ko; ++k)
+        if (p0.lo[c.o[k]] != 0 || p0.hi[c.o[k]] != in.shape[c.o[k]]) q = (int)k;
+      if (q < 0) {
+        Part pt;
         for (int n : c.n) {
-          hi[n] = ns[n];
-          local[n] = ns[n];
+          pt.lo.push_back(0);
+          pt.hi.push_back(ns[n]);
+          pt.merged_len *= ns[n];
         }
+        parts.push_back(pt);
+        options.push_back(parts);
         continue;
       }
-      bool rest_full = true;
-      for (size_t k = 1; k < c.o.size(); ++k) rest_full = rest_full && p0.lo[c.o[k]] == 0 && p0.hi[c.o[k]] == in.shape[c.o[k]];
-      if (c.n.size() == 1 && rest_full) {
-        int64_t inner = 1;
-        for (size_t k = 1; k < c.o.size(); ++k) inner *= in.shape[c.o[k]];
-        int n = c.n[0];
-        lo[n] = p0.lo[c.o[0]] * inner;
-        hi[n] = p0.hi[c.o[0]] * inner;
-        local[n] = hi[n] - lo[n];
-        continue;
+      std::vector<int64_t> so(ko + 1, 1), inner(m + 1, 1);      // suffix products: old dims, new dims
+      for (size_t k = ko; k-- > 0;) so[k] = so[k + 1] * in.shape[c.o[k]];
+      for (size_t k = m; k-- > 0;) inner[k] = inner[k + 1] * ns[c.n[k]];
+      std::vector<int64_t> x(q, 0);
+      for (int k = 0; k < q; ++k) x[k] = p0.lo[c.o[k]];
+      while (true) {
+        int64_t a = p0.lo[c.o[q]] * so[q + 1];
+        for (int k = 0; k < q; ++k) a += x[k] * so[k + 1];
+        const int64_t b = a + (p0.hi[c.o[q]] - p0.lo[c.o[q]]) * so[q + 1];
+        struct Job {
+          int64_t u, v;      // interval of the chunk's linear index
+          size_t level;      // new dims before `level` are fixed by u
+        };
+        std::vector<Job> todo{{a, b, 0}};
+        while (!todo.empty()) {
+          const Job jb = todo.back();
+          todo.pop_back();
+          if (jb.u >= jb.v) continue;
+          const int64_t in1 = inner[jb.level + 1];     // elements per index of new dim `level`
+          const int64_t base = jb.u / inner[jb.level] * inner[jb.level];
+          const int64_t u = jb.u - base, v = jb.v - base;
+          if (jb.level + 1 == m || (u % in1 == 0 && v % in1 == 0)) {
+            Part pt;
+            int64_t rem = base;
+            for (size_t k = 0; k < m; ++k) {
+              if (k < jb.level) {
+                const int64_t xi = rem / inner[k + 1];
+                rem -= xi * inner[k + 1];
+                pt.lo.push_back(xi);
+                pt.hi.push_back(xi + 1);
+              } else if (k == jb.level) {
+                pt.lo.push_back(u / in1);
+                pt.hi.push_back(v / in1);
+              } else {
+                pt.lo.push_back(0);
+                pt.hi.push_back(ns[c.n[k]]);
+              }
+            }
+            for (int k = 0; k < q; ++k) pt.fix.push_back({c.o[k], x[k] - p0.lo[c.o[k]]});
+            pt.merged_len = b - a;
+            pt.start = jb.u - a;
+            pt.len = jb.v - jb.u;
+            parts.push_back(pt);
+            if (parts.size() > (size_t)kMaxPieces) raise(VT_ERR_UNSUPPORTED, "reshape across a concat cut needs more than 16 pieces");
+            continue;
+          }
+          const int64_t first = u / in1, last = (v - 1) / in1;
+          if (first == last) {
+            todo.push_back({jb.u, jb.v, jb.level + 1});
+            continue;
+          }
+          const int64_t head_end = u % in1 ? (first + 1) * in1 : u, tail_begin = v % in1 ? last * in1 : v;
+          if (u < head_end) todo.push_back({base + u, base + head_end, jb.level + 1});
+          if (head_end < tail_begin) todo.push_back({base + head_end, base + tail_begin, jb.level});
+          if (tail_begin < v) todo.push_back({base + tail_begin, base + v, jb.level + 1});
+        }
+        int k = q - 1;
+        while (k >= 0 && ++x[k] == p0.hi[c.o[k]]) {
+          x[k] = p0.lo[c.o[k]];
+          --k;
+        }
+        if (k < 0) break;
       }
-      raise(VT_ERR_UNSUPPORTED, "reshape regroups a dim that a concat cut into pieces");
+      options.push_back(parts);
     }
-    view_reshape(d, p.v, local);
-    p.lo = lo;
-    p.hi = hi;
-    out.pieces.push_back(p);
+    // every combination of one part per chunk is a piece of the result
+    std::vector<size_t> pick(chunks.size(), 0);
+    while (true) {
+      Piece p = p0;
+      std::vector<int64_t> lo(ns.size(), 0), hi(ns.size(), 1), local(ns.size(), 1), merged;
+      bool cut = false;
+      for (size_t ci = 0; ci < chunks.size(); ++ci) {
+        const Chunk& c = chunks[ci];
+        const Part& pt = options[ci][pick[ci]];
+        for (size_t k = 0; k < c.n.size(); ++k) {
+          lo[c.n[k]] = pt.lo[k];
+          hi[c.n[k]] = pt.hi[k];
+          local[c.n[k]] = pt.hi[k] - pt.lo[k];
+        }
+        for (const auto& f : pt.fix) view_slice(d, p.v, f.first, f.second, 1, 1);
+        merged.push_back(pt.merged_len);
+        cut = cut || (pt.len >= 0 && pt.len != pt.merged_len);
+      }
+      if (cut) {
+        if (merged.empty()) merged.push_back(1);
+        view_reshape(d, p.v, merged);
+        for (size_t ci = 0; ci < chunks.size(); ++ci) {
+          const Part& pt = options[ci][pick[ci]];
+          if (pt.len >= 0 && pt.len != pt.merged_len) view_slice(d, p.v, (int)ci, pt.start, pt.len, 1);
+        }
+      }
+      view_reshape(d, p.v, local);
+      p.lo = lo;
+      p.hi = hi;
+      out.pieces.push_back(p);
+      if ((int)out.pieces.size() > kMaxPieces) raise(VT_ERR_UNSUPPORTED, "reshape across a concat cut needs more than 16 pieces");
+      size_t ci = 0;
+      while (ci < chunks.size() && ++pick[ci] == options[ci].size()) pick[ci++] = 0;
+      if (ci == chunks.size()) break;
+    }
   }
   return out;
 }

@@ -246,6 +246,17 @@ __device__ __forceinline__ float cursor_read(const BlockCursor& cur, uint32_t co
   return *reinterpret_cast<const float*>(a + (uint64_t)(col & ((1u << blog) - 1u)) * 4u);
 }
 
+// The same for a window of 64 columns starting at the wave-uniform column c0 when blocks hold at
+// least 64 columns: the whole window lies in one block, whose address is read from the owning
+// lane into scalar registers; a lane adds its own column.
+__device__ __forceinline__ float cursor_read_window(const BlockCursor& cur, uint32_t c0, uint32_t lane, uint32_t blog) {
+  const int owner = (int)((c0 >> blog) - cur.first);
+  const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)cur.addr, owner), hi = __builtin_amdgcn_readlane((uint32_t)(cur.addr >> 32), owner);
+  const float* base = reinterpret_cast<const float*>(((uint64_t)hi << 32) | lo);
+  return base[(c0 & ((1u << blog) - 1u)) + lane];
+}
+
+template <bool WIDE>   // WIDE: both operands keep blocks of at least 64 columns
 __global__ void __launch_bounds__(256) k_add_rowsum_blocks(const DevDesc X, const DevDesc Y, float* __restrict__ out, uint32_t R,
                                                            uint32_t C, uint32_t bx, uint32_t by) {
   const uint32_t lane = threadIdx.x & 63u;
@@ -264,8 +275,8 @@ __global__ void __launch_bounds__(256) k_add_rowsum_blocks(const DevDesc X, cons
       float xv[8], yv[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        xv[u] = cursor_read(cx, c0 + 64 * u + lane, bx);
-        yv[u] = cursor_read(cy, c0 + 64 * u + lane, by);
+        xv[u] = WIDE ? cursor_read_window(cx, c0 + 64 * u, lane, bx) : cursor_read(cx, c0 + 64 * u + lane, bx);
+        yv[u] = WIDE ? cursor_read_window(cy, c0 + 64 * u, lane, by) : cursor_read(cy, c0 + 64 * u + lane, by);
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) p = p + (xv[u] + yv[u]);
@@ -506,7 +517,8 @@ int vt_elementwise(int kind, const vt_desc* x, const vt_desc* y, float eps, void
       return l;
     };
     const uint32_t bx = block_log2(*x), by = block_log2(*y);
-    if (bx >= 4 && by >= 4) hipLaunchKernelGGL(k_add_rowsum_blocks, dim3((R + 3) / 4), dim3(256), 0, st, X, Y, (float*)out, R, C, bx, by);
+    if (bx >= 6 && by >= 6) hipLaunchKernelGGL(k_add_rowsum_blocks<true>, dim3((R + 3) / 4), dim3(256), 0, st, X, Y, (float*)out, R, C, bx, by);
+    else if (bx >= 4 && by >= 4) hipLaunchKernelGGL(k_add_rowsum_blocks<false>, dim3((R + 3) / 4), dim3(256), 0, st, X, Y, (float*)out, R, C, bx, by);
     else hipLaunchKernelGGL(k_add_rowsum, dim3((R + 3) / 4), dim3(256), 0, st, X, Y, (float*)out, R, C);
     return check_launch("vt_elementwise(add_rowsum)");
   }

@@ -70,7 +70,7 @@ def test_most_random_chains_are_supported():
             ok += 1
         except vt.VtError as e:
             assert e.code == vt.ERR_UNSUPPORTED
-    assert ok >= 110, ok
+    assert ok >= 140, ok
 
 
 def local_linear(local, shape):
@@ -342,6 +342,59 @@ def test_benchmark_chains_classes():
     assert vt.build_chain(c4.chain, specs_of(c4), c4.consumer["x"]).classify() == (vt.ACCESS_PARTIAL, 7 * 128 * 2)
 
 
+def dense_case(sources, chain, tables=None, result="R"):
+    src = {k: np.arange(100 * i, 100 * i + int(np.prod(shp)), dtype=np.float32).reshape(shp) for i, (k, shp) in enumerate(sources.items())}
+    wl = workloads.Workload("case", "f32", src, chain, {"kind": "materialize", "x": result}, tables or {})
+    dense = dm_ops.run_chain(chain, wl.sources, wl.index_tables)[result]
+    d = vt.build_chain(chain, specs_of(wl), result, wl.index_tables)
+    check_desc_against_dense(d, dense, wl)
+    check_runs(d)
+    check_blocks(d)
+    return d
+
+
+def test_index_select_along_a_concatenated_dim():
+    """Sec. 4.1 puts no restriction on composition: a gather whose table crosses the parts of a
+    Concat is split into runs of entries that stay in one part."""
+    cat = [("c", "concat", ("X", "Y"), {"dim": 1})]
+    # entries 0..5 name X's columns, 6..10 Y's
+    for table, pieces in (([0, 1, 7, 8, 9, 3], 3), ([10, 9, 8, 7, 6], 1), ([5, 6, 5, 6], 4), ([2], 1), ([0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10], 2)):
+        d = dense_case({"X": (4, 6), "Y": (4, 5)}, cat + [("R", "index_select", ("c",), {"dim": 1, "index": "t"})], {"t": np.array(table, np.int32)})
+        assert d.info()["n_pieces"] == pieces, (table, d.dump())
+    # the gathered dim was cut, another dim is cut as well; operators follow
+    chain = [("a", "concat", ("X", "Y"), {"dim": 1}), ("b", "concat", ("a", "Z"), {"dim": 0}),
+             ("g", "index_select", ("b",), {"dim": 0, "index": "t"}), ("p", "permute", ("g",), {"perm": (1, 0)}),
+             ("R", "slice", ("p",), {"dim": 0, "start": 2, "stop": 9, "step": 1})]
+    dense_case({"X": (4, 6), "Y": (4, 5), "Z": (2, 11)}, chain, {"t": np.array([5, 0, 1, 4, 2], np.int32)})
+    # a part of extent 1 along the gathered dim, and a gather of a gather
+    chain = [("c", "concat", ("X", "Y"), {"dim": 0}), ("g", "index_select", ("c",), {"dim": 0, "index": "t"}),
+             ("R", "index_select", ("g",), {"dim": 0, "index": "u"})]
+    dense_case({"X": (1, 3), "Y": (3, 3)}, chain, {"t": np.array([0, 0, 2, 3, 1], np.int32), "u": np.array([4, 0, 2, 2], np.int32)})
+
+
+def test_reshape_across_a_concat_cut():
+    """A Reshape that regroups a dim which a Concat cut: each part of the old dim is an interval of
+    the row-major order and becomes a few boxes of the new shape."""
+    cat0 = [("c", "concat", ("X", "Y"), {"dim": 0})]
+    for shape, pieces in (((2, 6), 3), ((6, 2), 2), ((4, 3), 4), ((12,), 2), ((2, 2, 3), 4), ((3, 2, 2), 2), ((1, 12, 1), 2)):
+        d = dense_case({"X": (2, 4), "Y": (1, 4)}, cat0 + [("R", "reshape", ("c",), {"shape": shape})])
+        assert d.info()["n_pieces"] == pieces, (shape, d.dump())
+    # the cut dim is an inner one: one interval per outer index
+    cat1 = [("c", "concat", ("X", "Y"), {"dim": 1})]
+    d = dense_case({"X": (3, 4), "Y": (3, 2)}, cat1 + [("R", "reshape", ("c",), {"shape": (18,)})])
+    assert d.info()["n_pieces"] == 6
+    dense_case({"X": (2, 4), "Y": (2, 2)}, cat1 + [("R", "reshape", ("c",), {"shape": (3, 4)})])
+    dense_case({"X": (2, 3, 4), "Y": (2, 3, 2)}, [("c", "concat", ("X", "Y"), {"dim": 2}), ("R", "reshape", ("c",), {"shape": (2, 18)})])
+    # views under the concat, operators after the reshape
+    chain = [("xp", "permute", ("X",), {"perm": (1, 0)}), ("c", "concat", ("xp", "Y"), {"dim": 0}), ("r", "reshape", ("c",), {"shape": (4, 5)}),
+             ("s", "slice", ("r",), {"dim": 1, "start": 1, "stop": 4, "step": 1}), ("R", "permute", ("s",), {"perm": (1, 0)})]
+    dense_case({"X": (2, 6), "Y": (4, 2)}, chain)
+    # too many intervals for the descriptor
+    with pytest.raises(vt.VtError) as ei:
+        dense_case({"X": (40, 4), "Y": (40, 2)}, cat1 + [("R", "reshape", ("c",), {"shape": (240,)})])
+    assert ei.value.code == vt.ERR_UNSUPPORTED
+
+
 def test_stacked_stage_case():
     # a reshape that straddles a slice boundary needs a second stage
     chain = [("a", "slice", ("X",), {"dim": 1, "start": 0, "stop": 3, "step": 1}),
@@ -374,8 +427,8 @@ def test_error_paths():
     assert code([("a", "expand", ("X",), {"shape": (4, 12)})], "a") == vt.ERR_SHAPE
     t = {"i": np.array([0, 7], np.int32)}
     assert code([("a", "index_select", ("X",), {"dim": 0, "index": "i"})], "a", t) == vt.ERR_RANGE
-    # index_select along a concatenated dim is outside the representation
-    t = {"i": np.array([0, 7], np.int32)}
+    # a table that hops between the parts of a concatenated dim more often than the descriptor has pieces
+    t = {"i": np.array([0, 7] * 9, np.int32)}
     chain = [("c", "concat", ("X", "Y"), {"dim": 1}), ("a", "index_select", ("c",), {"dim": 1, "index": "i"})]
     assert code(chain, "a", t) == vt.ERR_UNSUPPORTED
     # NULL arguments
@@ -438,6 +491,15 @@ def test_attention_plan_of_the_decode_chain():
     assert vt.vt_decode_attn_plan(*attn_descs(wl), n_splits=3)["splits"] == 3
     small = workloads.c2_decode_attention(seed=0, B=1, Hkv=1, G=16, S=70, D=128)
     assert vt.vt_decode_attn_plan(*attn_descs(small)) == {"group_size": 16, "n_segments": 2, "splits": 1, "paged_segments": 0}
+
+
+def test_attention_group_size_divides_the_broadcast_factor():
+    """18 query heads per kv head: more than one matrix tile holds (16), so the group must be a
+    divisor of 18 (9), not merely a divisor of the 36 query heads (12 would straddle two kv heads)."""
+    wl = workloads.c2_decode_attention(seed=0, B=1, Hkv=2, G=18, S=40, D=128)
+    assert vt.vt_decode_attn_plan(*attn_descs(wl))["group_size"] == 9
+    wl = workloads.c2_decode_attention(seed=0, B=1, Hkv=3, G=17, S=40, D=128)      # a prime above 16: one head per read
+    assert vt.vt_decode_attn_plan(*attn_descs(wl))["group_size"] == 1
 
 
 def test_attention_plan_recognises_page_tables():

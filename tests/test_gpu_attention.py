@@ -37,6 +37,7 @@ CASES = [
     (1, 1, 16, 95, "f16", 1),
     (1, 1, 32, 64, "bf16", 0),      # more sharing heads than one matrix tile holds
     (3, 2, 2, 777, "bf16", 7),
+    (1, 2, 18, 100, "bf16", 0),     # 18 sharing heads: groups of 9, two groups per kv head
 ]
 
 
