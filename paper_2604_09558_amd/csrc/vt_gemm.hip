@@ -17,6 +17,8 @@
 //   B ([K,N], N contiguous, the usual row-major weight): rows go to LDS as they are loaded
 //     ([k][n], 16 bytes per lane); the transposition into the operand layout (8 consecutive k
 //     per lane) is done by the LDS itself on the way out (ds_read_b64_tr_b16, two per fragment).
+//   B ([K,N] with K contiguous: an [N,K] weight seen through a Permute, the B_KMAJOR
+//     instantiation): treated like A, chunks of 8 k of one column n -> LDS [n][k], swizzled.
 // Workgroup ids are remapped so that each XCD (own L2) works on a contiguous band of tiles,
 // walked in groups of 8 tile rows, which keeps the A and B panels of neighbouring tiles in
 // that L2.  A launch covers up to 8 groups (grouped GEMM: one tile list over all groups).
@@ -25,6 +27,7 @@
 #include <algorithm>
 #include <cstring>
 #include <type_traits>
+#include <vector>
 
 #include "vt_gemm_common.h"
 #include "vt_profile.h"
@@ -52,6 +55,7 @@ struct GemmGroup {
   AxisMap<3> a_col, b_row, b_col;
   int32_t M, tile_begin, tiles_m;
   int32_t k64;   // a K step of 64 never leaves the innermost K digit of A or of B: the step's offset is uniform
+  int32_t b_kmajor;   // B's contiguous axis is K (all groups of a launch agree)
 };
 
 struct GemmParams {
@@ -71,7 +75,7 @@ struct OutMap {
   int32_t n, pad;
 };
 
-template <typename T, bool C_F32, bool K_TAIL, bool MAPPED>
+template <typename T, bool C_F32, bool K_TAIL, bool MAPPED, bool B_KMAJOR = false>
 __global__ void __launch_bounds__(256) k_gemm(const GemmParams P, const OutMap O) {
   typedef Mma<T> M_;
   typedef typename M_::vec opvec;
@@ -126,6 +130,12 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P, const OutMap O
   const int b_n = tn * BN + b_cn * 8;
   const char* b_colptr = G.b + axis_off(G.b_col, (uint32_t)min(b_n, N - 8)) * 2;
   const int64_t b_kstride = G.b_row.stride[2] * 2;
+  // B_KMAJOR: the thread's 8 columns n = a_r0 + 32 i (as for A's rows), chunk a_c of 8 k
+  int64_t bk_coloff[8];
+  if (B_KMAJOR) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) bk_coloff[i] = axis_off(G.b_col, (uint32_t)min(tn * BN + a_r0 + 32 * i, N - 1)) * 2;
+  }
 
   // ---- the pieces of one K step, each small enough to be placed between two MFMAs ----------
   uint4 ra[8], rb[8];
@@ -144,7 +154,7 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P, const OutMap O
     __syncthreads();
   }
   const uint32_t a_lane = (uint32_t)(a_c * 16);
-  const char* b_lane = b_colptr + (int64_t)(b_kb * 8) * b_kstride;
+  const char* b_lane = B_KMAJOR ? G.b + a_c * 16 : b_colptr + (int64_t)(b_kb * 8) * b_kstride;
   uint32_t t_a = 0;              // table entries of the step about to be fetched, read well ahead of their use
   int64_t t_b = 0;
   auto gload_lookup = [&](int k0) {
@@ -159,13 +169,16 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P, const OutMap O
       g_aco = t_a + a_lane;
       g_bp = b_lane + t_b;
     } else {
-      const int ka = k0 + a_c * 8, kb = k0 + b_kb * 8;
+      const int ka = k0 + a_c * 8, kb = B_KMAJOR ? ka : k0 + b_kb * 8;
       g_aco = (uint32_t)(axis_off(G.a_col, (uint32_t)(K_TAIL ? min(ka, K - 8) : ka)) * 2);
-      g_bp = b_colptr + axis_off(G.b_row, (uint32_t)(K_TAIL ? min(kb, K - 8) : kb)) * 2;
+      g_bp = (B_KMAJOR ? G.b : b_colptr) + axis_off(G.b_row, (uint32_t)(K_TAIL ? min(kb, K - 8) : kb)) * 2;
     }
   };
   auto gload_a = [&](int i) { ra[i] = *reinterpret_cast<const uint4*>(G.a + (a_rowoff[i] + g_aco)); };
-  auto gload_b = [&](int j) { rb[j] = *reinterpret_cast<const uint4*>(g_bp + j * b_kstride); };
+  auto gload_b = [&](int j) {
+    if (B_KMAJOR) rb[j] = *reinterpret_cast<const uint4*>(g_bp + bk_coloff[j]);
+    else rb[j] = *reinterpret_cast<const uint4*>(g_bp + j * b_kstride);
+  };
   auto store_a = [&](int buf, int i, int k0) {
     const int r = a_r0 + 32 * i;
     uint4 v = ra[i];
@@ -176,6 +189,13 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P, const OutMap O
   // the transposition the matrix core needs happens in the LDS read (ds_read_b64_tr_b16)
   auto store_b = [&](int buf, int j, int k0) {
     uint4 v = rb[j];
+    if (B_KMAJOR) {
+      // [n][8 chunks of 8 k], swizzled like A's tile
+      const int r = a_r0 + 32 * j;
+      if (K_TAIL && k0 + a_c * 8 >= K) v = make_uint4(0, 0, 0, 0);
+      reinterpret_cast<uint4*>(&ldsB[buf][0])[r * 8 + (a_c ^ (r & 7))] = v;
+      return;
+    }
     if (K_TAIL && k0 + b_kb * 8 >= K) v = make_uint4(0, 0, 0, 0);
     *reinterpret_cast<uint4*>(&ldsB[buf][(b_kb * 8 + j) * kBPitch + b_cn * 16]) = v;
   };
@@ -208,6 +228,10 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P, const OutMap O
     if (f == 0 || f >= 5) {
       const int mb = f == 0 ? 0 : f - 4;
       af[p][mb] = __builtin_bit_cast(opvec, ldsA[buf][a_unit[mb] + (chunk ^ a_key[mb])]);
+    } else if (B_KMAJOR) {
+      const int nb = f - 1;
+      const int r = wn * 128 + nb * 32 + l32;
+      bf[p][nb] = __builtin_bit_cast(opvec, reinterpret_cast<const uint4*>(&ldsB[buf][0])[r * 8 + (chunk ^ (r & 7))]);
     } else {
       const int nb = f - 1;
       typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -369,15 +393,27 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P, const OutMap O
 #endif
 }
 
-int plan_a(const vt_desc& d, GemmGroup* g, int64_t* M, int64_t* K) {
+// Piece `pi` of A as one operand of its own: a Concat along the rows makes A a stack of pieces,
+// each of which is a range of rows [*row_begin, *row_begin + *M) of the product.
+int plan_a(const vt_desc& d, GemmGroup* g, int64_t* M, int64_t* K, size_t pi = 0, int64_t* row_begin = nullptr) {
   int n = (int)d.shape.size();
   if (n < 2) return fail(VT_ERR_SHAPE, "vt_gemm: A must have at least 2 dims");
-  if (d.pieces.size() != 1 || !d.pieces[0].v.lower.empty())
-    return fail(VT_ERR_UNSUPPORTED, "vt_gemm: A must be a single piece with one index stage");
-  const Piece& p = d.pieces[0];
+  if (pi >= d.pieces.size() || !d.pieces[pi].v.lower.empty())
+    return fail(VT_ERR_UNSUPPORTED, "vt_gemm: A must have one index stage");
+  const Piece& p = d.pieces[pi];
   *K = d.shape[n - 1];
   *M = 1;
-  for (int i = 0; i < n - 1; ++i) *M *= d.shape[i];
+  int64_t inner_rows = 1;
+  for (int i = n - 2; i >= 0; --i) {
+    *M *= p.hi[i] - p.lo[i];
+    if (i > 0) {
+      if (p.lo[i] != 0 || p.hi[i] != d.shape[i]) return fail(VT_ERR_UNSUPPORTED, "vt_gemm: the pieces of A must be ranges of rows (a Concat along the outermost dim)");
+      inner_rows *= d.shape[i];
+    }
+  }
+  if (p.lo[n - 1] != 0 || p.hi[n - 1] != d.shape[n - 1]) return fail(VT_ERR_UNSUPPORTED, "vt_gemm: A is cut into pieces along K");
+  if (row_begin) *row_begin = p.lo[0] * inner_rows;
+  else if (d.pieces.size() != 1) return fail(VT_ERR_UNSUPPORTED, "vt_gemm: A must be a single piece here");
   int rc = make_axis(d, p, 0, n - 1, &g->a_row, "vt_gemm: A rows", true);
   if (rc != VT_OK) return rc;
   rc = make_axis(d, p, n - 1, n, &g->a_col, "vt_gemm: A columns");
@@ -418,11 +454,20 @@ int plan_b(const vt_desc& d, GemmGroup* g, int64_t* K, int64_t* N) {
   if (!src.ptr) return fail(VT_ERR_INVALID_ARG, "vt_gemm: B source without a device pointer");
   g->b = static_cast<const char*>(src.ptr) + p.v.base * 2;
   const AxisMap<3>& c = g->b_col;
-  bool ok = *N % 8 == 0 && *K % 8 == 0 && g->b_row.radix[2].d % 8 == 0 && (uintptr_t)g->b % 16 == 0 &&
-            strides_multiple_of(g->b_row, 8, 0) && c.nd >= 1 &&
+  const AxisMap<3>& r = g->b_row;
+  g->b_kmajor = 0;
+  bool ok = *N % 8 == 0 && *K % 8 == 0 && r.radix[2].d % 8 == 0 && (uintptr_t)g->b % 16 == 0 &&
+            strides_multiple_of(r, 8, 0) && c.nd >= 1 &&
             c.stride[2] == 1 && c.radix[2].d % 8 == 0 && strides_multiple_of(c, 8, 1);
-  if (!ok) return fail(VT_ERR_UNSUPPORTED, "vt_gemm: B needs runs of 8 contiguous, 16-byte aligned elements along N");
-  return VT_OK;
+  if (ok) return VT_OK;
+  // K contiguous instead (an [N,K] weight through a Permute): runs of 8 along K, everything else 16-byte aligned
+  ok = *K % 8 == 0 && (uintptr_t)g->b % 16 == 0 && r.nd >= 1 && r.stride[2] == 1 && r.radix[2].d % 8 == 0 &&
+       strides_multiple_of(r, 8, 1) && strides_multiple_of(c, 8, 0);
+  if (ok) {
+    g->b_kmajor = 1;
+    return VT_OK;
+  }
+  return fail(VT_ERR_UNSUPPORTED, "vt_gemm: B needs runs of 8 contiguous, 16-byte aligned elements along N or along K");
 }
 
 }  // namespace
@@ -445,6 +490,7 @@ int gemm_store_launch(const vt_desc& A, const vt_desc& B, const vt_desc& Cd, hip
   rc = plan_b(B, &P.g[0], &Kb, &N);
   if (rc != VT_OK) return rc;
   if (Ka != Kb) return fail(VT_ERR_SHAPE, "vt_gemm_store: inner dims of A and B differ");
+  if (P.g[0].b_kmajor) return fail(VT_ERR_UNSUPPORTED, "vt_gemm_store: B must be row-major [K,N]");
   if (M >= (1ll << 31) || N >= (1ll << 31) || Ka >= (1ll << 31)) return fail(VT_ERR_UNSUPPORTED, "vt_gemm_store: extents too large");
   OutMap O;
   memset(&O, 0, sizeof(O));
@@ -512,18 +558,29 @@ extern "C" int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* c
     return VT_OK;
   }
   int64_t N = -1, K = -1;
-  for (int g0 = 0; g0 < n_groups; g0 += kMaxGroups) {
+  // one unit of the launch per (group, piece of its A): a Concat along the rows of A is executed as
+  // a grouped launch, every piece writing its own range of rows of C
+  struct Unit {
+    int group;
+    size_t piece;
+  };
+  std::vector<Unit> units;
+  for (int i = 0; i < n_groups; ++i) {
+    if (!A[i] || !B[i] || !C[i]) return fail(VT_ERR_INVALID_ARG, "vt_gemm: NULL descriptor or output");
+    for (size_t pi = 0; pi < A[i]->pieces.size(); ++pi) units.push_back({i, pi});
+  }
+  for (size_t u0 = 0; u0 < units.size(); u0 += kMaxGroups) {
     GemmParams P;
     memset(&P, 0, sizeof(P));
-    const int ng = std::min(kMaxGroups, n_groups - g0);
+    const int ng = (int)std::min<size_t>(kMaxGroups, units.size() - u0);
     int tiles = 0;
     for (int i = 0; i < ng; ++i) {
-      const vt_desc* a = A[g0 + i];
-      const vt_desc* b = B[g0 + i];
-      if (!a || !b || !C[g0 + i]) return fail(VT_ERR_INVALID_ARG, "vt_gemm: NULL descriptor or output");
+      const vt_desc* a = A[units[u0 + i].group];
+      const vt_desc* b = B[units[u0 + i].group];
+      void* c = C[units[u0 + i].group];
       if (a->dtype != dt || b->dtype != dt) return fail(VT_ERR_INVALID_ARG, "vt_gemm: mixed operand dtypes");
-      int64_t M, Ka, Kb, Nb;
-      int rc = plan_a(*a, &P.g[i], &M, &Ka);
+      int64_t M, Ka, Kb, Nb, row_begin = 0;
+      int rc = plan_a(*a, &P.g[i], &M, &Ka, units[u0 + i].piece, &row_begin);
       if (rc != VT_OK) return rc;
       rc = plan_b(*b, &P.g[i], &Kb, &Nb);
       if (rc != VT_OK) return rc;
@@ -534,12 +591,13 @@ extern "C" int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* c
       }
       if (Nb != N || Ka != K) return fail(VT_ERR_SHAPE, "vt_gemm: all groups must share K and N");
       if (M >= (1ll << 31) || N >= (1ll << 31) || K >= (1ll << 31)) return fail(VT_ERR_UNSUPPORTED, "vt_gemm: extents too large");
-      if ((uintptr_t)C[g0 + i] % 4) return fail(VT_ERR_INVALID_ARG, "vt_gemm: misaligned C");
-      P.g[i].c = static_cast<char*>(C[g0 + i]);
+      if ((uintptr_t)c % 4) return fail(VT_ERR_INVALID_ARG, "vt_gemm: misaligned C");
+      P.g[i].c = static_cast<char*>(c) + (size_t)row_begin * (size_t)N * (c_dtype == VT_F32 ? 4 : 2);
       P.g[i].M = (int32_t)M;
       P.g[i].tiles_m = (int32_t)((M + BM - 1) / BM);
       P.g[i].tile_begin = tiles;
       P.g[i].k64 = P.g[i].a_col.radix[2].d % 64 == 0 && P.g[i].b_row.radix[2].d % 64 == 0;
+      if (P.g[i].b_kmajor != P.g[0].b_kmajor) return fail(VT_ERR_UNSUPPORTED, "vt_gemm: the groups of one call must store B the same way (all [K,N] or all [N,K])");
       tiles += P.g[i].tiles_m * (int32_t)((N + BN - 1) / BN);
     }
     P.n_groups = ng;
@@ -553,7 +611,11 @@ extern "C" int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* c
     const bool kt = K % BK != 0;
     OutMap no_map;
     memset(&no_map, 0, sizeof(no_map));
-#define VT_GEMM_LAUNCH(TT, CF, KT) hipLaunchKernelGGL((k_gemm<TT, CF, KT, false>), grid, dim3(256), 0, st, P, no_map)
+#define VT_GEMM_LAUNCH(TT, CF, KT)                                                                              \
+  do {                                                                                                          \
+    if (P.g[0].b_kmajor) hipLaunchKernelGGL((k_gemm<TT, CF, KT, false, true>), grid, dim3(256), 0, st, P, no_map); \
+    else hipLaunchKernelGGL((k_gemm<TT, CF, KT, false, false>), grid, dim3(256), 0, st, P, no_map);             \
+  } while (0)
     if (dt == VT_BF16) {
       if (P.c_f32) { if (kt) VT_GEMM_LAUNCH(bf16_t, true, true); else VT_GEMM_LAUNCH(bf16_t, true, false); }
       else { if (kt) VT_GEMM_LAUNCH(bf16_t, false, true); else VT_GEMM_LAUNCH(bf16_t, false, false); }

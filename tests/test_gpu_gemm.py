@@ -131,13 +131,61 @@ def test_rejects_unsupported_operands(gpu):
     wl = workloads.c3_oproj_gemm(seed=6, B=1, H=2, S=16, D=8, N=64)
     dw = tio.DeviceWorkload(wl)
     a = dw.build("A")
-    # B given transposed ([N,K] viewed as [K,N]): columns are not contiguous
-    bt = vt.build_chain([("Bt", "permute", ("W",), {"perm": (1, 0)})],
-                        {"W": ((64, 16), "bf16", dw.tensors["W"].data_ptr())}, "Bt")
     out = torch.empty((16, 64), dtype=torch.bfloat16, device="cuda:0")
+    # B with neither N nor K contiguous (every second column of a wider matrix)
+    wide = torch.zeros((16, 128), dtype=torch.bfloat16, device="cuda:0")
+    bs = vt.build_chain([("Bs", "slice", ("W",), {"dim": 1, "start": 0, "stop": 128, "step": 2})],
+                        {"W": ((16, 128), "bf16", wide.data_ptr())}, "Bs")
     with pytest.raises(vt.VtError) as ei:
-        vt.vt_gemm([a], [bt], [out], "bf16")
+        vt.vt_gemm([a], [bs], [out], "bf16")
     assert ei.value.code == vt.ERR_UNSUPPORTED
+    # A cut into pieces along K (a Concat along the contraction dim)
+    ak = vt.build_chain([("Ak", "concat", ("P", "Q"), {"dim": 1})],
+                        {"P": ((16, 8), "bf16", wide.data_ptr()), "Q": ((16, 8), "bf16", wide.data_ptr() + 4096)}, "Ak")
+    with pytest.raises(vt.VtError) as ei:
+        vt.vt_gemm([ak], [dw.build("W")], [out], "bf16")
+    assert ei.value.code == vt.ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("M,K,N,dtype", [(300, 128, 264, "bf16"), (64, 24, 256, "f16"), (513, 1032, 520, "bf16")])
+def test_weight_stored_n_by_k_through_a_permute(gpu, M, K, N, dtype):
+    """B = permute(W[N,K]): the contraction index is the contiguous one.  Same products, same order
+    of accumulation as with the [K,N] copy of the weight: identical bits, and the oracle's values."""
+    vt, tio, pipelines, torch = gpu
+    rng = np.random.default_rng(21)
+    a = workloads.encode(rng.normal(size=(M, K)).astype(np.float32), dtype)
+    w_nk = workloads.encode((rng.normal(size=(N, K)) * 0.05).astype(np.float32), dtype)
+    chain = [("B", "permute", ("W",), {"perm": (1, 0)})]
+    wl = workloads.Workload("nk", dtype, {"A": a, "W": w_nk}, chain, {"kind": "gemm", "a": "A", "b": "B"})
+    ref = run_workload(wl)["out"]
+    p = run(pipelines, tio, torch, wl)
+    check(tio.to_host_f64(p.out), ref)
+    wl2 = workloads.Workload("kn", dtype, {"A": a, "B": np.ascontiguousarray(w_nk.T)}, [], {"kind": "gemm", "a": "A", "b": "B"})
+    p2 = run(pipelines, tio, torch, wl2)
+    assert torch.equal(p.out, p2.out)
+
+
+def test_operand_stacked_by_a_concat_along_the_rows(gpu):
+    """A = concat of three tensors along dim 0 (two of them seen through a Permute): executed as
+    one grouped launch, every piece writing its own rows of C."""
+    vt, tio, pipelines, torch = gpu
+    rng = np.random.default_rng(22)
+    K, N = 128, 264
+    src = {"P": workloads.encode(rng.normal(size=(2, 50, K)).astype(np.float32), "bf16"),
+           "Q": workloads.encode(rng.normal(size=(300, K)).astype(np.float32), "bf16"),
+           "R": workloads.encode(rng.normal(size=(19, 3, K)).astype(np.float32), "bf16"),
+           "W": workloads.encode((rng.normal(size=(K, N)) * 0.05).astype(np.float32), "bf16")}
+    chain = [("p1", "permute", ("P",), {"perm": (1, 0, 2)}), ("p2", "reshape", ("p1",), {"shape": (100, K)}),
+             ("r1", "permute", ("R",), {"perm": (1, 0, 2)}), ("r2", "reshape", ("r1",), {"shape": (57, K)}),
+             ("A", "concat", ("p2", "Q", "r2"), {"dim": 0})]
+    wl = workloads.Workload("stack", "bf16", src, chain, {"kind": "gemm", "a": "A", "b": "W"})
+    ref = run_workload(wl)["out"]
+    assert ref.shape == (457, N)
+    p = run(pipelines, tio, torch, wl)
+    assert p.A[0].info()["n_pieces"] == 3
+    check(tio.to_host_f64(p.out), ref)
+    m = run(pipelines, tio, torch, wl, materialized=True)
+    assert torch.equal(p.out, m.out)
 
 
 @pytest.fixture(scope="module")
