@@ -173,6 +173,13 @@ int vt_weighted_sum(const vt_desc* x, const vt_desc* y, const float* weights, vo
  * folded: [.., K] counts as rows x K), B[g] virtual [K, N]; f16 or bf16 operands, fp32
  * accumulation, C[g] dense [M_g, N] row-major device pointers of dtype c_dtype (same as the
  * operands, or VT_F32).  One launch covers all groups.
+ * Operand forms: the tiled kernel (256 x 256 tiles) takes maps that separate into a row part plus
+ * a column part with runs of 8 contiguous, 16-byte aligned elements along K for A (rows through
+ * any mixed-radix map or an index table: permuted, gathered, broadcast rows) and along N or
+ * along K for B (a [K,N] weight, or an [N,K] weight seen through a Permute); an A that a Concat
+ * stacked along its outermost dim runs as one group per piece.  Every other representable map
+ * (pieces along K, stacked index stages, tables on columns, no alignment at all) runs on a generic
+ * kernel that applies the whole map per element: same results, far slower.
  * prologue = VT_GEMM_LAYERNORM applies per-row LayerNorm (gamma 1, beta 0, eps) over K to A,
  * rounded to the operand dtype, before the product, inside the load stage (the normalised
  * tensor is never stored).  The fused kernel takes K = 64 or 128, N <= 384, contiguous rows of

@@ -393,6 +393,100 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P, const OutMap O
 #endif
 }
 
+// ------------------------------------------------------------------------------------------
+// The same product for ANY pair of maps the descriptor can hold (pieces along K, stacked index
+// stages, tables anywhere, no contiguity at all): every element of A and B is found through the
+// generic evaluator, staged in LDS with the contraction index contiguous, and multiplied on the
+// matrix cores.  Correct for every representable chain, and slow (one evaluation per element):
+// the tiled kernel above takes over whenever the maps have its separable form.
+// 64 x 64 tile per workgroup, one 32 x 32 block per wave, K in steps of 16.
+// ------------------------------------------------------------------------------------------
+template <typename T, bool C_F32>
+__global__ void __launch_bounds__(256) k_gemm_generic(const DevDesc A, const DevDesc B, void* __restrict__ Cout, int M, int N, int K) {
+  typedef Mma<T> M_;
+  typedef typename M_::vec opvec;
+  __shared__ __attribute__((aligned(16))) T la[64][24];      // [row][k], 16 k used, pitch 48 bytes
+  __shared__ __attribute__((aligned(16))) T lb[64][24];      // [col][k]
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, lh = lane >> 5;
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  f32x16 acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  for (int k0 = 0; k0 < K; k0 += 16) {
+    {  // A: thread -> row t / 4, k = (t % 4) * 4 .. + 3
+      const int r = t >> 2, m = min(m0 + r, M - 1);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int k = k0 + (t & 3) * 4 + i;
+        T v = from_float<T>(0.f);
+        if (k < K) {
+          int64_t off;
+          const void* ptr;
+          vtd_eval(A, 0, (uint32_t)m * (uint32_t)K + (uint32_t)k, &off, &ptr);
+          v = static_cast<const T*>(ptr)[off];
+        }
+        la[r][(t & 3) * 4 + i] = v;
+      }
+    }
+    {  // B: thread -> k = t / 16, n = (t % 16) * 4 .. + 3, written transposed
+      const int kk = t >> 4, k = k0 + kk;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int c = (t & 15) * 4 + i, n = min(n0 + c, N - 1);
+        T v = from_float<T>(0.f);
+        if (k < K) {
+          int64_t off;
+          const void* ptr;
+          vtd_eval(B, 0, (uint32_t)k * (uint32_t)N + (uint32_t)n, &off, &ptr);
+          v = static_cast<const T*>(ptr)[off];
+        }
+        lb[c][kk] = v;
+      }
+    }
+    __syncthreads();
+    const opvec af = *reinterpret_cast<const opvec*>(&la[wm * 32 + l32][lh * 8]);
+    const opvec bf = *reinterpret_cast<const opvec*>(&lb[wn * 32 + l32][lh * 8]);
+    acc = M_::run(af, bf, acc);
+    __syncthreads();
+  }
+  typedef typename std::conditional<C_F32, float, T>::type CT;
+  CT* c = static_cast<CT*>(Cout);
+  const int col = n0 + wn * 32 + l32;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = m0 + wm * 32 + lh * 4 + 8 * j + i;
+      if (row < M && col < N) c[(size_t)row * N + col] = from_float<CT>(acc[4 * j + i]);
+    }
+}
+
+int launch_generic(const vt_desc& a, const vt_desc& b, void* c, int c_dtype, hipStream_t st) {
+  const int n = (int)a.shape.size();
+  if (n < 2 || b.shape.size() != 2) return fail(VT_ERR_SHAPE, "vt_gemm: A must be [.., K] and B [K, N]");
+  int64_t M = 1;
+  for (int i = 0; i < n - 1; ++i) M *= a.shape[i];
+  const int64_t K = a.shape[n - 1], N = b.shape[1];
+  if (b.shape[0] != K) return fail(VT_ERR_SHAPE, "vt_gemm: inner dims of A and B differ");
+  DevDesc DA, DB;
+  int64_t oa, ia, ob, ib;
+  int rc = to_device(a, &DA, &oa, &ia);
+  if (rc != VT_OK) return rc;
+  rc = to_device(b, &DB, &ob, &ib);
+  if (rc != VT_OK) return rc;
+  if (oa != 1 || ob != 1 || M > 65535ll * 64 || N > 65535ll * 64) return fail(VT_ERR_UNSUPPORTED, "vt_gemm: operand too large for the generic path");
+  dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64));
+  if (a.dtype == VT_BF16) {
+    if (c_dtype == VT_F32) hipLaunchKernelGGL((k_gemm_generic<bf16_t, true>), grid, dim3(256), 0, st, DA, DB, c, (int)M, (int)N, (int)K);
+    else hipLaunchKernelGGL((k_gemm_generic<bf16_t, false>), grid, dim3(256), 0, st, DA, DB, c, (int)M, (int)N, (int)K);
+  } else {
+    if (c_dtype == VT_F32) hipLaunchKernelGGL((k_gemm_generic<f16_t, true>), grid, dim3(256), 0, st, DA, DB, c, (int)M, (int)N, (int)K);
+    else hipLaunchKernelGGL((k_gemm_generic<f16_t, false>), grid, dim3(256), 0, st, DA, DB, c, (int)M, (int)N, (int)K);
+  }
+  return check_launch("vt_gemm (generic maps)");
+}
+
 // Piece `pi` of A as one operand of its own: a Concat along the rows makes A a stack of pieces,
 // each of which is a range of rows [*row_begin, *row_begin + *M) of the product.
 int plan_a(const vt_desc& d, GemmGroup* g, int64_t* M, int64_t* K, size_t pi = 0, int64_t* row_begin = nullptr) {
@@ -556,6 +650,26 @@ extern "C" int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* c
       if (rc != VT_OK) return rc;
     }
     return VT_OK;
+  }
+  // Can the tiled kernel take every operand?  If a map lacks the separable form it needs (and only
+  // then: wrong arguments are still errors), the whole call runs on the generic kernel, group by group.
+  {
+    bool generic = false;
+    for (int i = 0; i < n_groups && !generic; ++i) {
+      if (!A[i] || !B[i] || !C[i]) return fail(VT_ERR_INVALID_ARG, "vt_gemm: NULL descriptor or output");
+      if (A[i]->dtype != dt || B[i]->dtype != dt) return fail(VT_ERR_INVALID_ARG, "vt_gemm: mixed operand dtypes");
+      GemmGroup probe;
+      int64_t m_, k_, n_, rb_;
+      for (size_t pi = 0; pi < A[i]->pieces.size() && !generic; ++pi) generic = plan_a(*A[i], &probe, &m_, &k_, pi, &rb_) == VT_ERR_UNSUPPORTED;
+      generic = generic || plan_b(*B[i], &probe, &k_, &n_) == VT_ERR_UNSUPPORTED;
+    }
+    if (generic) {
+      for (int i = 0; i < n_groups; ++i) {
+        int rc = launch_generic(*A[i], *B[i], C[i], c_dtype, st);
+        if (rc != VT_OK) return rc;
+      }
+      return VT_OK;
+    }
   }
   int64_t N = -1, K = -1;
   // one unit of the launch per (group, piece of its A): a Concat along the rows of A is executed as

@@ -126,25 +126,57 @@ def test_c3_full_size_every_output(gpu):
     check_rounded_product(tio.to_host_f64(p.out), ref)
 
 
-def test_rejects_unsupported_operands(gpu):
+GENERIC_CASES = [
+    # what the tiled kernel cannot take: the generic kernel finds every element through the whole map
+    ("a_cut_along_k", {"P": (70, 24), "Q": (70, 40), "W": (64, 72)},
+     [("A", "concat", ("P", "Q"), {"dim": 1})], "A", "W"),
+    ("b_every_second_column", {"A": (33, 48), "W": (48, 200)},
+     [("B", "slice", ("W",), {"dim": 1, "start": 1, "stop": 200, "step": 2})], "A", "B"),          # N = 100
+    ("odd_k_and_n", {"A": (65, 37), "W": (37, 51)}, [], "A", "W"),
+    ("gathered_columns", {"X": (40, 90), "W": (30, 64)},
+     [("A", "index_select", ("X",), {"dim": 1, "index": "t"})], "A", "W"),
+    ("reshape_across_a_slice", {"X": (12, 20), "W": (18, 40)},
+     [("s", "slice", ("X",), {"dim": 1, "start": 1, "stop": 19, "step": 1}), ("r", "reshape", ("s",), {"shape": (6, 36)}),
+      ("A", "slice", ("r",), {"dim": 1, "start": 0, "stop": 18, "step": 1})], "A", "W"),
+]
+
+
+@pytest.mark.parametrize("name,shapes,chain,a,b", GENERIC_CASES, ids=[c[0] for c in GENERIC_CASES])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_any_representable_map_runs_on_the_generic_kernel(gpu, name, shapes, chain, a, b, dtype):
+    vt, tio, pipelines, torch = gpu
+    rng = np.random.default_rng(23)
+    src = {k: workloads.encode((rng.normal(size=shp) * (0.1 if k == "W" else 1.0)).astype(np.float32), dtype) for k, shp in shapes.items()}
+    tables = {"t": rng.integers(0, 90, size=30).astype(np.int32)}
+    wl = workloads.Workload(name, dtype, src, chain, {"kind": "gemm", "a": a, "b": b}, tables)
+    ref = run_workload(wl)["out"]
+    p = run(pipelines, tio, torch, wl)
+    assert tuple(p.out.shape) == ref.shape
+    check(tio.to_host_f64(p.out), ref)
+    out32 = torch.empty(ref.shape, dtype=torch.float32, device="cuda:0")
+    vt.vt_gemm(p.A, p.B, [out32], "f32")
+    torch.cuda.synchronize()
+    assert np.max(np.abs(out32.cpu().numpy().astype(np.float64) - ref)) <= 2e-4 * max(1.0, np.abs(ref).max())
+
+
+def test_rejects_bad_arguments(gpu):
     vt, tio, pipelines, torch = gpu
     wl = workloads.c3_oproj_gemm(seed=6, B=1, H=2, S=16, D=8, N=64)
     dw = tio.DeviceWorkload(wl)
-    a = dw.build("A")
+    a, w = dw.build("A"), dw.build("W")
     out = torch.empty((16, 64), dtype=torch.bfloat16, device="cuda:0")
-    # B with neither N nor K contiguous (every second column of a wider matrix)
-    wide = torch.zeros((16, 128), dtype=torch.bfloat16, device="cuda:0")
-    bs = vt.build_chain([("Bs", "slice", ("W",), {"dim": 1, "start": 0, "stop": 128, "step": 2})],
-                        {"W": ((16, 128), "bf16", wide.data_ptr())}, "Bs")
+    f32 = torch.zeros((16, 64), dtype=torch.float32, device="cuda:0")
+    wf = vt.build_chain([], {"F": ((16, 64), "f32", f32.data_ptr())}, "F")
     with pytest.raises(vt.VtError) as ei:
-        vt.vt_gemm([a], [bs], [out], "bf16")
-    assert ei.value.code == vt.ERR_UNSUPPORTED
-    # A cut into pieces along K (a Concat along the contraction dim)
-    ak = vt.build_chain([("Ak", "concat", ("P", "Q"), {"dim": 1})],
-                        {"P": ((16, 8), "bf16", wide.data_ptr()), "Q": ((16, 8), "bf16", wide.data_ptr() + 4096)}, "Ak")
+        vt.vt_gemm([a], [wf], [out], "bf16")
+    assert ei.value.code == vt.ERR_INVALID_ARG
+    w_short = vt.build_chain([("s", "slice", ("W",), {"dim": 0, "start": 0, "stop": 8, "step": 1})], {"W": ((16, 64), "bf16", dw.tensors["W"].data_ptr())}, "s")
     with pytest.raises(vt.VtError) as ei:
-        vt.vt_gemm([ak], [dw.build("W")], [out], "bf16")
-    assert ei.value.code == vt.ERR_UNSUPPORTED
+        vt.vt_gemm([a], [w_short], [out], "bf16")
+    assert ei.value.code == vt.ERR_SHAPE
+    with pytest.raises(vt.VtError) as ei:
+        vt.vt_gemm([a], [w], [out], "f16")          # C neither the operands' type nor f32
+    assert ei.value.code == vt.ERR_INVALID_ARG
 
 
 @pytest.mark.parametrize("M,K,N,dtype", [(300, 128, 264, "bf16"), (64, 24, 256, "f16"), (513, 1032, 520, "bf16")])
