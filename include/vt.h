@@ -265,6 +265,51 @@ int vt_gemm_store_workspace_init(void* workspace, size_t workspace_bytes, void* 
 int vt_gemm_store(const vt_desc* A, const vt_desc* B, const vt_desc* C, void* workspace,
                   size_t workspace_bytes, void* stream);
 
+/* ---- which tensors to make virtual (Sec. 5) -------------------------------------------------
+ * The virtual tensor opportunity graph of a computation graph (Sec. 5.1, Def. 6, Alg. 1) and the
+ * global greedy choice of a points-to graph (Sec. 5.2, Alg. 2).  Host only.
+ * A graph is n_tensors tensors (numbers 0 .. n_tensors-1) and a list of statements; kind is a
+ * vt_op_kind, VT_OP_SCATTER_ND (inputs: data, indices, updates) or VT_OP_COMPUTE (any operator
+ * that is not data movement: creates no opportunity).  pinned[t] != 0 marks the inputs and outputs
+ * of the graph, which stay physical.  A *bundle* says: `tensor` can become a virtual tensor of
+ * `targets` by eliminating statement `stmt`, reading through the map (VT_DIR_READ: the tensor is
+ * an output of the operator) or storing through it (VT_DIR_STORE: the tensor is an input that
+ * lives inside the operator's output).  The bundles of one tensor exclude each other (the conflict
+ * set).  A strategy is an array bundle_of_tensor[n_tensors]: a bundle number, or -1 = physical. */
+#define VT_OP_SCATTER_ND 8
+#define VT_OP_COMPUTE (-1)
+#define VT_DIR_READ 1
+#define VT_DIR_STORE 2
+typedef struct {
+  int32_t kind;
+  int32_t n_in;
+  int32_t in[VT_MAX_OP_INPUTS];
+  int32_t n_out;                   /* 1, or the number of outputs of a SPLIT */
+  int32_t out[VT_MAX_OP_INPUTS];
+} vt_graph_stmt;
+typedef struct vt_vtog vt_vtog;    /* opaque; host memory owned by the library */
+/* Alg. 1.  directions: VT_DIR_READ | VT_DIR_STORE or one of them.  Errors: INVALID_ARG. */
+int vt_vtog_build(const vt_graph_stmt* stmts, int n_stmts, int n_tensors, const uint8_t* pinned, int directions,
+                  vt_vtog** out);
+int vt_vtog_free(vt_vtog* g);
+int vt_vtog_size(const vt_vtog* g, int* n_tensors, int* n_bundles);
+/* Bundle b (in statement order); targets must hold VT_MAX_OP_INPUTS entries.  Outputs may be NULL. */
+int vt_vtog_bundle(const vt_vtog* g, int b, int* tensor, int* n_targets, int* targets, int* stmt, int* direction);
+/* ok = 1 if every chosen bundle belongs to its tensor and following the edges always ends at a
+ * physical tensor (no cycle): a points-to graph (Sec. 5.2). */
+int vt_vtog_is_points_to_graph(const vt_vtog* g, const int* bundle_of_tensor, int* ok);
+/* Alg. 2.  saving(user, b, bundle_of_tensor) returns the latency saving w of adding bundle b to the
+ * strategy built so far (measured by the caller, e.g. by timing both variants on the GPU); it is
+ * called once per bundle at the start and again for the bundles that point to a tensor that has
+ * just joined.  Every iteration anchors one tensor: the one whose best ready bundle (targets all
+ * anchored, saving >= 0) saves most, with that bundle; if no bundle is ready, the unanchored tensor
+ * nearest the graph's outputs, as a physical tensor.  bundle_of_tensor (n_tensors entries)
+ * receives the strategy, total the sum of the savings taken; order (may be NULL, n_tensors
+ * entries) the bundles in the order they were taken, n_order their number. */
+typedef double (*vt_saving_fn)(void* user, int bundle, const int* bundle_of_tensor);
+int vt_vtog_greedy(const vt_vtog* g, vt_saving_fn saving, void* user, int* bundle_of_tensor, double* total,
+                   int* order, int* n_order);
+
 const char* vt_last_error(void);
 const char* vt_version(void);
 

@@ -39,6 +39,15 @@ class VtOp(C.Structure):
                 ("index", C.c_void_p), ("index_host", C.c_void_p), ("n_index", C.c_int64)]
 
 
+class VtGraphStmt(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("n_in", C.c_int32), ("in_", C.c_int32 * VT_MAX_OP_INPUTS),
+                ("n_out", C.c_int32), ("out", C.c_int32 * VT_MAX_OP_INPUTS)]
+
+
+SAVING_FN = C.CFUNCTYPE(C.c_double, C.c_void_p, C.c_int, C.POINTER(C.c_int))
+OP_SCATTER_ND, OP_COMPUTE, DIR_READ, DIR_STORE = 8, -1, 1, 2
+
+
 class VtError(RuntimeError):
     def __init__(self, code, msg):
         super().__init__("vt error %d: %s" % (code, msg))
@@ -86,6 +95,12 @@ def lib():
         L.vt_decode_attn_static_capacity.argtypes = []
         L.vt_decode_attn_static_capacity.restype = C.c_size_t
         L.vt_decode_attn_static.argtypes = [P, P, P, C.c_float, P, P, C.c_int, P]
+        L.vt_vtog_build.argtypes = [C.POINTER(VtGraphStmt), C.c_int, C.c_int, C.POINTER(C.c_uint8), C.c_int, C.POINTER(P)]
+        L.vt_vtog_free.argtypes = [P]
+        L.vt_vtog_size.argtypes = [P, C.POINTER(C.c_int), C.POINTER(C.c_int)]
+        L.vt_vtog_bundle.argtypes = [P, C.c_int] + [C.POINTER(C.c_int)] * 5
+        L.vt_vtog_is_points_to_graph.argtypes = [P, C.POINTER(C.c_int), C.POINTER(C.c_int)]
+        L.vt_vtog_greedy.argtypes = [P, SAVING_FN, C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_double), C.POINTER(C.c_int), C.POINTER(C.c_int)]
         L.vt_last_error.restype = C.c_char_p
         L.vt_version.restype = C.c_char_p
         _lib = L

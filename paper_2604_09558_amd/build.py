@@ -11,7 +11,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libvt.so")
 LIB_PROFILE = os.path.join(HERE, "libvt_profile.so")   # same sources with -DVT_PROFILE: per-workgroup timestamps
 
-HOST_SOURCES = ["vt_build.cpp", "vt_device_host.cpp"]
+HOST_SOURCES = ["vt_build.cpp", "vt_device_host.cpp", "vt_vtog.cpp"]
 HIP_SOURCES = ["vt_kernels.hip", "vt_attn.hip", "vt_gemm.hip", "vt_ln_gemm.hip", "vt_gemm_store.hip"]
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC, "-Wall", "-Wno-unused-function"]

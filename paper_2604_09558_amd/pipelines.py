@@ -322,8 +322,9 @@ def choose_path(dw: DeviceWorkload, iters=20, warmup=3, unit_bytes=0, **kw):
 # of vtog.py measures, and what it finally keeps
 # ------------------------------------------------------------------------------------------
 class StrategyPipeline:
-    """`chosen` maps tensor names to read-direction opportunities (vtog.Opportunity): those
-    tensors are virtual.  Every other intermediate the consumer depends on is physical and is
+    """`chosen` maps tensor names to opportunities (vtog.Opportunity): those tensors are virtual,
+    in the read direction (the consumer reads through the map) or, for inputs of a Concat, in the
+    store direction (the input is written straight into the Concat's output).  Every other intermediate the consumer depends on is physical and is
     produced by one copy kernel that reads through the descriptor of the eliminated operators
     above it; the consumer reads its operands through descriptors over the nearest physical
     tensors.  With `chosen` empty this is the fully materialized path, with every tensor chosen
@@ -353,12 +354,48 @@ class StrategyPipeline:
             for o in vtog.outputs_of(st):
                 read_opp[o] = vtog.Opportunity(o, tuple(i for i in st[2] if isinstance(i, str)), st_i, "read")
         done = set()
+        # store direction (Sec. 4.2, Sec. 4.4): an input of a Concat that was made a virtual tensor
+        # of the Concat's output is never stored on its own; it is written where it lives inside
+        # the output.  Such a Concat is executed input by input: each one goes through its own map
+        # (over whatever physical tensors it is made of) straight into its range of the output.
+        stored = {t: o for t, o in chosen.items() if o.direction == "store"}
+        for t, o in stored.items():
+            if stmts[o.op_index][1] != "concat":
+                raise vt.VtError(vt.ERR_UNSUPPORTED, "only store-direction choices of Concat inputs are lowered (tensor %r)" % t)
+        chosen = {t: o for t, o in chosen.items() if o.direction == "read"}
+        by_concat = {}
+        for t, o in stored.items():
+            by_concat.setdefault(o.op_index, set()).add(t)
 
         def ensure(t):
             """make sure tensor t (a physical intermediate) has a buffer and a copy that fills it"""
             if t in done or t not in produced:
                 return
             done.add(t)
+            if produced[t] in by_concat:
+                out, _, ins, p = stmts[produced[t]]
+                dim = p["dim"]
+                parts = []
+                for i in ins:
+                    via = dict(chosen)
+                    if i in stored and i in read_opp:
+                        via[i] = read_opp[i]       # its producing operator writes into the output: no buffer of its own
+                    chain, sources = vtog.read_chain(stmts, via, i)
+                    for s in sources:
+                        ensure(s)
+                    parts.append(self._build(chain, sources, i))
+                shape = list(parts[0].shape)
+                shape[dim] = sum(d.shape[dim] for d in parts)
+                self.shapes[t] = tuple(shape)
+                self.bufs[t] = torch.empty(self.shapes[t], dtype=TORCH_DTYPE[wl.dtype], device=dw.device)
+                self.bytes_written += self.bufs[t].numel() * self.bufs[t].element_size()
+                at = 0
+                for k, d in enumerate(parts):
+                    slot = "%s__part%d" % (t, k)
+                    dst = self._build([(slot, "slice", (t,), {"dim": dim, "start": at, "stop": at + d.shape[dim], "step": 1})], [t], slot)
+                    self.copies.append((produced[t], d, dst))
+                    at += d.shape[dim]
+                return
             forced = dict(chosen)
             forced[t] = read_opp[t]
             chain, sources = vtog.read_chain(stmts, forced, t)

@@ -1,31 +1,27 @@
 """Which tensors to make virtual: the virtual tensor opportunity graph (Sec. 5.1, Def. 6,
 Alg. 1) and the global greedy construction of a points-to graph (Sec. 5.2, Alg. 2).
 
-Host logic only.  A computation graph is a list of statements ``(out, op, inputs, params)`` (the
-form the workloads use; ``out`` is a tuple for operators with several outputs) plus the names of
-the graph's input and output tensors.  Operators whose kind is not a data-movement operator are
-compute operators: they create no opportunities.
+The two algorithms run inside the library (vt_vtog_build, vt_vtog_greedy, ... of include/vt.h);
+this module turns a graph written with tensor names into tensor numbers and back.  A computation
+graph is a list of statements ``(out, op, inputs, params)`` (the form the workloads use; ``out``
+is a tuple for operators with several outputs) plus the names of the graph's input and output
+tensors.  Operators whose kind is not a data-movement operator are compute operators: they
+create no opportunities.
 
 An *opportunity* (one edge bundle of the VTOG) says: tensor ``a`` can be made a virtual tensor
-of the tensors ``targets`` by eliminating exactly one data-movement operator.  Two directions:
-
-  read   ``a`` is an output of the operator and its elements are found in the operator's inputs
-         (the consumer of ``a`` reads through the map);
-  store  ``a`` is an input of the operator and lives inside the operator's output (the producer
-         of ``a`` writes through the map): inputs of Concat, the input of a Reshape or Permute,
-         the updates and the data input of a ScatterND.
-
-Rules per operator follow Sec. 4.4.  All edges of a bundle are taken together (the output of a
-Concat is a virtual tensor of all of its inputs at once); bundles of one tensor that come from
-different operators, or from different directions of one operator, are mutually exclusive (a
-tensor mapped into two places would break the one-to-one property): that is the conflict set.
+of the tensors ``targets`` by eliminating exactly one data-movement operator, in the read
+direction (``a`` is an output of the operator; its consumer reads through the map) or in the
+store direction (``a`` is an input that lives inside the operator's output; its producer writes
+through the map).  Bundles of one tensor exclude each other: that is the conflict set.
 """
 from __future__ import annotations
 
+import ctypes as C
 from dataclasses import dataclass, field
 
-READ_OPS = ("reshape", "permute", "slice", "unsqueeze", "expand", "index_select", "split", "concat", "scatter_nd")
-BIJECTIVE = ("reshape", "permute", "unsqueeze")
+from . import binding
+
+KINDS = dict(binding.OP_KINDS, scatter_nd=binding.OP_SCATTER_ND)
 
 
 @dataclass(frozen=True)
@@ -45,45 +41,35 @@ class Vtog:
     nodes: list
     opportunities: list                              # every bundle, in statement order
     by_tensor: dict = field(default_factory=dict)    # tensor -> its bundles (the conflict set: pick at most one)
+    handle: object = None                            # vt_vtog* of the library
+    index: dict = field(default_factory=dict)        # tensor name -> number
 
     @property
     def edges(self):
         return [e for o in self.opportunities for e in o.edges]
 
+    def __del__(self):
+        try:
+            if self.handle:
+                binding.lib().vt_vtog_free(self.handle)
+                self.handle = None
+        except Exception:
+            pass
+
+    def strategy_array(self, chosen):
+        """dict tensor -> Opportunity as the library's array (bundle number per tensor, -1 = physical);
+        None if some choice is not a bundle of this graph."""
+        arr = (C.c_int * len(self.nodes))(*([-1] * len(self.nodes)))
+        for t, o in chosen.items():
+            if t not in self.index or o not in self.opportunities or o.tensor != t:
+                return None
+            arr[self.index[t]] = self.opportunities.index(o)
+        return arr
+
 
 def outputs_of(stmt):
     out = stmt[0]
     return tuple(out) if isinstance(out, (tuple, list)) else (out,)
-
-
-def vt_rules(stmt, index):
-    """Opportunities one data-movement statement creates (Sec. 4.4), both directions."""
-    _, op, ins, _ = stmt
-    outs = outputs_of(stmt)
-    res = []
-    if op not in READ_OPS:
-        return res
-    if op == "scatter_nd":
-        data, _, updates = ins[0], ins[1], ins[2]
-        # the output starts as a clone of `data`: output as a virtual tensor of data (Type I),
-        # and `updates` as a virtual tensor of the output (Type II: the indices may scatter)
-        res.append(Opportunity(outs[0], (data,), index, "read"))
-        res.append(Opportunity(updates, (outs[0],), index, "store"))
-        return res
-    if op == "split":
-        for o in outs:
-            res.append(Opportunity(o, (ins[0],), index, "read"))
-        res.append(Opportunity(ins[0], outs, index, "store"))        # the input stitched from its outputs: Type II
-        return res
-    if op == "concat":
-        res.append(Opportunity(outs[0], tuple(ins), index, "read"))
-        for i in ins:
-            res.append(Opportunity(i, (outs[0],), index, "store"))
-        return res
-    res.append(Opportunity(outs[0], (ins[0],), index, "read"))
-    if op in BIJECTIVE:
-        res.append(Opportunity(ins[0], (outs[0],), index, "store"))
-    return res
 
 
 def build_vtog(statements, graph_inputs, graph_outputs, directions=("read", "store")):
@@ -94,13 +80,37 @@ def build_vtog(statements, graph_inputs, graph_outputs, directions=("read", "sto
         for o in outputs_of(st):
             if o not in nodes:
                 nodes.append(o)
-    pinned = set(graph_inputs) | set(graph_outputs)
-    g = Vtog(nodes, [])
+    for st in statements:                     # names that only ever appear as inputs (index tensors and the like)
+        for i in st[2]:
+            if isinstance(i, str) and i not in nodes:
+                nodes.append(i)
+    index = {n: k for k, n in enumerate(nodes)}
+    arr = (binding.VtGraphStmt * max(1, len(statements)))()
     for k, st in enumerate(statements):
-        for opp in vt_rules(st, k):
-            if opp.direction in directions and opp.tensor not in pinned:
-                g.opportunities.append(opp)
-                g.by_tensor.setdefault(opp.tensor, []).append(opp)
+        ins = [i for i in st[2] if isinstance(i, str)]
+        outs = outputs_of(st)
+        arr[k].kind = KINDS.get(st[1], binding.OP_COMPUTE)
+        arr[k].n_in, arr[k].n_out = len(ins), len(outs)
+        for j, i in enumerate(ins):
+            arr[k].in_[j] = index[i]
+        for j, o in enumerate(outs):
+            arr[k].out[j] = index[o]
+    pinned = (C.c_uint8 * len(nodes))(*[1 if n in set(graph_inputs) | set(graph_outputs) else 0 for n in nodes])
+    mask = (binding.DIR_READ if "read" in directions else 0) | (binding.DIR_STORE if "store" in directions else 0)
+    h = C.c_void_p()
+    L = binding.lib()
+    binding._check(L.vt_vtog_build(arr, len(statements), len(nodes), pinned, mask, C.byref(h)))
+    g = Vtog(nodes, [], handle=h, index=index)
+    nb = C.c_int()
+    binding._check(L.vt_vtog_size(h, None, C.byref(nb)))
+    for b in range(nb.value):
+        t, nt, st, dr = C.c_int(), C.c_int(), C.c_int(), C.c_int()
+        tg = (C.c_int * binding.VT_MAX_OP_INPUTS)()
+        binding._check(L.vt_vtog_bundle(h, b, C.byref(t), C.byref(nt), tg, C.byref(st), C.byref(dr)))
+        opp = Opportunity(nodes[t.value], tuple(nodes[tg[i]] for i in range(nt.value)), st.value,
+                          "read" if dr.value == binding.DIR_READ else "store")
+        g.opportunities.append(opp)
+        g.by_tensor.setdefault(opp.tensor, []).append(opp)
     return g
 
 
@@ -108,59 +118,45 @@ def is_points_to_graph(vtog, chosen):
     """`chosen`: tensor -> Opportunity.  Valid if every choice is one of the tensor's bundles
     (at most one each, so no two conflict) and following the edges always ends at a physical
     tensor (no cycle)."""
-    for t, o in chosen.items():
-        if o not in vtog.by_tensor.get(t, []):
-            return False
-    state = {}
-
-    def grounded(t):
-        if t not in chosen:
-            return True
-        if state.get(t) == 1:
-            return False
-        if state.get(t) == 2:
-            return True
-        state[t] = 1
-        ok = all(grounded(x) for x in chosen[t].targets)
-        state[t] = 2
-        return ok
-
-    return all(grounded(t) for t in chosen)
+    arr = vtog.strategy_array(chosen)
+    if arr is None:
+        return False
+    ok = C.c_int()
+    binding._check(binding.lib().vt_vtog_is_points_to_graph(vtog.handle, arr, C.byref(ok)))
+    return bool(ok.value)
 
 
 def greedy(vtog, profile):
-    """Alg. 2.  ``profile(opportunity, chosen)`` returns the latency saving of adding that bundle
-    to the strategy ``chosen`` (dict tensor -> Opportunity), i.e. the sum of w(e) over its edges.
+    """Alg. 2 (runs in the library).  ``profile(opportunity, chosen)`` returns the latency saving of
+    adding that bundle to the strategy ``chosen`` (dict tensor -> Opportunity), i.e. the sum of w(e)
+    over its edges.  Returns (chosen, total saving, [(opportunity, its saving) in the order taken])."""
+    n = len(vtog.nodes)
+    seen = {}
 
-    Reading of the listing where it leaves room: MaxEdges(v, S(v), A) ranges over the bundles of v
-    whose targets all lie in the anchor set A (bundles of one tensor exclude each other, so the
-    best non-conflicting edge set is the best single bundle); a tensor without such a bundle is
-    not a candidate in that iteration; when the best candidate saves nothing (< 0) the loop stops
-    and every tensor left over stays physical.  After a tensor joins, the bundles that point to it
-    are profiled again against the grown strategy."""
-    anchors = {v for v in vtog.nodes if not vtog.by_tensor.get(v)}
-    chosen = {}
-    w = {o: profile(o, dict(chosen)) for o in vtog.opportunities}
-    total = 0.0
-    trace = []
-    while len(anchors) < len(vtog.nodes):
-        best = None
-        for v in vtog.nodes:
-            if v in anchors:
-                continue
-            for o in vtog.by_tensor[v]:
-                if all(t in anchors for t in o.targets) and (best is None or w[o] > w[best]):
-                    best = o
-        if best is None or w[best] < 0:
-            break
-        anchors.add(best.tensor)
-        chosen[best.tensor] = best
-        total += w[best]
-        trace.append((best, w[best]))
-        for o in vtog.opportunities:
-            if best.tensor in o.targets and o.tensor not in anchors:
-                w[o] = profile(o, dict(chosen))
-    return chosen, total, trace
+    failure = []
+
+    def saving(_user, b, arr):
+        if failure:                      # an exception cannot cross the library: stop the search, raise afterwards
+            return -1.0
+        try:
+            chosen = {vtog.nodes[t]: vtog.opportunities[arr[t]] for t in range(n) if arr[t] >= 0}
+            w = float(profile(vtog.opportunities[b], chosen))
+        except BaseException as e:       # noqa: B902
+            failure.append(e)
+            return -1.0
+        seen[b] = w
+        return w
+
+    out = (C.c_int * n)()
+    order = (C.c_int * n)()
+    total, n_order = C.c_double(), C.c_int()
+    cb = binding.SAVING_FN(saving)
+    binding._check(binding.lib().vt_vtog_greedy(vtog.handle, cb, None, out, C.byref(total), order, C.byref(n_order)))
+    if failure:
+        raise failure[0]
+    chosen = {vtog.nodes[t]: vtog.opportunities[out[t]] for t in range(n) if out[t] >= 0}
+    trace = [(vtog.opportunities[order[k]], seen[order[k]]) for k in range(n_order.value)]
+    return chosen, total.value, trace
 
 
 def read_chain(statements, chosen, tensor):

@@ -119,3 +119,37 @@ def test_lean_materialized_path(gpu, name, make, copies, appends):
         qkv = tio.to_host_bits(dw.tensors["QKV"]).reshape(2, -1)
         kc = tio.to_host_bits(dw.tensors["Kcache"])
         assert np.array_equal(kc[:, :, S - 1, :].reshape(2, -1), qkv[:, 8 * 128:10 * 128])
+
+
+def test_store_direction_choices_of_concat_inputs_are_lowered(gpu):
+    """Config 1's Concat with its inputs made virtual tensors of its output (store direction,
+    Sec. 4.4): each input is written straight into its columns of V, no buffer of its own, and the
+    result is the oracle's, bit for bit, for every mix with read-direction choices upstream."""
+    vt, tio, pipelines, vtog, torch = gpu
+    wl = workloads.c1_tiny_chain(seed=5, a=3, b=8, c=40, lo=2, hi=20, ny=7)
+    ref = run_workload(wl)["out"].astype(np.float32)
+    g = vtog.build_vtog(list(wl.chain), tuple(wl.sources), ())
+    store_t3 = next(o for o in g.by_tensor["t3"] if o.direction == "store" and o.targets == ("V",))
+    read = {t: next(o for o in g.by_tensor[t] if o.direction == "read") for t in ("t1", "t2")}
+    dw = tio.DeviceWorkload(wl)
+    for upstream in ({}, {"t1": read["t1"]}, {"t2": read["t2"]}, dict(read)):
+        chosen = dict(upstream)
+        chosen["t3"] = store_t3
+        assert vtog.is_points_to_graph(g, chosen)
+        p = pipelines.StrategyPipeline(dw, chosen)
+        assert "t3" not in p.bufs and "V" in p.bufs            # t3 lives inside V
+        assert sum(isinstance(c[2], vt.Desc) for c in p.copies) == 2     # two stores into V: t3's part and Y's
+        p.run()
+        torch.cuda.synchronize()
+        assert np.array_equal(p.out.cpu().numpy(), ref), sorted(chosen)
+    # the append of the decode chain as a store: the new K/V row is written into the concatenated tensor
+    wl = workloads.c2_decode_attention(seed=6, B=2, Hkv=2, G=4, S=130, D=128)
+    g = vtog.build_vtog(list(wl.chain), tuple(wl.sources), ())
+    chosen = {t: next(o for o in g.by_tensor[t] if o.direction == "read") for t in g.by_tensor if t not in ("kn", "vn", "kf", "vf")}
+    for t, c in (("kn", "kf"), ("vn", "vf")):
+        chosen[t] = next(o for o in g.by_tensor[t] if o.direction == "store" and o.targets == (c,))
+    assert vtog.is_points_to_graph(g, chosen)
+    p = pipelines.StrategyPipeline(tio.DeviceWorkload(wl), chosen)
+    p.run()
+    torch.cuda.synchronize()
+    assert np.max(np.abs(tio.to_host_f64(p.out) - run_workload(wl)["out"])) <= 2e-3

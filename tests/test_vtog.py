@@ -110,10 +110,10 @@ def test_greedy_is_valid_and_never_beats_exhaustive_search(seed):
 
 
 def test_greedy_finds_the_optimum_on_most_random_graphs():
-    """Greedy is a heuristic (Sec. 5.2: it stops at the first negative maximum and never revisits a
-    choice), so it misses optima that need a losing step first; on these small graphs with
-    additive savings it still reaches the exhaustive optimum on close to half of them (28 of 60
-    when written).  A search that gives up early, or takes bundles in a wrong order, shows here."""
+    """Greedy is a heuristic (Sec. 5.2: it never revisits a choice), so it misses optima that need
+    a losing step first; on these small graphs with additive savings it still reaches the
+    exhaustive optimum on most of them (39 of 60 when written).  A search that gives up early, or
+    takes bundles in a wrong order, shows here."""
     hits = positive = 0
     for seed in range(60):
         stmts, gin, gout = random_graph(seed)
@@ -125,7 +125,7 @@ def test_greedy_finds_the_optimum_on_most_random_graphs():
         positive += best_s > 0
         hits += best_s > 0 and abs(total - best_s) < 1e-12
     print("greedy optimal on %d of %d graphs with a positive optimum" % (hits, positive))
-    assert positive >= 40 and hits >= 24
+    assert positive >= 40 and hits >= 34
 
 
 @pytest.mark.parametrize("seed", range(20))
@@ -140,11 +140,10 @@ def test_greedy_is_optimal_on_chains(seed):
     chosen, total, _ = vtog.greedy(g, lambda o, c: weight[o.tensor])
     saving = lambda c: sum(weight[t] for t in c)                      # noqa: E731
     best, best_s, _ = strategy_search.best_strategy(bundles_of(g), saving)
-    # greedy stops at the first negative maximum; on a chain every tensor becomes eligible in order
-    # from the input, so it may stop before a later positive one: it is optimal when savings are all positive
-    assert total <= best_s + 1e-12
-    if all(v > 0 for v in weight.values()):
-        assert abs(total - best_s) < 1e-12 and len(chosen) == n
+    # a bundle that loses time is left out (its tensor is anchored as a physical one) and the search
+    # goes on behind it: on a chain with additive savings that is the optimum
+    assert abs(total - best_s) < 1e-12
+    assert set(chosen) == {t for t, v in weight.items() if v >= 0}
 
 
 def test_exhaustive_search_counts_strategies_of_a_known_case():
@@ -167,3 +166,84 @@ def test_read_chain_extraction():
     assert [s[0] for s in chain] == ["a", "b", "c"] and sources == ["X"]
     chain, sources = vtog.read_chain(stmts, {}, "c")
     assert chain == [] and sources == ["c"]
+
+
+# Fig. 6 (conflicting edges): c = Concat(a, b) is read by a Reshape.  c can be a virtual tensor of
+# a AND b together (edges 1 and 2: one bundle), or of d (edge 3), never both.
+FIG6 = [
+    ("a", "conv", ("x",), {}),
+    ("b", "conv", ("y",), {}),
+    ("c", "concat", ("a", "b"), {"dim": 1}),
+    ("d", "reshape", ("c",), {"shape": (4, 4)}),
+    ("z", "matmul", ("d", "w"), {}),
+]
+
+
+def test_fig6_conflicting_edges():
+    g = vtog.build_vtog(FIG6, ("x", "y", "w"), ("z",))
+    assert sorted(o.targets for o in g.by_tensor["c"]) == [("a", "b"), ("d",)]
+    both, into_d = sorted(g.by_tensor["c"], key=lambda o: o.targets)
+    assert both.direction == "read" and into_d.direction == "store"
+    # edges 1 and 2 together, or edge 3 alone, are strategies; a tensor holds one bundle, so 1 and 3 cannot be combined
+    assert vtog.is_points_to_graph(g, {"c": both}) and vtog.is_points_to_graph(g, {"c": into_d})
+    assert {"c"} == {t for t, opps in g.by_tensor.items() if len({o.targets for o in opps}) > 1 and t == "c"}
+    # c inside d while d reads c back: nobody holds the data
+    d_of_c = next(o for o in g.by_tensor["d"] if o.targets == ("c",))
+    assert not vtog.is_points_to_graph(g, {"c": into_d, "d": d_of_c})
+    assert not strategy_search.valid({"c": ("d",), "d": ("c",)})
+    # a bundle that belongs to another tensor is not a choice for c
+    assert not vtog.is_points_to_graph(g, {"c": d_of_c})
+
+
+# Sec. 7 case study, the C3K2 block of YOLOv11: a convolution's output is split in two, one half
+# runs through a bottleneck, and both halves and the bottleneck's result are concatenated.
+C3K2 = [
+    ("a", "conv", ("X", "w1"), {}),
+    (("b", "c"), "split", ("a",), {"dim": 1, "sizes": (16, 16)}),
+    ("d", "conv", ("c", "w2"), {}),
+    ("e", "swish_add", ("d", "c"), {}),
+    ("Y", "concat", ("b", "c", "e"), {"dim": 1}),
+    ("Z", "conv", ("Y", "w3"), {}),
+]
+C3K2_IN, C3K2_OUT = ("X", "w1", "w2", "w3"), ("Z",)
+
+
+def test_c3k2_block_every_tensor_of_split_and_concat_lives_in_y():
+    """The paper's strategy: a, b, c and e are virtual tensors of Y (the Split and the Concat are
+    both eliminated, only Y is allocated).  It is a points-to graph of the opportunity graph, greedy
+    finds it when every eliminated copy saves time, and no strategy saves more."""
+    g = vtog.build_vtog(C3K2, C3K2_IN, C3K2_OUT)
+    pick = lambda t, targets: next(o for o in g.by_tensor[t] if o.targets == targets)   # noqa: E731
+    paper = {"a": pick("a", ("b", "c")), "b": pick("b", ("Y",)), "c": pick("c", ("Y",)), "e": pick("e", ("Y",))}
+    assert all(o.direction == "store" for o in paper.values())
+    assert vtog.is_points_to_graph(g, paper)
+    # d is produced and consumed by compute operators: no opportunity; Y could also read its inputs
+    assert "d" not in g.by_tensor and pick("Y", ("b", "c", "e")).direction == "read"
+    # everything the strategy makes virtual ends in Y
+    def root(t):
+        return {t} if t not in paper else set().union(*[root(x) for x in paper[t].targets])
+    assert all(root(t) == {"Y"} for t in paper)
+    # savings: bytes a copy kernel would move for the eliminated operator's share (a: 32 channels, b, c, e: 16 each);
+    # reading Y through its inputs saves the same Concat but leaves three tensors allocated, so it is worth less here
+    gain = {("a", ("b", "c")): 32.0, ("b", ("Y",)): 16.0, ("c", ("Y",)): 16.0, ("e", ("Y",)): 16.0,
+            ("b", ("a",)): 8.0, ("c", ("a",)): 8.0, ("Y", ("b", "c", "e")): 24.0}
+    chosen, total, trace = vtog.greedy(g, lambda o, c: gain[(o.tensor, o.targets)])
+    assert {t: o.targets for t, o in chosen.items()} == {t: o.targets for t, o in paper.items()}
+    assert total == 80.0 and [o.tensor for o, _ in trace][-1] == "a"        # a joins last: b and c must be anchored first
+    best, best_s, n = strategy_search.best_strategy(bundles_of(g), lambda c: sum(gain[(t, tg)] for t, tg in c.items()))
+    assert best_s == 80.0 and best == {t: o.targets for t, o in paper.items()} and n > 10
+
+
+def test_vtog_library_rejects_bad_graphs():
+    import ctypes as C
+    from paper_2604_09558_amd import binding
+    L = binding.lib()
+    assert L.vt_vtog_build(None, 0, 0, None, 3, None) == binding.ERR_INVALID_ARG
+    st = (binding.VtGraphStmt * 1)()
+    st[0].kind, st[0].n_in, st[0].n_out = binding.OP_KINDS["reshape"], 1, 1
+    st[0].in_[0], st[0].out[0] = 0, 5                      # tensor 5 of a graph with 2 tensors
+    h = C.c_void_p()
+    pinned = (C.c_uint8 * 2)(0, 0)
+    assert L.vt_vtog_build(st, 1, 2, pinned, 3, C.byref(h)) == binding.ERR_INVALID_ARG
+    assert b"outside the graph" in L.vt_last_error()
+    assert L.vt_vtog_build(st, 1, 2, pinned, 0, C.byref(h)) == binding.ERR_INVALID_ARG
