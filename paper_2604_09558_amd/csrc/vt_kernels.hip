@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 
 #include "vt_device.h"
 #include "vt_numeric.h"
@@ -69,35 +70,71 @@ __global__ void __launch_bounds__(256) k_copy_blocks(const DevDesc S, const DevD
   const uint32_t n_here = min(rb, inner_blocks - first);
   const uint32_t sub = lane / BL, c16 = (lane % BL) * 16u;
   const uint32_t iters = (n_here + G - 1) / G;
+  // the address of block `blk` of this round, from the lane that applied the map to it
+  auto addr_of = [&](uint64_t mine, uint32_t blk) -> uint64_t {
+    if (BL == 64) {                                  // one block per instruction: a wave-uniform address
+      const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)mine, (int)blk), hi = __builtin_amdgcn_readlane((uint32_t)(mine >> 32), (int)blk);
+      return ((uint64_t)hi << 32) | lo;
+    }
+    return shfl_u64(mine, (int)min(blk, 63u));
+  };
   for (uint32_t o = blockIdx.y; o < outer; o += gridDim.y) {
     const uint32_t mine = first + min(lane, n_here - 1);
     int64_t off;
     const void* ptr;
     vtd_eval(S, o, mine * block_elems, &off, &ptr);
     const uint64_t src_addr = reinterpret_cast<uint64_t>(ptr) + (uint64_t)(off * S.elem_size);
-    uint64_t dst_addr;
+    uint64_t dst_addr = 0;
     if (SCATTER) {
       vtd_eval(D, o, mine * block_elems, &off, &ptr);
       dst_addr = reinterpret_cast<uint64_t>(ptr) + (uint64_t)(off * D.elem_size);
-    } else {
-      dst_addr = reinterpret_cast<uint64_t>(dst) + ((uint64_t)o * inner_blocks + mine) * (uint64_t)(BL * 16);
     }
-    for (uint32_t j0 = 0; j0 < iters; j0 += 8) {
-      uint4 v[8];
+    // dense destination: block b of the round sits at a fixed distance from the round's first block
+    const uint64_t dense0 = reinterpret_cast<uint64_t>(dst) + ((uint64_t)o * inner_blocks + first) * (uint64_t)(BL * 16) + c16;
+    uint32_t j0 = 0;
+    // whole batches of sixteen instructions, nothing to guard: sixteen loads in flight, then their stores
+    for (; j0 + 16 <= iters && (j0 + 16) * G <= n_here; j0 += 16) {
+      uint4 v[16];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < 16; ++u) v[u] = *reinterpret_cast<const uint4*>(addr_of(src_addr, (j0 + u) * G + sub) + c16);
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
         const uint32_t blk = (j0 + u) * G + sub;
-        const uint64_t a = shfl_u64(src_addr, (int)min(blk, 63u));
-        if (j0 + u < iters && blk < n_here) v[u] = *reinterpret_cast<const uint4*>(a + c16);
+        const uint64_t a = SCATTER ? addr_of(dst_addr, blk) + c16 : dense0 + (uint64_t)blk * (BL * 16);
+        *reinterpret_cast<uint4*>(a) = v[u];
+      }
+    }
+    for (; j0 < iters; j0 += 4) {                     // the remainder, four at a time, guarded
+      uint4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const uint32_t blk = (j0 + u) * G + sub;
+        const uint64_t a = addr_of(src_addr, min(blk, n_here - 1)) + c16;
+        if (blk < n_here) v[u] = *reinterpret_cast<const uint4*>(a);
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < 4; ++u) {
         const uint32_t blk = (j0 + u) * G + sub;
-        const uint64_t a = shfl_u64(dst_addr, (int)min(blk, 63u));
-        if (j0 + u < iters && blk < n_here) *reinterpret_cast<uint4*>(a + c16) = v[u];
+        const uint64_t a = SCATTER ? addr_of(dst_addr, min(blk, n_here - 1)) + c16 : dense0 + (uint64_t)blk * (BL * 16);
+        if (blk < n_here) *reinterpret_cast<uint4*>(a) = v[u];
       }
     }
   }
+}
+
+// A map that is one contiguous range of one source (Def. 5 with minimal contiguous dimension 1:
+// a Reshape, a Slice or Split along the outermost dim, ...): a plain vector copy, no index work.
+__global__ void __launch_bounds__(256) k_copy_flat(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n_vec) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  for (; i + 3 * stride < n_vec; i += 4 * stride) {
+    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    dst[i] = a;
+    dst[i + stride] = b;
+    dst[i + 2 * stride] = c;
+    dst[i + 3 * stride] = d;
+  }
+  for (; i < n_vec; i += stride) dst[i] = src[i];
 }
 
 // Picks the block size and launches k_copy_blocks; returns false if the maps allow no block of
@@ -113,9 +150,12 @@ static bool launch_copy_blocks(const vt_desc& s, const vt_desc* d, const DevDesc
   if (bl < 2) return false;
   const int64_t blocks = inner / be;
   if (blocks >= (1ll << 31)) return false;
-  // blocks per wave and round: as many as keep about 4096 waves busy, at least one instruction's worth
-  uint32_t rb = 64;
-  while (rb > (uint32_t)(64 / bl) && blocks / rb < 4096) rb >>= 1;
+  // blocks per wave: sixteen instructions' worth (the map is then applied once per 16 KB at most),
+  // fewer while that leaves less than about 16384 waves (two full rounds of the chip), never
+  // less than one instruction's worth
+  const uint32_t want_waves = 16384;
+  uint32_t rb = std::min<uint32_t>(64, 16 * (64 / bl));
+  while (rb > (uint32_t)(64 / bl) && blocks / rb < want_waves) rb >>= 1;
   const int64_t waves = (blocks + rb - 1) / rb;
   dim3 grid((unsigned)((waves + 3) / 4), (unsigned)std::min<int64_t>(outer, 65535));
 #define VT_COPY_BLOCKS(BLV)                                                                                         \
@@ -171,6 +211,24 @@ static int launch_materialize(const vt_desc& d, void* dst, hipStream_t stream) {
   int64_t outer, inner;
   int rc = to_device(d, &D, &outer, &inner);
   if (rc != VT_OK) return rc;
+  {
+    int64_t numel = 1;
+    for (int64_t e : d.shape) numel *= e;
+    const int64_t bytes_total = numel * dtype_size(d.dtype);
+    if (d.pieces.size() == 1 && d.run >= numel && bytes_total % 16 == 0 && (uintptr_t)dst % 16 == 0) {
+      const Piece& p = d.pieces[0];
+      int64_t base = p.v.base;
+      for (const Stage& st : p.v.lower) base = st.base + base;     // a fully contiguous piece: stages only add their bases
+      const char* src = static_cast<const char*>(d.sources[p.src].ptr) + base * dtype_size(d.dtype);
+      if ((uintptr_t)src % 16 == 0 && p.v.lower.empty()) {
+        const size_t n_vec = (size_t)(bytes_total / 16);
+        const unsigned blocks = (unsigned)std::min<size_t>((n_vec + 1023) / 1024, 1u << 20);
+        hipLaunchKernelGGL(k_copy_flat, dim3(std::max(1u, blocks)), dim3(256), 0, stream, reinterpret_cast<const uint4*>(src),
+                           reinterpret_cast<uint4*>(dst), n_vec);
+        return check_launch("vt_materialize");
+      }
+    }
+  }
   if (launch_copy_blocks(d, nullptr, D, D, dst, outer, inner, stream)) return check_launch("vt_materialize");
   int vec = vector_width(d);
   if ((uintptr_t)dst % 16) vec = 1;
