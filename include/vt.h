@@ -191,13 +191,15 @@ int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* const* C, in
 
 /* Split-K flash-decoding attention with grouped queries (Sec. 3.1: the attention kernel
  * reads the un-expanded cache).  Q virtual [B,Hq,1,D], K and V virtual [B,Hq,S,D]
- * (f16/bf16, D = 128).  out dense [B,Hq,D], same dtype, 8-byte aligned.  softmax(scale * q.k) in fp32.
+ * (f16/bf16; the planned kernel is built for D = 128).  out dense [B,Hq,D], same dtype, 8-byte aligned.  softmax(scale * q.k) in fp32.
  * Query heads whose K/V rows coincide (a broadcast digit in the map) share one read.
  * K and V may be split into pieces along the context (Concat), and a piece may reach its rows
  * through a page table: an index_select over a pool of pages of 32 k rows, in context order
  * after the usual reshape / permute (a paged KV cache); the kernel then looks up the page of
- * every 32-row tile.  Other maps (more than two index stages, tables elsewhere, rows that are
- * not contiguous along D) give VT_ERR_UNSUPPORTED.
+ * every 32-row tile.  Anything else that a descriptor can hold (another head dim up to 1024, more
+ * index stages, tables elsewhere, rows that are not contiguous along D, pieces along other dims)
+ * runs on a generic kernel that applies the whole map per element: same result to rounding,
+ * far slower, no context splits; vt_decode_attn_plan reports VT_ERR_UNSUPPORTED for such operands.
  * workspace: device pointer (16-byte aligned) of at least vt_decode_attn_workspace(...) bytes,
  * holding arrival counters and the per-split partial results, prepared once with
  * vt_decode_attn_workspace_init; the split that finishes last for a (batch, kv head) merges

@@ -563,6 +563,76 @@ k_decode_attn(const AttnParams P) {
 #endif
 }
 
+// ------------------------------------------------------------------------------------------
+// The same attention for ANY maps the descriptors can hold and any head dim (tables anywhere,
+// stacked index stages, pieces along any dim, rows that are not contiguous): every element of Q,
+// K and V is found through the generic evaluator.  One workgroup per (batch, query head) walks the
+// context in chunks of 256 keys with a running maximum and sum (fp32); thread t scores key t of
+// the chunk, then thread d accumulates output column d.  Correct for every representable chain,
+// and slow: the kernel above takes over whenever the maps have the form it plans for.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) k_decode_attn_generic(const DevDesc Q, const DevDesc K, const DevDesc V, T* __restrict__ out,
+                                                             float* __restrict__ lse, int Hq, int S, int D, float scale) {
+  __shared__ float p_sh[256];
+  __shared__ float red[256];
+  const int h = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
+  const uint32_t q_lin = (uint32_t)(b * Hq + h) * (uint32_t)D;              // [B,Hq,1,D]
+  const uint32_t kv_lin = (uint32_t)(b * Hq + h) * (uint32_t)S * (uint32_t)D;   // [B,Hq,S,D]
+  auto at = [](const DevDesc& X, uint32_t lin) {
+    int64_t off;
+    const void* ptr;
+    vtd_eval(X, 0, lin, &off, &ptr);
+    return to_float(static_cast<const T*>(ptr)[off]);
+  };
+  float m_run = -3.0e38f, l_run = 0.f;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};             // output columns t, t + 256, ... (D <= 1024)
+  for (int t0 = 0; t0 < S; t0 += 256) {
+    const int key = t0 + t;
+    float sc = -3.0e38f;
+    if (key < S) {
+      sc = 0.f;
+      for (int d = 0; d < D; ++d) sc += at(Q, q_lin + d) * at(K, kv_lin + (uint32_t)key * D + d);
+      sc *= scale;
+    }
+    red[t] = sc;
+    __syncthreads();
+    for (int w = 128; w >= 1; w >>= 1) {
+      if (t < w) red[t] = fmaxf(red[t], red[t + w]);
+      __syncthreads();
+    }
+    const float m_new = fmaxf(m_run, red[0]);
+    __syncthreads();
+    const float alpha = __expf(m_run - m_new), pv = key < S ? __expf(sc - m_new) : 0.f;
+    p_sh[t] = pv;
+    red[t] = pv;
+    __syncthreads();
+    for (int w = 128; w >= 1; w >>= 1) {
+      if (t < w) red[t] += red[t + w];
+      __syncthreads();
+    }
+    l_run = l_run * alpha + red[0];
+    m_run = m_new;
+    const int n_keys = min(256, S - t0);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int d = t + 256 * c;
+      if (d < D) {
+        float a = acc[c] * alpha;
+        for (int j = 0; j < n_keys; ++j) a += p_sh[j] * at(V, kv_lin + (uint32_t)(t0 + j) * D + d);
+        acc[c] = a;
+      }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const int d = t + 256 * c;
+    if (d < D) out[(size_t)(b * Hq + h) * D + d] = from_float<T>(acc[c] / l_run);
+  }
+  if (lse && t == 0) lse[b * Hq + h] = m_run + __logf(l_run);
+}
+
 __global__ void k_zero_words(uint32_t* p, size_t n) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0u;
@@ -934,6 +1004,21 @@ static int launch_attention(const vt_desc* Q, const vt_desc* K, const vt_desc* V
   if (!out || !workspace) return fail(VT_ERR_INVALID_ARG, std::string(who) + ": NULL argument");
   AttnParams P;
   int rc = plan_attention(Q, K, V, n_splits, P);
+  if (rc == VT_ERR_UNSUPPORTED) {
+    // maps or a head dim the planned kernel does not take: the generic kernel, if the shapes allow
+    const std::string why = vt_last_error();
+    const int64_t B = K->shape[0], Hq = K->shape[1], S = K->shape[2], D = K->shape[3];
+    DevDesc DQ, DK, DV;
+    int64_t o1, i1, o2, i2, o3, i3;
+    if (D > 1024 || B > 65535 || to_device(*Q, &DQ, &o1, &i1) != VT_OK || to_device(*K, &DK, &o2, &i2) != VT_OK ||
+        to_device(*V, &DV, &o3, &i3) != VT_OK || o1 != 1 || o2 != 1 || o3 != 1)
+      return fail(VT_ERR_UNSUPPORTED, why);
+    hipStream_t gs = (hipStream_t)stream;
+    dim3 grid((unsigned)Hq, (unsigned)B);
+    if (Q->dtype == VT_BF16) hipLaunchKernelGGL((k_decode_attn_generic<bf16_t>), grid, dim3(256), 0, gs, DQ, DK, DV, (bf16_t*)out, lse, (int)Hq, (int)S, (int)D, scale);
+    else hipLaunchKernelGGL((k_decode_attn_generic<f16_t>), grid, dim3(256), 0, gs, DQ, DK, DV, (f16_t*)out, lse, (int)Hq, (int)S, (int)D, scale);
+    return check_launch(who);
+  }
   if (rc != VT_OK) return rc;
   const int64_t B = P.B, Hq = (int64_t)P.Hkv * P.G;
   const int ns_eff = P.n_splits, Hkv = P.Hkv;

@@ -23,9 +23,15 @@
 
 #include "vt_coherent.h"
 #include "vt_gemm_common.h"
+#include "vt_profile.h"
 
 using namespace vt;
 using namespace vt::gemm;
+
+// profile marks: 0 start, 1 first tile multiplied, 2 tile loop done, 3 partial sums stored, 4 ticket taken,
+// 5 mapped store done, 7 compute die
+VT_PROF_DECLARE(gemm_store)
+#define STORE_WG (blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z))
 
 namespace vt {
 int gemm_store_launch(const vt_desc& A, const vt_desc& B, const vt_desc& Cd, hipStream_t st);   // vt_gemm.hip
@@ -98,6 +104,8 @@ __global__ void __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_e
   __shared__ __attribute__((aligned(16))) float red[kWaves][kBM * kBN];     // 32 KB
   __shared__ uint32_t ticket_sh;
 
+  VT_PROF_BEGIN();
+  VT_PROF(0);
   const int split = blockIdx.x, cb = blockIdx.y, rb = blockIdx.z;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int l16 = lane & 15, lg = lane >> 4;
@@ -170,6 +178,7 @@ __global__ void __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_e
   for (int tile = wave; tile < n_tiles; tile += 3 * kWaves) {
     issue(tile + 2 * kWaves, S2{});
     multiply(S0{});
+    VT_PROF_ONCE(1);
     if (tile + kWaves >= n_tiles) break;
     issue(tile + 3 * kWaves, S0{});
     multiply(S1{});
@@ -184,6 +193,7 @@ __global__ void __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_e
 #pragma unroll
     for (int i = 0; i < 4; ++i) red[wave][l16 * kBN + (lg * 4 + i) * 8 + e] = acc[e][i];
   __syncthreads();
+  VT_PROF(2);
   const size_t blk = (size_t)rb * gridDim.y + cb;
   float* mine = P.partial + (blk * P.n_splits + split) * (kBM * kBN);
   const int n_valid = min(kBM, M - rb * kBM) * kBN;     // rows past M are neither summed nor stored
@@ -202,9 +212,14 @@ __global__ void __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_e
   // wraps to 0 at n_splits - 1, which leaves the counter ready for the next launch.
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
+  VT_PROF(3);
   if (threadIdx.x == 0) ticket_sh = atomicInc(&P.tickets[blk], (uint32_t)(P.n_splits - 1));
   __syncthreads();
-  if (ticket_sh != (uint32_t)(P.n_splits - 1)) return;
+  VT_PROF(4);
+  if (ticket_sh != (uint32_t)(P.n_splits - 1)) {
+    VT_PROF_FLUSH(gemm_store, STORE_WG);
+    return;
+  }
   const float* all = P.partial + blk * P.n_splits * (kBM * kBN);
   for (int idx = threadIdx.x * 4; idx < n_valid; idx += kWaves * 64 * 4) {
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -237,6 +252,11 @@ __global__ void __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_e
       *reinterpret_cast<T*>(o.base + off * 2) = from_float<T>(sv[c]);
     }
   }
+#ifdef VT_PROFILE
+  __builtin_amdgcn_s_waitcnt(0);
+  VT_PROF(5);
+  VT_PROF_FLUSH(gemm_store, STORE_WG);
+#endif
 }
 
 __global__ void k_zero_store_ws(uint32_t* p, size_t n) {

@@ -33,6 +33,7 @@ MARKS = {
     "attn": ["start", "first K tile staged", "tile loop done", "partial results stored", "ticket taken",
              "merge written", "merge loads landed"],
     "gemm": ["start", "first tiles in LDS", "K loop done", "tile stored"],
+    "gemm_store": ["start", "first tile multiplied", "tile loop done", "partial sums stored", "ticket taken", "mapped store done"],
 }
 
 
@@ -132,13 +133,40 @@ def trace_gemm(a):
         print("  shader cycle counter over the K loop: %.3f GHz median (%.3f .. %.3f)" % (np.median(ghz), ghz.min(), ghz.max()))
 
 
+def trace_gemm_store(a):
+    """The decode-step QKV projection [8,4096] x [4096,6144] with the producer-side store."""
+    import torch
+    import workloads
+    import paper_2604_09558_amd as vt
+    from paper_2604_09558_amd import pipelines, torch_io as tio
+    lib = vt.lib()
+    ps = [pipelines.GemmStore(tio.DeviceWorkload(workloads.qkv_proj_store(seed=s))) for s in range(4)]
+    n_wg = 4096
+    for p in ps:
+        p.run()
+    torch.cuda.synchronize()
+    read_marks(lib, "gemm_store", n_wg)
+    for rep in range(a.reps):
+        for p in (ps[2], ps[3], ps[0]):
+            p.run()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ps[1].run()
+        e1.record()
+        torch.cuda.synchronize()
+        t, rate = read_marks(lib, "gemm_store", n_wg)
+        live = t[:, 0] > 0
+        print("qkv projection store, %d workgroups, launch %d: %.1f us between events" % (int(live.sum()), rep, e0.elapsed_time(e1) * 1e3))
+        report("gemm_store", (t[live], rate))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("kernel", choices=sorted(MARKS))
     ap.add_argument("--n-splits", type=int, default=0)
     ap.add_argument("--reps", type=int, default=3)
     a = ap.parse_args()
-    {"attn": trace_attn, "gemm": trace_gemm}[a.kernel](a)
+    {"attn": trace_attn, "gemm": trace_gemm, "gemm_store": trace_gemm_store}[a.kernel](a)
 
 
 if __name__ == "__main__":

@@ -102,13 +102,48 @@ def test_decode_attention_full_size(gpu):
     assert np.max(np.abs(tio.to_host_f64(res["lse"]) - ref["lse"])) <= 1e-3
 
 
-def test_rejects_what_it_cannot_run(gpu):
+def test_other_head_dims_run_on_the_generic_kernel(gpu):
+    """Head dims other than 128 (and maps the planned kernel does not take) run on the generic
+    kernel, which finds every element through the whole map."""
     vt, tio, pipelines, torch = gpu
-    wl = workloads.c2_decode_attention(B=1, Hkv=1, G=2, S=8, D=64)
+    for D, S, G in ((64, 300, 2), (96, 70, 4), (256, 40, 1)):
+        wl = workloads.c2_decode_attention(seed=7, B=2, Hkv=2, G=G, S=S, D=D)
+        ref = run_workload(wl)
+        res = pipelines.run_decode_attention(tio.DeviceWorkload(wl))
+        check(tio.to_host_f64(res["out"]), ref["out"])
+        assert np.max(np.abs(tio.to_host_f64(res["lse"]) - ref["lse"])) <= 2e-3
+
+
+def test_maps_without_the_planned_form_run_on_the_generic_kernel(gpu):
+    """K stored feature-major (rows not contiguous along the head dim), V's context gathered
+    through a table in arbitrary order: still attention over the same virtual tensors."""
+    vt, tio, pipelines, torch = gpu
+    rng = np.random.default_rng(8)
+    B, H, S, D = 2, 3, 77, 128
+    q = workloads.encode(rng.normal(size=(B, H, 1, D)).astype(np.float32), "bf16")
+    kt = workloads.encode(rng.normal(size=(B, H, D, S)).astype(np.float32), "bf16")         # [.., D, S]
+    vpool = workloads.encode(rng.normal(size=(B, H, S + 5, D)).astype(np.float32), "bf16")
+    order = rng.permutation(S + 5)[:S].astype(np.int32)
+    chain = [("K", "permute", ("KT",), {"perm": (0, 1, 3, 2)}), ("V", "index_select", ("VP",), {"dim": 2, "index": "order"})]
+    wl = workloads.Workload("odd_maps", "bf16", {"Q": q, "KT": kt, "VP": vpool}, chain,
+                            {"kind": "decode_attn", "q": "Q", "k": "K", "v": "V", "scale": 1.0 / np.sqrt(D)}, {"order": order})
+    ref = run_workload(wl)
+    res = pipelines.run_decode_attention(tio.DeviceWorkload(wl))
+    check(tio.to_host_f64(res["out"]), ref["out"])
+    assert np.max(np.abs(tio.to_host_f64(res["lse"]) - ref["lse"])) <= 2e-3
+
+
+def test_rejects_bad_arguments(gpu):
+    vt, tio, pipelines, torch = gpu
+    wl = workloads.c2_decode_attention(B=1, Hkv=1, G=2, S=8, D=128)
     dw = tio.DeviceWorkload(wl)
+    p = pipelines.DecodeAttention(dw)
+    with pytest.raises(vt.VtError) as ei:         # K in the place of Q: shapes do not fit
+        vt.vt_decode_attn(p.k, p.k, p.v, p.scale, p.out, p.ws, p.ws_bytes)
+    assert ei.value.code == vt.ERR_SHAPE
     with pytest.raises(vt.VtError) as ei:
-        pipelines.run_decode_attention(dw)
-    assert ei.value.code == vt.ERR_UNSUPPORTED
+        vt.vt_decode_attn(p.q, p.k, p.v, p.scale, p.out, p.ws, 16)      # workspace too small
+    assert ei.value.code == vt.ERR_INVALID_ARG
 
 
 def test_repeated_launches_are_deterministic(gpu):
