@@ -182,8 +182,8 @@ int vt_weighted_sum(const vt_desc* x, const vt_desc* y, const float* weights, vo
  * kernel that applies the whole map per element: same results, far slower.
  * prologue = VT_GEMM_LAYERNORM applies per-row LayerNorm (gamma 1, beta 0, eps) over K to A,
  * rounded to the operand dtype, before the product, inside the load stage (the normalised
- * tensor is never stored).  The fused kernel takes K = 64 or 128, N <= 384, contiguous rows of
- * A; other shapes return VT_ERR_UNSUPPORTED (run vt_elementwise(LAYERNORM) + vt_gemm instead).
+ * tensor is never stored).  The fused kernel is built for K = 64 or 128, N <= 384 and contiguous
+ * rows of A; other shapes and maps run on the generic kernel with the same prologue (far slower).
  * A, B, C are host arrays of n_groups pointers. */
 typedef enum { VT_GEMM_PLAIN = 0, VT_GEMM_LAYERNORM = 1 } vt_gemm_prologue;
 int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* const* C, int n_groups,

@@ -401,8 +401,10 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P, const OutMap O
 // the tiled kernel above takes over whenever the maps have its separable form.
 // 64 x 64 tile per workgroup, one 32 x 32 block per wave, K in steps of 16.
 // ------------------------------------------------------------------------------------------
-template <typename T, bool C_F32>
-__global__ void __launch_bounds__(256) k_gemm_generic(const DevDesc A, const DevDesc B, void* __restrict__ Cout, int M, int N, int K) {
+// LN: per-row LayerNorm over K (gamma 1, beta 0, biased variance, fp32, two passes) applied to A,
+// rounded to the operand type, before the product.
+template <typename T, bool C_F32, bool LN>
+__global__ void __launch_bounds__(256) k_gemm_generic(const DevDesc A, const DevDesc B, void* __restrict__ Cout, int M, int N, int K, float eps) {
   typedef Mma<T> M_;
   typedef typename M_::vec opvec;
   __shared__ __attribute__((aligned(16))) T la[64][24];      // [row][k], 16 k used, pitch 48 bytes
@@ -413,6 +415,29 @@ __global__ void __launch_bounds__(256) k_gemm_generic(const DevDesc A, const Dev
   f32x16 acc;
 #pragma unroll
   for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  float mean = 0.f, rstd = 1.f;                      // of row t / 4 (the four threads of a row agree)
+  if (LN) {
+    const int m = min(m0 + (t >> 2), M - 1);
+    auto a_at = [&](int k) {
+      int64_t off;
+      const void* ptr;
+      vtd_eval(A, 0, (uint32_t)m * (uint32_t)K + (uint32_t)k, &off, &ptr);
+      return to_float(static_cast<const T*>(ptr)[off]);
+    };
+    float s1 = 0.f;
+    for (int k = t & 3; k < K; k += 4) s1 += a_at(k);
+    s1 += __shfl_xor(s1, 1, 64);
+    s1 += __shfl_xor(s1, 2, 64);
+    mean = s1 / (float)K;
+    float s2 = 0.f;
+    for (int k = t & 3; k < K; k += 4) {
+      const float dlt = a_at(k) - mean;
+      s2 += dlt * dlt;
+    }
+    s2 += __shfl_xor(s2, 1, 64);
+    s2 += __shfl_xor(s2, 2, 64);
+    rstd = 1.0f / sqrtf(s2 / (float)K + eps);
+  }
   for (int k0 = 0; k0 < K; k0 += 16) {
     {  // A: thread -> row t / 4, k = (t % 4) * 4 .. + 3
       const int r = t >> 2, m = min(m0 + r, M - 1);
@@ -425,6 +450,7 @@ __global__ void __launch_bounds__(256) k_gemm_generic(const DevDesc A, const Dev
           const void* ptr;
           vtd_eval(A, 0, (uint32_t)m * (uint32_t)K + (uint32_t)k, &off, &ptr);
           v = static_cast<const T*>(ptr)[off];
+          if (LN) v = from_float<T>((to_float(v) - mean) * rstd);
         }
         la[r][(t & 3) * 4 + i] = v;
       }
@@ -462,7 +488,10 @@ __global__ void __launch_bounds__(256) k_gemm_generic(const DevDesc A, const Dev
     }
 }
 
-int launch_generic(const vt_desc& a, const vt_desc& b, void* c, int c_dtype, hipStream_t st) {
+}  // namespace
+
+namespace vt {
+int launch_generic(const vt_desc& a, const vt_desc& b, void* c, int c_dtype, bool layernorm, float eps, hipStream_t st) {
   const int n = (int)a.shape.size();
   if (n < 2 || b.shape.size() != 2) return fail(VT_ERR_SHAPE, "vt_gemm: A must be [.., K] and B [K, N]");
   int64_t M = 1;
@@ -477,15 +506,24 @@ int launch_generic(const vt_desc& a, const vt_desc& b, void* c, int c_dtype, hip
   if (rc != VT_OK) return rc;
   if (oa != 1 || ob != 1 || M > 65535ll * 64 || N > 65535ll * 64) return fail(VT_ERR_UNSUPPORTED, "vt_gemm: operand too large for the generic path");
   dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64));
+#define VT_GENERIC(TT, CF)                                                                                          \
+  do {                                                                                                              \
+    if (layernorm) hipLaunchKernelGGL((k_gemm_generic<TT, CF, true>), grid, dim3(256), 0, st, DA, DB, c, (int)M, (int)N, (int)K, eps); \
+    else hipLaunchKernelGGL((k_gemm_generic<TT, CF, false>), grid, dim3(256), 0, st, DA, DB, c, (int)M, (int)N, (int)K, eps);          \
+  } while (0)
   if (a.dtype == VT_BF16) {
-    if (c_dtype == VT_F32) hipLaunchKernelGGL((k_gemm_generic<bf16_t, true>), grid, dim3(256), 0, st, DA, DB, c, (int)M, (int)N, (int)K);
-    else hipLaunchKernelGGL((k_gemm_generic<bf16_t, false>), grid, dim3(256), 0, st, DA, DB, c, (int)M, (int)N, (int)K);
+    if (c_dtype == VT_F32) VT_GENERIC(bf16_t, true);
+    else VT_GENERIC(bf16_t, false);
   } else {
-    if (c_dtype == VT_F32) hipLaunchKernelGGL((k_gemm_generic<f16_t, true>), grid, dim3(256), 0, st, DA, DB, c, (int)M, (int)N, (int)K);
-    else hipLaunchKernelGGL((k_gemm_generic<f16_t, false>), grid, dim3(256), 0, st, DA, DB, c, (int)M, (int)N, (int)K);
+    if (c_dtype == VT_F32) VT_GENERIC(f16_t, true);
+    else VT_GENERIC(f16_t, false);
   }
+#undef VT_GENERIC
   return check_launch("vt_gemm (generic maps)");
 }
+}  // namespace vt
+
+namespace {
 
 // Piece `pi` of A as one operand of its own: a Concat along the rows makes A a stack of pieces,
 // each of which is a range of rows [*row_begin, *row_begin + *M) of the product.
@@ -647,6 +685,8 @@ extern "C" int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* c
       if (!A[i] || !B[i] || !C[i]) return fail(VT_ERR_INVALID_ARG, "vt_gemm: NULL descriptor or output");
       if (A[i]->dtype != dt || B[i]->dtype != dt) return fail(VT_ERR_INVALID_ARG, "vt_gemm: mixed operand dtypes");
       int rc = ln_gemm_launch(*A[i], *B[i], C[i], c_dtype, eps, st);
+      // shapes or maps the fused kernel is not built for: the generic kernel with the same prologue
+      if (rc == VT_ERR_UNSUPPORTED) rc = launch_generic(*A[i], *B[i], C[i], c_dtype, true, eps, st);
       if (rc != VT_OK) return rc;
     }
     return VT_OK;
@@ -665,7 +705,7 @@ extern "C" int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* c
     }
     if (generic) {
       for (int i = 0; i < n_groups; ++i) {
-        int rc = launch_generic(*A[i], *B[i], C[i], c_dtype, st);
+        int rc = launch_generic(*A[i], *B[i], C[i], c_dtype, false, 0.f, st);
         if (rc != VT_OK) return rc;
       }
       return VT_OK;

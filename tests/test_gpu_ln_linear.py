@@ -106,3 +106,16 @@ def test_c4_one_full_round_plus_a_partial_one_and_f32_output(gpu):
     torch.cuda.synchronize()
     # no final rounding to fp16: only the fp16 rounding of the normalised rows remains
     check(out32.cpu().numpy().astype(np.float64).reshape(ref.shape), ref, atol=2e-3, rtol=2e-3)
+
+
+@pytest.mark.parametrize("B,R,win,C,N,dtype", [(1, 6, 3, 96, 200, "f16"), (1, 4, 2, 256, 520, "bf16"), (2, 6, 3, 40, 24, "f16")])
+def test_shapes_outside_the_fused_kernel_run_on_the_generic_one(gpu, B, R, win, C, N, dtype):
+    """Feature sizes other than 64 / 128 and more than 384 outputs: the LayerNorm prologue runs in
+    the generic kernel (whole map per element), same values to the same tolerance."""
+    vt, tio, pipelines, torch = gpu
+    wl = workloads.c4_window_ln_linear(seed=5, B=B, R=R, win=win, C=C, N=N, dtype=dtype)
+    ref = run_workload(wl)["out"]
+    p = pipelines.Gemm(tio.DeviceWorkload(wl), fused=True)
+    p.run()
+    torch.cuda.synchronize()
+    check(tio.to_host_f64(p.out).reshape(ref.shape), ref)
