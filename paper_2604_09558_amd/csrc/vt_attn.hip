@@ -97,7 +97,6 @@ struct AttnParams {
   const char* q_ptr;
   int64_t q_sb, q_sh;    // bytes
   int32_t B, Hkv, G, S, n_splits, rows_per_split;
-  int32_t unit_major;    // 1: 1-D grid, all splits of a (batch, kv head) unit on one compute die
   float scale_log2;      // softmax scale * log2(e)
   uint32_t* tickets;     // [B, Hkv], zero between launches
   float* ws_ml;          // [B, Hkv, n_splits, G, 2]
@@ -277,16 +276,7 @@ k_decode_attn(const AttnParams P) {
 
   VT_PROF_BEGIN();
   VT_PROF(0);
-  int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
-  if (P.unit_major) {
-    // workgroups go to the compute dies round-robin by linear id: die = id % 8.  Unit u runs on
-    // die u % 8, its splits one after the other in that die's share of the ids.
-    const int id = blockIdx.x, slot = id >> 3;
-    const int unit = (slot / P.n_splits) * 8 + (id & 7);
-    split = slot % P.n_splits;
-    g = unit % P.Hkv;
-    b = unit / P.Hkv;
-  }
+  const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int l16 = lane & 15, lg = lane >> 4;
   const int t_begin = split * P.rows_per_split;
@@ -1041,14 +1031,6 @@ static int launch_attention(const vt_desc* Q, const vt_desc* K, const vt_desc* V
     if (rc != VT_OK) return rc;
   }
   dim3 grid(ns_eff, Hkv, (unsigned)B);
-  static const int unit_major = [] {
-    const char* e = getenv("VT_ATTN_UNIT_MAJOR");
-    return e ? atoi(e) : 0;
-  }();
-  if (unit_major && (B * Hkv) % 8 == 0) {
-    P.unit_major = 1;
-    grid = dim3((unsigned)(ns_eff * Hkv * B), 1, 1);
-  }
   static const int occ = [] {
     const char* e = getenv("VT_ATTN_OCC");     // tuning knob: waves per SIMD the kernel is compiled for
     return e && atoi(e) == 2 ? 2 : 3;
