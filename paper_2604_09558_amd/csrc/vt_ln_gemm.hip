@@ -21,9 +21,15 @@
 #include <type_traits>
 
 #include "vt_gemm_common.h"
+#include "vt_profile.h"
 
 using namespace vt;
 using namespace vt::gemm;
+
+// profile marks (LDS writes: they are not among the vector memory operations the waits below count):
+// 0 start, 1 first two blocks requested, 2 W in registers, 3 first block multiplied, 4 last block
+// multiplied, 5 last stores issued, 6 all memory operations complete, 7 compute die
+VT_PROF_DECLARE(ln_gemm)
 
 namespace {
 
@@ -109,6 +115,8 @@ k_ln_gemm(const LnGemmParams P) {
   // result to the same place); multiplied.
   uint4* tiles = reinterpret_cast<uint4*>(lds_raw + kRegion0);
   char* cstage = lds_raw;
+  VT_PROF_BEGIN();
+  VT_PROF(0);
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int l16 = lane & 15, lg = lane >> 4;
@@ -166,6 +174,7 @@ k_ln_gemm(const LnGemmParams P) {
   eval_rows(0);
   load_rows(0, 0);
   load_rows(1, 1);
+  VT_PROF(1);
 
   // Memory operations a step issues after its row requests; together with the next step's requests
   // they are what may still be in flight when the rows requested one step earlier are needed
@@ -327,6 +336,7 @@ k_ln_gemm(const LnGemmParams P) {
     }
   };
 
+  VT_PROF(2);
   int it = 0, slot = 0;                               // block `it` is multiplied from tile `slot` = it % 3
   int64_t prev_row0 = 0, prev_end = 0;                // the block whose outputs wait in the staged C tile
   __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): the first two blocks' rows are in LDS
@@ -393,6 +403,7 @@ k_ln_gemm(const LnGemmParams P) {
       prev_row0 = row0;
       prev_end = r_end;
     }
+    VT_PROF_ONCE(3);
     const int nslot = slot == 2 ? 0 : slot + 1;
     if (it + 1 < n_it) {
       __builtin_amdgcn_s_waitcnt(kWaitRows);          // the rows requested one step ago have landed
@@ -401,11 +412,15 @@ k_ln_gemm(const LnGemmParams P) {
     slot = nslot;
     if (++it >= n_it) break;
   }
+  VT_PROF(4);
   if (!C_F32) {
     __syncthreads();                                  // the last staged C tile is complete
     store_block((it & 1) ^ 1, prev_row0, prev_end);
   }
+  VT_PROF(5);
   __builtin_amdgcn_s_waitcnt(0x0F70);                 // requests past the last block still target this workgroup's LDS
+  VT_PROF(6);
+  VT_PROF_FLUSH(ln_gemm, blockIdx.x);
 }
 
 template <typename T, bool C_F32>

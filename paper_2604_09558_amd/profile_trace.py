@@ -8,6 +8,8 @@ the compute dies compare.  The marks cost a little time: read the ordinary libra
 from rocprofv3, and the shape of the timeline from here.
 
     python -m paper_2604_09558_amd.profile_trace attn [--n-splits N] [--reps R]
+    python -m paper_2604_09558_amd.profile_trace gemm | gemm_store | ln_gemm
+    python -m paper_2604_09558_amd.profile_trace gemm_values     (k_gemm's duration and clock against the operand values)
 """
 from __future__ import annotations
 
@@ -34,6 +36,8 @@ MARKS = {
              "merge written", "merge loads landed"],
     "gemm": ["start", "first tiles in LDS", "K loop done", "tile stored"],
     "gemm_store": ["start", "first tile multiplied", "tile loop done", "partial sums stored", "ticket taken", "mapped store done"],
+    "ln_gemm": ["start", "first two blocks requested", "W in registers", "first block multiplied", "last block multiplied",
+                "last stores issued", "all memory operations complete"],
 }
 
 
@@ -133,6 +137,81 @@ def trace_gemm(a):
         print("  shader cycle counter over the K loop: %.3f GHz median (%.3f .. %.3f)" % (np.median(ghz), ghz.min(), ghz.max()))
 
 
+def trace_ln_gemm(a):
+    """Config 4 (window partition -> LayerNorm -> linear 128 -> 384, fp16): the persistent workgroups' phases."""
+    import torch
+    import workloads
+    import paper_2604_09558_amd as vt
+    from paper_2604_09558_amd import pipelines, torch_io as tio
+    lib = vt.lib()
+    ps = [pipelines.make_pipeline(tio.DeviceWorkload(workloads.c4_window_ln_linear(seed=s))) for s in range(4)]
+    n_wg = 256
+    for p in ps:
+        p.run()
+    torch.cuda.synchronize()
+    read_marks(lib, "ln_gemm", n_wg)
+    for rep in range(a.reps):
+        for p in (ps[2], ps[3], ps[0]):
+            p.run()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ps[1].run()
+        e1.record()
+        torch.cuda.synchronize()
+        print("config 4, %d workgroups, launch %d: %.1f us between events" % (n_wg, rep, e0.elapsed_time(e1) * 1e3))
+        t, rate = read_marks(lib, "ln_gemm", n_wg)
+        report("ln_gemm", (t, rate))
+        us = (t[:, :7] - t[:, 0:1].min()) / rate
+        seven = us[:, 4] > np.median(us[:, 4]) + 1.0
+        print("  workgroups with one more block: %d; their 'last block multiplied' median %.2f, the others' %.2f" % (
+            int(seven.sum()), np.median(us[seven, 4]) if seven.any() else float("nan"), np.median(us[~seven, 4])))
+
+
+def trace_gemm_values(a):
+    """Config 3's shape with dense operands of different VALUES: the matrix cores draw less power
+    on zeros than on random data, and the clock the chip grants follows.  Prints, per kind of data,
+    the duration of 20 back-to-back launches (three times), the shader clock over the K loop of the
+    last launch, and the duration of torch.matmul (the vendor library) on the same operands."""
+    import torch
+    import paper_2604_09558_amd as vt
+    lib = vt.lib()
+    M, K, N, n_wg = 8192, 4096, 4096, 512
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1)
+    zeros = lambda *s: torch.zeros(*s, dtype=torch.bfloat16, device="cuda")
+    normal = lambda *s: torch.randn(*s, generator=gen, device="cuda").to(torch.bfloat16)
+    c = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+
+    def timed(fn):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        out = []
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            out.append(e0.elapsed_time(e1) / 20 * 1e3)
+        return out
+
+    print("8192 x 4096 x 4096, bf16, dense operands; us per launch over 20 launches (three runs), marks included")
+    for name, a_, b_ in (("zeros", zeros(M, K), zeros(K, N)), ("ones", zeros(M, K) + 1, zeros(K, N) + 1),
+                         ("A normal, B zeros", normal(M, K), zeros(K, N)), ("normal", normal(M, K), normal(K, N))):
+        A = vt.build_chain([], {"A": ((M, K), "bf16", a_.data_ptr())}, "A")
+        B = vt.build_chain([], {"B": ((K, N), "bf16", b_.data_ptr())}, "B")
+        ts = timed(lambda: vt.vt_gemm([A], [B], [c], "bf16"))
+        t, rate = read_marks(lib, "gemm", n_wg)
+        ghz = (t[:, 5] - t[:, 4]) / ((t[:, 2] - t[:, 1]) / rate) / 1e3
+        ref = timed(lambda: torch.matmul(a_, b_, out=c))
+        flops = 2.0 * M * N * K
+        print("  %-18s k_gemm %s us (best %.0f TFLOP/s), K-loop clock %.3f GHz median | torch.matmul %s us (best %.0f TFLOP/s)" % (
+            name, " ".join("%.1f" % x for x in ts), flops / min(ts) / 1e6, np.median(ghz),
+            " ".join("%.1f" % x for x in ref), flops / min(ref) / 1e6), flush=True)
+
+
 def trace_gemm_store(a):
     """The decode-step QKV projection [8,4096] x [4096,6144] with the producer-side store."""
     import torch
@@ -162,11 +241,12 @@ def trace_gemm_store(a):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("kernel", choices=sorted(MARKS))
+    ap.add_argument("kernel", choices=sorted(MARKS) + ["gemm_values"])
     ap.add_argument("--n-splits", type=int, default=0)
     ap.add_argument("--reps", type=int, default=3)
     a = ap.parse_args()
-    {"attn": trace_attn, "gemm": trace_gemm, "gemm_store": trace_gemm_store}[a.kernel](a)
+    {"attn": trace_attn, "gemm": trace_gemm, "gemm_store": trace_gemm_store, "gemm_values": trace_gemm_values,
+     "ln_gemm": trace_ln_gemm}[a.kernel](a)
 
 
 if __name__ == "__main__":
