@@ -206,6 +206,9 @@ int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* const* C, in
  * the partial results inside the same launch, in split order: results are bitwise reproducible
  * from launch to launch.  n_splits = 0 lets the library choose.  lse (device, B*Hq floats,
  * may be NULL) receives the log-sum-exp of the scaled scores. */
+int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float scale, void* out,
+                   float* lse, void* workspace, size_t workspace_bytes, int n_splits, void* stream);
+
 /* What vt_decode_attn would decide for these operands, without launching anything (host only; the
  * sources need non-NULL, suitably aligned pointers but nothing is dereferenced): the number of
  * query heads served by one read of K/V, the context segments, the context splits, and how many
@@ -213,14 +216,15 @@ int vt_gemm(const vt_desc* const* A, const vt_desc* const* B, void* const* C, in
  * pointer may be NULL. */
 int vt_decode_attn_plan(const vt_desc* Q, const vt_desc* K, const vt_desc* V, int n_splits, int* group_size,
                         int* n_segments, int* splits, int* paged_segments);
+/* Bytes of workspace vt_decode_attn needs for this problem (S = context length: the number of
+ * splits the library picks for n_splits = 0, and with it the size of the partial results, depends
+ * on it).  Host only. */
 size_t vt_decode_attn_workspace(int B, int Hq, int D, int S, int n_splits);
 /* Clears a freshly allocated workspace (its first bytes hold one arrival counter per (batch,
  * kv head), which must be zero when vt_decode_attn starts and which vt_decode_attn leaves at
  * zero).  Call once after allocating, on the stream of the first vt_decode_attn, or clear
  * the buffer yourself.  Launches that share a workspace must not overlap in time. */
 int vt_decode_attn_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
-int vt_decode_attn(const vt_desc* Q, const vt_desc* K, const vt_desc* V, float scale, void* out,
-                   float* lse, void* workspace, size_t workspace_bytes, int n_splits, void* stream);
 
 /* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc): vt_decode_attn without the workspace argument.  The
