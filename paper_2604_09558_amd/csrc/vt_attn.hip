@@ -30,7 +30,6 @@
 
 #include <algorithm>
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <numeric>
@@ -1031,17 +1030,10 @@ static int launch_attention(const vt_desc* Q, const vt_desc* K, const vt_desc* V
     if (rc != VT_OK) return rc;
   }
   dim3 grid(ns_eff, Hkv, (unsigned)B);
-  static const int occ = [] {
-    const char* e = getenv("VT_ATTN_OCC");     // tuning knob: waves per SIMD the kernel is compiled for
-    return e && atoi(e) == 2 ? 2 : 3;
-  }();
-  if (Q->dtype == VT_BF16) {
-    if (occ == 2) hipLaunchKernelGGL((k_decode_attn<bf16_t, kWaves, 2>), grid, dim3(kWaves * 64), 0, st, P);
-    else hipLaunchKernelGGL((k_decode_attn<bf16_t, kWaves, 3>), grid, dim3(kWaves * 64), 0, st, P);
-  } else {
-    if (occ == 2) hipLaunchKernelGGL((k_decode_attn<f16_t, kWaves, 2>), grid, dim3(kWaves * 64), 0, st, P);
-    else hipLaunchKernelGGL((k_decode_attn<f16_t, kWaves, 3>), grid, dim3(kWaves * 64), 0, st, P);
-  }
+  // compiled for three waves per SIMD (two workgroups of four waves per compute unit and room for
+  // a third): measured faster than two on the benchmark's shape
+  if (Q->dtype == VT_BF16) hipLaunchKernelGGL((k_decode_attn<bf16_t, kWaves, 3>), grid, dim3(kWaves * 64), 0, st, P);
+  else hipLaunchKernelGGL((k_decode_attn<f16_t, kWaves, 3>), grid, dim3(kWaves * 64), 0, st, P);
   return check_launch(who);
 }
 

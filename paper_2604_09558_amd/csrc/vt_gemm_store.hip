@@ -17,7 +17,6 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
-#include <cstdlib>
 #include <cstring>
 #include <type_traits>
 
@@ -269,10 +268,7 @@ __global__ void k_zero_store_ws(uint32_t* p, size_t n) {
 // at least one tile per wave.
 int choose_k_splits(int64_t blocks, int64_t K) {
   const int64_t max_splits = std::max<int64_t>(1, K / (kTileK * kWaves));
-  static const int target = [] {
-    const char* e = getenv("VT_STORE_WGS");             // tuning knob: workgroups the launch aims for
-    return e && atoi(e) > 0 ? atoi(e) : 192;
-  }();
+  const int target = 192;
   const int64_t want = std::min<int64_t>(std::min(std::max<int64_t>(1, (target + blocks - 1) / blocks), max_splits), 64);
   int ns = 1;
   while (ns * 2 <= want) ns *= 2;
