@@ -88,38 +88,46 @@ def capture(torch, fns):
     return graph
 
 
+GRAPH_CAP = 512     # launches per HIP graph in the timed region
+
+
 def time_steps(torch, step_fns, steps, warmup, use_graph):
     """Warm-up, then EXACTLY `steps` calls of step_fns[k % R], bracketed by synchronize and by two
-    HIP events on the launch stream.  With use_graph the R step functions are one HIP graph and
-    the steps that do not fill a whole replay are a second, shorter graph: no step is launched
-    from Python.  Returns (wall ms per step, event ms per step)."""
+    HIP events on the launch stream.  With use_graph the timed region is replayed from HIP graphs
+    of up to GRAPH_CAP launches each (one graph for the default 400 steps), captured beforehand: no
+    step is launched from Python and a short run does not pay one graph launch per few steps.
+    Returns (wall ms per step, event ms per step)."""
     R = len(step_fns)
     stream = torch.cuda.current_stream()
-    full = part_w = part_s = None
-    if use_graph:
-        full = capture(torch, step_fns)
-        if warmup % R:
-            part_w = capture(torch, step_fns[:warmup % R])
-        if steps % R:
-            part_s = capture(torch, step_fns[:steps % R])
+    graphs = {}
 
-    def run(n, part):
-        if full is None:
+    def graph_of(n):
+        if n not in graphs:
+            graphs[n] = capture(torch, [step_fns[k % R] for k in range(n)])
+        return graphs[n]
+
+    def chunks(n):
+        return [GRAPH_CAP] * (n // GRAPH_CAP) + ([n % GRAPH_CAP] if n % GRAPH_CAP else [])
+
+    if use_graph:
+        for n in set(chunks(warmup) + chunks(steps)):
+            graph_of(n)
+
+    def run(n):
+        if not use_graph:
             for k in range(n):
                 step_fns[k % R](stream)
             return
-        for _ in range(n // R):
-            full.replay()
-        if part is not None:
-            part.replay()
+        for c in chunks(n):
+            graph_of(c).replay()
 
-    run(warmup, part_w)
+    run(warmup)
     torch.cuda.synchronize()
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record()
-    run(steps, part_s)
+    run(steps)
     e1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
