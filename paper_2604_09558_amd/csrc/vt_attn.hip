@@ -30,12 +30,14 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstddef>
 #include <cstring>
 #include <mutex>
 #include <numeric>
 #include <string>
 
 #include "vt_coherent.h"
+#include "vt_kernarg.h"
 #include "vt_device.h"
 #include "vt_numeric.h"
 #include "vt_profile.h"
@@ -80,15 +82,18 @@ struct PagedOperand {
   FastDiv W, page;       // elements per table entry; rows per page (a multiple of 32, or the whole segment)
 };
 
+// (what every tile walk reads comes first, in 72 bytes: two lines of the kernel arguments at most)
 struct AttnSeg {
-  const char* k;         // K element (b=0, g=0, t=t_lo, d=0); for a paged operand: element 0 of its source
-  const char* v;
-  PagedOperand kp, vp;
-  int64_t k_sb, k_sh, v_sb, v_sh;   // bytes per batch / per stored head
-  uint32_t k_st, v_st;              // bytes per context row
+  int32_t t_lo, t_hi;
+  int32_t paged;         // bit 0: K is paged in this segment, bit 1: V is
   int32_t k_hdiv, v_hdiv;           // head group g reads stored head g / hdiv (1 unless this operand is
                                     // broadcast over more heads than the group size G both operands share)
-  int32_t t_lo, t_hi;
+  uint32_t k_st, v_st;              // bytes per context row
+  int32_t pad;
+  const char* k;         // K element (b=0, g=0, t=t_lo, d=0); for a paged operand: element 0 of its source
+  const char* v;
+  int64_t k_sb, k_sh, v_sb, v_sh;   // bytes per batch / per stored head
+  PagedOperand kp, vp;
 };
 struct AttnParams {
   AttnSeg seg[kMaxSegs];
@@ -158,6 +163,7 @@ struct TileWalk {
   int r0, end;           // the tile: rows [r0, end), at most 32
   int seg_end;           // end of the tile's (first) segment, clipped to the split
   int seg;               // its (first) segment, P.n_seg when the walk is over
+  int paged;             // that segment's paged bits
   int cut, seg2;         // rows >= cut belong to segment seg2 (cut = INT_MAX, seg2 = -1: one segment only)
   const char* k2;        // K row `cut` of this (b, g) in segment seg2
   const char* v2;
@@ -192,8 +198,8 @@ __device__ __forceinline__ const char* paged_base(const PagedOperand& o, const c
 // the tile at w.r0 moved: paged operands look their page up again
 __device__ __forceinline__ void walk_locate(const AttnParams& P, TileWalk& w, int b, int g) {
   const AttnSeg& sg = P.seg[w.seg];
-  if (sg.kp.tab) w.k = paged_base(sg.kp, sg.k, sg.k_st, b, g / sg.k_hdiv, w.r0 - sg.t_lo);
-  if (sg.vp.tab) w.v = paged_base(sg.vp, sg.v, sg.v_st, b, g / sg.v_hdiv, w.r0 - sg.t_lo);
+  if (w.paged & 1) w.k = paged_base(sg.kp, sg.k, sg.k_st, b, g / sg.k_hdiv, w.r0 - sg.t_lo);
+  if (w.paged & 2) w.v = paged_base(sg.vp, sg.v, sg.v_st, b, g / sg.v_hdiv, w.r0 - sg.t_lo);
 }
 
 // The tile that starts at row r0 of segment seg (r0 inside the segment and the split).
@@ -203,12 +209,12 @@ __device__ __forceinline__ void walk_place(const AttnParams& P, TileWalk& w, int
   w.cut = 0x7fffffff;
   w.seg2 = -1;
   const int seg_end = min(P.seg[seg].t_hi, t_end);
+  w.paged = P.seg[seg].paged;
   w.seg_end = seg_end;
   w.end = min(r0 + kTile, seg_end);
   if (w.end < r0 + kTile && seg_end < t_end && seg + 1 < P.n_seg) {
-    const AttnSeg& A = P.seg[seg];
     const AttnSeg& B = P.seg[seg + 1];
-    if (!A.kp.tab && !A.vp.tab && !B.kp.tab && !B.vp.tab) {
+    if ((w.paged | B.paged) == 0) {
       w.cut = seg_end;
       w.seg2 = seg + 1;
       w.end = min(r0 + kTile, min(B.t_hi, t_end));
@@ -236,7 +242,7 @@ __device__ __forceinline__ void walk_fetch(const AttnParams& P, TileWalk& w, int
   w.k_st = sg.k_st;
   w.v_st = sg.v_st;
   w.t_lo = sg.t_lo;
-  if (sg.kp.tab || sg.vp.tab) walk_locate(P, w, b, g);
+  if (w.paged) walk_locate(P, w, b, g);
   if (w.seg2 >= 0) {
     const AttnSeg& s2 = P.seg[w.seg2];
     w.k2 = s2.k + b * s2.k_sb + (g / s2.k_hdiv) * s2.k_sh + (int64_t)(w.cut - s2.t_lo) * s2.k_st;
@@ -255,7 +261,7 @@ __device__ __forceinline__ void walk_advance(const AttnParams& P, TileWalk& w, i
     w.r0 += kTile * n;
     w.end = w.r0 + kTile;
     if (fetched) {                       // same segment: only a paged operand has to look its page up again
-      if (P.seg[w.seg].kp.tab || P.seg[w.seg].vp.tab) walk_locate(P, w, b, g);
+      if (w.paged) walk_locate(P, w, b, g);
       return;
     }
   } else {
@@ -273,6 +279,12 @@ k_decode_attn(const AttnParams P) {
   __shared__ float red_ml[WAVES * 16 * 2];   // [WAVES][16][2]
   __shared__ uint32_t ticket_sh;
 
+  // the tile walk below reads the segment table with data-dependent indices: have its first lines
+  // (three segments) and the scalars behind the table in the scalar cache before the chain of
+  // dependent reads starts
+  static_assert(offsetof(AttnParams, n_seg) >= 1024 && offsetof(AttnParams, n_seg) / 64 * 64 + 68 <= sizeof(AttnParams),
+                "the warmed lines lie inside the arguments");
+  warm_kernarg_16_and_2(offsetof(AttnParams, n_seg) / 64 * 64);
   VT_PROF_BEGIN();
   VT_PROF(0);
   const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
@@ -561,10 +573,18 @@ k_decode_attn(const AttnParams P) {
 // and slow: the kernel above takes over whenever the maps have the form it plans for.
 // ------------------------------------------------------------------------------------------
 template <typename T>
-__global__ void __launch_bounds__(256) k_decode_attn_generic(const DevDesc Q, const DevDesc K, const DevDesc V, T* __restrict__ out,
+__global__ void __launch_bounds__(256) k_decode_attn_generic(const DevDesc Q_, const DevDesc K_, const DevDesc V_, T* __restrict__ out,
                                                              float* __restrict__ lse, int Hq, int S, int D, float scale) {
   __shared__ float p_sh[256];
   __shared__ float red[256];
+  __shared__ DevDesc maps[3];                        // the evaluator reads the maps from LDS
+  {
+    const DevDesc* const from[3] = {&Q_, &K_, &V_};
+    stage_maps(maps, from);
+  }
+  const DevDesc& Q = maps[0];
+  const DevDesc& K = maps[1];
+  const DevDesc& V = maps[2];
   const int h = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
   const uint32_t q_lin = (uint32_t)(b * Hq + h) * (uint32_t)D;              // [B,Hq,1,D]
   const uint32_t kv_lin = (uint32_t)(b * Hq + h) * (uint32_t)S * (uint32_t)D;   // [B,Hq,S,D]
@@ -931,6 +951,7 @@ static int plan_attention(const vt_desc* Q, const vt_desc* K, const vt_desc* V, 
         PagedOperand& dst = which == 0 ? sg.kp : sg.vp;
         dst = pc.pg;
         if (!pc.pg.tab) continue;
+        sg.paged |= 1 << which;
         const int64_t rel = t - pc.t_lo;
         if (rel % pc.page_rows || t % kTile) return fail(VT_ERR_UNSUPPORTED, "vt_decode_attn: a paged operand's segment does not start on a page boundary");
         dst.L0 += rel / pc.page_rows * pc.pg.Lp;
@@ -979,7 +1000,7 @@ int vt_decode_attn_plan(const vt_desc* Q, const vt_desc* K, const vt_desc* V, in
   if (splits) *splits = P.n_splits;
   if (paged_segments) {
     *paged_segments = 0;
-    for (int i = 0; i < P.n_seg; ++i) *paged_segments += (P.seg[i].kp.tab || P.seg[i].vp.tab) ? 1 : 0;
+    for (int i = 0; i < P.n_seg; ++i) *paged_segments += P.seg[i].paged ? 1 : 0;
   }
   return VT_OK;
 }

@@ -121,6 +121,22 @@ __host__ __device__ __forceinline__ int vtd_eval(const DevDesc& D, uint32_t o, u
   return found;
 }
 
+#ifdef __HIPCC__
+// The evaluator walks a map with per-lane indices (which piece, which digits): read from the
+// kernel arguments every step of that walk is a dependent read of memory.  The kernels that
+// evaluate per lane copy their maps to LDS first, with one coalesced read.
+template <int N>
+__device__ __forceinline__ void stage_maps(DevDesc* dst, const DevDesc* const (&src)[N]) {
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    const uint32_t* s = reinterpret_cast<const uint32_t*>(src[k]);
+    uint32_t* d = reinterpret_cast<uint32_t*>(&dst[k]);
+    for (uint32_t i = threadIdx.x; i < sizeof(DevDesc) / 4; i += blockDim.x) d[i] = s[i];
+  }
+  __syncthreads();
+}
+#endif
+
 // Largest vector width (elements, a power of two, at most 16 bytes) with which aligned groups
 // of consecutive virtual elements can be moved as one access: it divides every piece's run,
 // every piece boundary and every offset at which a run can start, and the source pointers are

@@ -404,11 +404,18 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmParams P, const OutMap O
 // LN: per-row LayerNorm over K (gamma 1, beta 0, biased variance, fp32, two passes) applied to A,
 // rounded to the operand type, before the product.
 template <typename T, bool C_F32, bool LN>
-__global__ void __launch_bounds__(256) k_gemm_generic(const DevDesc A, const DevDesc B, void* __restrict__ Cout, int M, int N, int K, float eps) {
+__global__ void __launch_bounds__(256) k_gemm_generic(const DevDesc A_, const DevDesc B_, void* __restrict__ Cout, int M, int N, int K, float eps) {
   typedef Mma<T> M_;
   typedef typename M_::vec opvec;
   __shared__ __attribute__((aligned(16))) T la[64][24];      // [row][k], 16 k used, pitch 48 bytes
   __shared__ __attribute__((aligned(16))) T lb[64][24];      // [col][k]
+  __shared__ DevDesc maps[2];                                // the evaluator reads the maps from LDS
+  {
+    const DevDesc* const from[2] = {&A_, &B_};
+    stage_maps(maps, from);
+  }
+  const DevDesc& A = maps[0];
+  const DevDesc& B = maps[1];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, lh = lane >> 5;
   const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;

@@ -17,13 +17,19 @@ using namespace vt;
 template <typename V>
 __global__ void __launch_bounds__(256) k_materialize(const DevDesc D, V* __restrict__ dst, uint32_t inner_vecs,
                                                      uint32_t vec_elems, uint32_t outer) {
+  __shared__ DevDesc map[1];
+  {
+    const DevDesc* const from[1] = {&D};
+    stage_maps(map, from);
+  }
+  const DevDesc& M = map[0];
   uint32_t vi = blockIdx.x * 256u + threadIdx.x;
   if (vi >= inner_vecs) return;
   for (uint32_t o = blockIdx.y; o < outer; o += gridDim.y) {
     int64_t off;
     const void* ptr;
-    vtd_eval(D, o, vi * vec_elems, &off, &ptr);
-    const V* src = reinterpret_cast<const V*>(static_cast<const char*>(ptr) + off * D.elem_size);
+    vtd_eval(M, o, vi * vec_elems, &off, &ptr);
+    const V* src = reinterpret_cast<const V*>(static_cast<const char*>(ptr) + off * M.elem_size);
     dst[(size_t)o * inner_vecs + vi] = *src;
   }
 }
@@ -33,15 +39,20 @@ __global__ void __launch_bounds__(256) k_materialize(const DevDesc D, V* __restr
 template <typename V>
 __global__ void __launch_bounds__(256) k_scatter(const DevDesc S, const DevDesc D, uint32_t inner_vecs, uint32_t vec_elems,
                                                  uint32_t outer) {
+  __shared__ DevDesc maps[2];
+  {
+    const DevDesc* const from[2] = {&S, &D};
+    stage_maps(maps, from);
+  }
   uint32_t vi = blockIdx.x * 256u + threadIdx.x;
   if (vi >= inner_vecs) return;
   for (uint32_t o = blockIdx.y; o < outer; o += gridDim.y) {
     int64_t so, dof;
     const void *sp, *dp;
-    vtd_eval(S, o, vi * vec_elems, &so, &sp);
-    vtd_eval(D, o, vi * vec_elems, &dof, &dp);
-    *reinterpret_cast<V*>(static_cast<char*>(const_cast<void*>(dp)) + dof * D.elem_size) =
-        *reinterpret_cast<const V*>(static_cast<const char*>(sp) + so * S.elem_size);
+    vtd_eval(maps[0], o, vi * vec_elems, &so, &sp);
+    vtd_eval(maps[1], o, vi * vec_elems, &dof, &dp);
+    *reinterpret_cast<V*>(static_cast<char*>(const_cast<void*>(dp)) + dof * maps[1].elem_size) =
+        *reinterpret_cast<const V*>(static_cast<const char*>(sp) + so * maps[0].elem_size);
   }
 }
 
@@ -63,6 +74,22 @@ template <int BL, bool SCATTER>
 __global__ void __launch_bounds__(256) k_copy_blocks(const DevDesc S, const DevDesc D, char* __restrict__ dst,
                                                      uint32_t inner_blocks, uint32_t block_elems, uint32_t rb, uint32_t outer) {
   constexpr int G = 64 / BL;                         // blocks moved by one instruction
+  // Small blocks: the maps are evaluated often for the bytes moved, and are read from an LDS copy.
+  // Blocks of 1 KB: one evaluation moves a kilobyte, and the copy to LDS with its barrier costs
+  // more than it saves (measured on the gather of 28 KB rows: 10 % slower with it).
+  constexpr bool STAGE = BL < 64;
+  __shared__ DevDesc staged[STAGE ? (SCATTER ? 2 : 1) : 1];
+  if (STAGE) {
+    if (SCATTER) {
+      const DevDesc* const from[2] = {&S, &D};
+      stage_maps(reinterpret_cast<DevDesc*>(staged), from);
+    } else {
+      const DevDesc* const from[1] = {&S};
+      stage_maps(reinterpret_cast<DevDesc*>(staged), from);
+    }
+  }
+  const DevDesc& MS = STAGE ? staged[0] : S;
+  const DevDesc& MD = STAGE ? staged[SCATTER ? 1 : 0] : D;
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t wv = blockIdx.x * 4u + (threadIdx.x >> 6);
   const uint32_t first = wv * rb;                    // this wave's blocks: [first, first + rb)
@@ -82,12 +109,12 @@ __global__ void __launch_bounds__(256) k_copy_blocks(const DevDesc S, const DevD
     const uint32_t mine = first + min(lane, n_here - 1);
     int64_t off;
     const void* ptr;
-    vtd_eval(S, o, mine * block_elems, &off, &ptr);
-    const uint64_t src_addr = reinterpret_cast<uint64_t>(ptr) + (uint64_t)(off * S.elem_size);
+    vtd_eval(MS, o, mine * block_elems, &off, &ptr);
+    const uint64_t src_addr = reinterpret_cast<uint64_t>(ptr) + (uint64_t)(off * MS.elem_size);
     uint64_t dst_addr = 0;
     if (SCATTER) {
-      vtd_eval(D, o, mine * block_elems, &off, &ptr);
-      dst_addr = reinterpret_cast<uint64_t>(ptr) + (uint64_t)(off * D.elem_size);
+      vtd_eval(MD, o, mine * block_elems, &off, &ptr);
+      dst_addr = reinterpret_cast<uint64_t>(ptr) + (uint64_t)(off * MD.elem_size);
     }
     // dense destination: block b of the round sits at a fixed distance from the round's first block
     const uint64_t dense0 = reinterpret_cast<uint64_t>(dst) + ((uint64_t)o * inner_blocks + first) * (uint64_t)(BL * 16) + c16;
@@ -261,6 +288,11 @@ static int launch_materialize(const vt_desc& d, void* dst, hipStream_t stream) {
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_add_rowsum(const DevDesc X, const DevDesc Y, float* __restrict__ out,
                                                     uint32_t R, uint32_t C) {
+  __shared__ DevDesc maps[2];
+  {
+    const DevDesc* const src[2] = {&X, &Y};
+    stage_maps(maps, src);
+  }
   uint32_t lane = threadIdx.x & 63u;
   uint32_t row = blockIdx.x * 4u + (threadIdx.x >> 6);
   if (row >= R) return;
@@ -268,8 +300,8 @@ __global__ void __launch_bounds__(256) k_add_rowsum(const DevDesc X, const DevDe
   for (uint32_t c = lane; c < C; c += 64u) {
     int64_t ox, oy;
     const void *px, *py;
-    vtd_eval(X, 0, row * C + c, &ox, &px);
-    vtd_eval(Y, 0, row * C + c, &oy, &py);
+    vtd_eval(maps[0], 0, row * C + c, &ox, &px);
+    vtd_eval(maps[1], 0, row * C + c, &oy, &py);
     float t = static_cast<const float*>(px)[ox] + static_cast<const float*>(py)[oy];
     p = p + t;
   }
@@ -317,6 +349,11 @@ __device__ __forceinline__ float cursor_read_window(const BlockCursor& cur, uint
 template <bool WIDE>   // WIDE: both operands keep blocks of at least 64 columns
 __global__ void __launch_bounds__(256) k_add_rowsum_blocks(const DevDesc X, const DevDesc Y, float* __restrict__ out, uint32_t R,
                                                            uint32_t C, uint32_t bx, uint32_t by) {
+  __shared__ DevDesc maps[2];
+  {
+    const DevDesc* const src[2] = {&X, &Y};
+    stage_maps(maps, src);
+  }
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t row = blockIdx.x * 4u + (threadIdx.x >> 6);
   if (row >= R) return;
@@ -325,8 +362,8 @@ __global__ void __launch_bounds__(256) k_add_rowsum_blocks(const DevDesc X, cons
   float p = 0.0f;
   BlockCursor cx, cy;
   for (uint32_t c0 = 0; c0 < C;) {
-    if (c0 % span_x == 0) cursor_load(X, row, C, bx, c0 >> bx, lane, cx);
-    if (c0 % span_y == 0) cursor_load(Y, row, C, by, c0 >> by, lane, cy);
+    if (c0 % span_x == 0) cursor_load(maps[0], row, C, bx, c0 >> bx, lane, cx);
+    if (c0 % span_y == 0) cursor_load(maps[1], row, C, by, c0 >> by, lane, cy);
     const uint32_t end = min(C, min((c0 / span_x + 1) * span_x, (c0 / span_y + 1) * span_y));
     // whole windows of 64 columns, eight at a time so that sixteen loads are in flight per lane
     for (; c0 + 512 <= end; c0 += 512) {
@@ -357,6 +394,11 @@ __global__ void __launch_bounds__(256) k_add_rowsum_blocks(const DevDesc X, cons
 template <typename T, int VEC>
 __global__ void __launch_bounds__(256) k_layernorm(const DevDesc X, T* __restrict__ out, uint32_t rows, uint32_t C,
                                                    uint32_t lpr_log2, float eps, uint32_t outer, uint32_t rows_inner) {
+  __shared__ DevDesc map[1];
+  {
+    const DevDesc* const from[1] = {&X};
+    stage_maps(map, from);
+  }
   const uint32_t lpr = 1u << lpr_log2;
   const uint32_t rpw = 64u >> lpr_log2;                 // rows per wave
   const uint32_t lane = threadIdx.x & 63u;
@@ -375,7 +417,7 @@ __global__ void __launch_bounds__(256) k_layernorm(const DevDesc X, T* __restric
       uint32_t o = row / rows_inner, ri = row - o * rows_inner;
       int64_t off;
       const void* ptr;
-      vtd_eval(X, o, ri * C + j * VEC, &off, &ptr);
+      vtd_eval(map[0], o, ri * C + j * VEC, &off, &ptr);
       Vec<T, VEC> raw = *reinterpret_cast<const Vec<T, VEC>*>(static_cast<const T*>(ptr) + off);
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
