@@ -440,13 +440,25 @@ k_decode_attn(const AttnParams P) {
     if (more) issue_v(cur);              // next tile's V: lands while the next K tile is being scored
   }
 
+  // Everything the rest of the kernel needs from the arguments is fetched here, in one batch, and
+  // pinned in registers (the empty statement makes the values opaque, so they cannot be fetched
+  // again later): the steps below are a chain of round trips to memory, and a reload of a pointer
+  // from the argument segment in front of each of them would lengthen every link.
+  uint32_t* a_tickets = P.tickets;
+  float* a_ws_ml = P.ws_ml;
+  float* a_ws_o = P.ws_o;
+  T* a_out = static_cast<T*>(P.out);
+  float* a_lse = P.lse;
+  int a_G = P.G, a_ns = P.n_splits, a_Hkv = P.Hkv;
+  asm volatile("" : "+s"(a_tickets), "+s"(a_ws_ml), "+s"(a_ws_o), "+s"(a_out), "+s"(a_lse), "+s"(a_G), "+s"(a_ns), "+s"(a_Hkv));
+
   // ---- merge the waves of the workgroup through LDS, then write the split's partial result
   l_run += __shfl_xor(l_run, 16, 64);
   l_run += __shfl_xor(l_run, 32, 64);
   __syncthreads();                       // every wave is done with its K tile
   VT_PROF(2);
   float* red_o = reinterpret_cast<float*>(&lds[0][0]);    // [WAVES][G][D] floats: at most the K tiles' 32 KB
-  const int G = P.G;
+  const int G = a_G;
   if (l16 < G) {
 #pragma unroll
     for (int e = 0; e < 8; ++e)
@@ -458,8 +470,8 @@ k_decode_attn(const AttnParams P) {
     }
   }
   __syncthreads();
-  const int bg = b * P.Hkv + g;
-  const size_t unit = (size_t)bg * P.n_splits + split;
+  const int bg = b * a_Hkv + g;
+  const size_t unit = (size_t)bg * a_ns + split;
   // four consecutive d per thread; partial results go out as 16-byte device-coherent stores
   // (written through to where every compute die sees them), whole cache lines per wave
   for (int idx = threadIdx.x * 4; idx < G * kD; idx += WAVES * 64 * 4) {
@@ -476,10 +488,10 @@ k_decode_attn(const AttnParams P) {
       o.x += r.x * sc; o.y += r.y * sc; o.z += r.z * sc; o.w += r.w * sc;
       l += red_ml[(w * 16 + h) * 2 + 1] * sc;
     }
-    store_device_b128(&P.ws_o[unit * G * kD + idx], __builtin_bit_cast(u32x4_t, o));
+    store_device_b128(&a_ws_o[unit * G * kD + idx], __builtin_bit_cast(u32x4_t, o));
     if (idx == h * kD) {
-      __hip_atomic_store(&P.ws_ml[(unit * G + h) * 2 + 0], mx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(&P.ws_ml[(unit * G + h) * 2 + 1], l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&a_ws_ml[(unit * G + h) * 2 + 0], mx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&a_ws_ml[(unit * G + h) * 2 + 1], l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
 
@@ -491,16 +503,16 @@ k_decode_attn(const AttnParams P) {
   __builtin_amdgcn_s_waitcnt(0);         // this wave's stores have completed (vmcnt = 0)
   __syncthreads();
   VT_PROF(3);
-  if (threadIdx.x == 0) ticket_sh = atomicInc(&P.tickets[bg], (uint32_t)(P.n_splits - 1));
+  if (threadIdx.x == 0) ticket_sh = atomicInc(&a_tickets[bg], (uint32_t)(a_ns - 1));
   __syncthreads();
   VT_PROF(4);
-  if (ticket_sh != (uint32_t)(P.n_splits - 1)) {
+  if (ticket_sh != (uint32_t)(a_ns - 1)) {
     VT_PROF_FLUSH(attn, ATTN_WG);
     return;
   }
-  const size_t u0 = (size_t)bg * P.n_splits;
-  const int ns = P.n_splits;
-  T* out = static_cast<T*>(P.out);
+  const size_t u0 = (size_t)bg * a_ns;
+  const int ns = a_ns;
+  T* out = a_out;
   auto ld = [](const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
   // (m, l) of every split and head go to LDS (ns * G * 2 contiguous floats; the K tiles' LDS is
   // free now).  Each thread merges four consecutive d of one head; the first eight splits'
@@ -511,17 +523,17 @@ k_decode_attn(const AttnParams P) {
   const int h0 = min(idx0 / kD, G - 1), d0 = idx0 % kD;
   const int i_ml = threadIdx.x;                       // ns * G * 2 <= 256 * 32 ... a thread may own several
   float ml_first = 0.f;
-  if (i_ml < ns * G * 2) ml_first = ld(&P.ws_ml[u0 * G * 2 + i_ml]);
+  if (i_ml < ns * G * 2) ml_first = ld(&a_ws_ml[u0 * G * 2 + i_ml]);
   u32x4_t v0[8];
   {
     const void* q[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) q[u] = &P.ws_o[((u0 + min(u, ns - 1)) * G + h0) * kD + d0];
+    for (int u = 0; u < 8; ++u) q[u] = &a_ws_o[((u0 + min(u, ns - 1)) * G + h0) * kD + d0];
     load_device_8xb128(q, v0);
   }
   VT_PROF(6);
   if (i_ml < ns * G * 2) ml_sh[i_ml] = ml_first;
-  for (int i = i_ml + WAVES * 64; i < ns * G * 2; i += WAVES * 64) ml_sh[i] = ld(&P.ws_ml[u0 * G * 2 + i]);
+  for (int i = i_ml + WAVES * 64; i < ns * G * 2; i += WAVES * 64) ml_sh[i] = ld(&a_ws_ml[u0 * G * 2 + i]);
   __syncthreads();
   for (int idx = idx0; idx < G * kD; idx += WAVES * 64 * 4) {
     const int h = idx / kD, d = idx - h * kD;
@@ -537,7 +549,7 @@ k_decode_attn(const AttnParams P) {
       } else {
         const void* q[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) q[u] = &P.ws_o[((u0 + min(sp0 + u, ns - 1)) * G + h) * kD + d];
+        for (int u = 0; u < 8; ++u) q[u] = &a_ws_o[((u0 + min(sp0 + u, ns - 1)) * G + h) * kD + d];
         load_device_8xb128(q, v);
       }
 #pragma unroll
@@ -555,7 +567,7 @@ k_decode_attn(const AttnParams P) {
     r.v[0] = from_float<T>(o.x / l); r.v[1] = from_float<T>(o.y / l);
     r.v[2] = from_float<T>(o.z / l); r.v[3] = from_float<T>(o.w / l);
     *reinterpret_cast<Vec<T, 4>*>(&out[hq * kD + d]) = r;
-    if (P.lse && d == 0) P.lse[hq] = (mx + log2f(l)) * 0.6931471805599453f;
+    if (a_lse && d == 0) a_lse[hq] = (mx + log2f(l)) * 0.6931471805599453f;
   }
 #ifdef VT_PROFILE
   __builtin_amdgcn_s_waitcnt(0);

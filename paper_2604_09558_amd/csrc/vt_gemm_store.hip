@@ -102,6 +102,15 @@ __global__ void __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_e
   typedef typename M_::vec opvec;
   __shared__ __attribute__((aligned(16))) float red[kWaves][kBM * kBN];     // 32 KB
   __shared__ uint32_t ticket_sh;
+  // The output pieces' maps, copied from the arguments while the tiles stream: the store stage
+  // picks a piece per lane and evaluates its row and column maps, and read from the argument
+  // segment every step of that would be a dependent read of memory at the very end of the kernel.
+  __shared__ OutPiece out_sh[kMaxOutPieces];
+  {
+    const uint32_t* from = reinterpret_cast<const uint32_t*>(&P.out[0]);
+    uint32_t* to = reinterpret_cast<uint32_t*>(&out_sh[0]);
+    for (uint32_t i = threadIdx.x; i < sizeof(out_sh) / 4; i += kWaves * 64) to[i] = from[i];
+  }
 
   VT_PROF_BEGIN();
   VT_PROF(0);
@@ -186,6 +195,14 @@ __global__ void __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_e
     multiply(S2{});
   }
 
+  // what the rest of the kernel needs from the arguments, fetched in one batch and pinned in
+  // registers (the empty statement makes the values opaque, so they are not fetched again in
+  // front of each of the dependent steps below)
+  uint32_t* a_tickets = P.tickets;
+  float* a_partial = P.partial;
+  int a_ns = P.n_splits, a_nout = P.n_out;
+  asm volatile("" : "+s"(a_tickets), "+s"(a_partial), "+s"(a_ns), "+s"(a_nout));
+
   // ---- sum the waves through LDS.  acc[e][i] is C[m = l16][n = (lg*4 + i)*8 + e] of the block.
 #pragma unroll
   for (int e = 0; e < 8; ++e)
@@ -194,7 +211,7 @@ __global__ void __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_e
   __syncthreads();
   VT_PROF(2);
   const size_t blk = (size_t)rb * gridDim.y + cb;
-  float* mine = P.partial + (blk * P.n_splits + split) * (kBM * kBN);
+  float* mine = a_partial + (blk * a_ns + split) * (kBM * kBN);
   const int n_valid = min(kBM, M - rb * kBM) * kBN;     // rows past M are neither summed nor stored
   // four consecutive columns per thread: 16-byte device-coherent stores, whole lines per wave
   for (int idx = threadIdx.x * 4; idx < n_valid; idx += kWaves * 64 * 4) {
@@ -212,25 +229,25 @@ __global__ void __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_e
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
   VT_PROF(3);
-  if (threadIdx.x == 0) ticket_sh = atomicInc(&P.tickets[blk], (uint32_t)(P.n_splits - 1));
+  if (threadIdx.x == 0) ticket_sh = atomicInc(&a_tickets[blk], (uint32_t)(a_ns - 1));
   __syncthreads();
   VT_PROF(4);
-  if (ticket_sh != (uint32_t)(P.n_splits - 1)) {
+  if (ticket_sh != (uint32_t)(a_ns - 1)) {
     VT_PROF_FLUSH(gemm_store, STORE_WG);
     return;
   }
-  const float* all = P.partial + blk * P.n_splits * (kBM * kBN);
+  const float* all = a_partial + blk * a_ns * (kBM * kBN);
   for (int idx = threadIdx.x * 4; idx < n_valid; idx += kWaves * 64 * 4) {
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int sp0 = 0; sp0 < P.n_splits; sp0 += 4) {      // slices in order: the sum is reproducible
+    for (int sp0 = 0; sp0 < a_ns; sp0 += 4) {      // slices in order: the sum is reproducible
       u32x4_t v[4];
       const float* q[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) q[u] = &all[(size_t)min(sp0 + u, P.n_splits - 1) * (kBM * kBN) + idx];
+      for (int u = 0; u < 4; ++u) q[u] = &all[(size_t)min(sp0 + u, a_ns - 1) * (kBM * kBN) + idx];
       load_device_4xb128(q[0], q[1], q[2], q[3], v);
 #pragma unroll
       for (int u = 0; u < 4; ++u)
-        if (sp0 + u < P.n_splits) {
+        if (sp0 + u < a_ns) {
           const float4 t = __builtin_bit_cast(float4, v[u]);
           s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
         }
@@ -245,8 +262,8 @@ __global__ void __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_e
       int pc = 0;
 #pragma unroll
       for (int i = 1; i < kMaxOutPieces; ++i)
-        if (i < P.n_out && n >= P.out[i].col_lo) pc = i;
-      const OutPiece& o = P.out[pc];
+        if (i < a_nout && n >= out_sh[i].col_lo) pc = i;
+      const OutPiece& o = out_sh[pc];
       const int64_t off = axis_off(o.row, (uint32_t)mm) + axis_off(o.col, (uint32_t)(n - o.col_lo));
       *reinterpret_cast<T*>(o.base + off * 2) = from_float<T>(sv[c]);
     }
