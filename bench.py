@@ -212,8 +212,18 @@ def hbm_roofline(alg_bytes, us, kernel):
 
 def mfma_roofline(flops, us, kernel):
     tf = flops / (us * 1e-6) / 1e12
-    return {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None, "kernel": kernel}
+    r = {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+         "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None, "kernel": kernel}
+    try:
+        # the same against compute units x reported clock x 4096 flop per cycle (16-bit operands, dense)
+        import torch
+        pr = torch.cuda.get_device_properties(0)
+        peak = pr.multi_processor_count * pr.clock_rate * 1e3 * 4096 / 1e12
+        r["peak_at_reported_clock"] = round(peak, 1)
+        r["frac_at_reported_clock"] = round(tf / peak, 4)
+    except Exception:
+        pass
+    return r
 
 
 def chain_stats(torch, name, no_graph=False, with_materialized=True):
