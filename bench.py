@@ -187,6 +187,79 @@ def cpu_baseline_c2(wl, alg_bytes):
             "sample": "one full pass of config 2 (B=8, context 4096): %.2f s wall" % dt, "seconds": dt}
 
 
+# chains whose full oracle pass takes seconds on the host (config 5 and the combine take tens of
+# seconds and are timed by the parity tests only)
+ORACLE_TIMED = ("c1", "c3", "c4", "rowsum_large", "qkv_store")
+
+
+def oracle_seconds(name):
+    """Wall time and cores of one full oracle pass of a chain (every operator materialized, then
+    the consumer, float64 unless the paper fixes the precision), inputs generated beforehand."""
+    import psutil
+    import workloads
+    from oracle.run import run_workload
+    wl = workloads.CONFIGS[name](seed=0)
+    proc = psutil.Process()
+    c0 = proc.cpu_times()
+    t0 = time.perf_counter()
+    run_workload(wl)
+    dt = time.perf_counter() - t0
+    c1 = proc.cpu_times()
+    cpu = (c1.user - c0.user) + (c1.system - c0.system)
+    return {"seconds": round(dt, 4), "cores": max(1, int(round(cpu / dt))), "kind": "oracle", "sample": "one full pass"}
+
+
+# ------------------------------------------------------------------------------------------
+# the chains besides the headline
+# ------------------------------------------------------------------------------------------
+# name -> (input copies the virtual path rotates over, launches to sample, HIP graph?)
+CHAIN_PLAN = {
+    "c1": (1, 256, True),
+    "c3": (3, 30, False),
+    "c4": (6, 240, True),
+    "c5": (1, 6, False),
+    "rowsum_large": (2, 60, False),
+    "qkv_store": (6, 240, True),
+    "decode_segment": (4, 120, True),
+    "paged": (4, 200, True),
+    "moe_combine": (1, 40, False),
+}
+
+
+def hbm_roofline(alg_bytes, us, kernel):
+    gbs = alg_bytes / (us * 1e-6) / 1e9
+    return {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
+            "traffic": None, "kernel": kernel}
+
+
+def mfma_roofline(flops, us, kernel):
+    tf = flops / (us * 1e-6) / 1e12
+    return {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None, "kernel": kernel}
+
+
+# chains whose full oracle pass takes seconds on the host (config 5 and the combine take tens of
+# seconds and are timed by the parity tests only)
+ORACLE_TIMED = ("c1", "c3", "c4", "rowsum_large", "qkv_store")
+
+
+def oracle_seconds(name):
+    """Wall time and cores of one full oracle pass of a chain (every operator materialized, then
+    the consumer, float64 unless the paper fixes the precision), inputs generated beforehand."""
+    import psutil
+    import workloads
+    from oracle.run import run_workload
+    wl = workloads.CONFIGS[name](seed=0)
+    proc = psutil.Process()
+    c0 = proc.cpu_times()
+    t0 = time.perf_counter()
+    run_workload(wl)
+    dt = time.perf_counter() - t0
+    c1 = proc.cpu_times()
+    cpu = (c1.user - c0.user) + (c1.system - c0.system)
+    return {"seconds": round(dt, 4), "cores": max(1, int(round(cpu / dt))), "kind": "oracle", "sample": "one full pass"}
+
+
 # ------------------------------------------------------------------------------------------
 # the chains besides the headline
 # ------------------------------------------------------------------------------------------
@@ -442,6 +515,11 @@ def main():
                 out["chains"][name] = {"error": "%s: %s" % (type(e).__name__, e)}
             out["chains"][name]["bench_seconds"] = round(time.perf_counter() - t0, 1)
             torch.cuda.empty_cache()
+            if not a.no_cpu_baseline and name in ORACLE_TIMED:
+                try:
+                    out["chains"][name]["cpu_baseline"] = oracle_seconds(name)
+                except Exception as e:
+                    out["chains"][name]["cpu_baseline"] = {"error": "%s: %s" % (type(e).__name__, e)}
 
     if not a.no_cpu_baseline and wls is not None:
         out["cpu_baseline"] = cpu_baseline_c2(wls[0], alg)
