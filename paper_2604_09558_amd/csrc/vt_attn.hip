@@ -1064,7 +1064,7 @@ static int launch_attention(const vt_desc* Q, const vt_desc* K, const vt_desc* V
   }
   dim3 grid(ns_eff, Hkv, (unsigned)B);
   // compiled for three waves per SIMD (two workgroups of four waves per compute unit and room for
-  // a third): measured faster than two on the benchmark's shape
+  // a third); the build for two measures the same on the benchmark's shape
   if (Q->dtype == VT_BF16) hipLaunchKernelGGL((k_decode_attn<bf16_t, kWaves, 3>), grid, dim3(kWaves * 64), 0, st, P);
   else hipLaunchKernelGGL((k_decode_attn<f16_t, kWaves, 3>), grid, dim3(kWaves * 64), 0, st, P);
   return check_launch(who);
