@@ -16,3 +16,14 @@ def test_a_multi_rank_launch_is_refused_too():
     env = dict(os.environ, WORLD_SIZE="2", RANK="0", LOCAL_RANK="0")
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")], capture_output=True, text=True, timeout=120, env=env)
     assert r.returncode != 0 and "single-GPU" in r.stderr
+
+
+def test_counter_traffic_is_tied_to_the_kernel_source():
+    """roofline.traffic comes from a committed counter summary that records the SHA-256 of the
+    kernel's source: for the committed pair the figure is reported, for any other source it is not."""
+    sys.path.insert(0, ROOT)
+    import bench
+    t = bench.counter_traffic("k_decode_attn_c2_hbm_traffic.txt", "vt_attn.hip")
+    assert t is not None and 136_511_488 <= t <= 1.02 * 136_511_488, t      # nothing read twice
+    assert bench.counter_traffic("k_decode_attn_c2_hbm_traffic.txt", "vt_gemm.hip") is None     # another source: stale
+    assert bench.counter_traffic("no_such_file.txt", "vt_attn.hip") is None
