@@ -2,63 +2,16 @@
 // whose prologue walks a large by-value parameter structure (segment tables, axis maps) reads
 // those lines in several rounds, each waiting for the one before (data-dependent indices, or
 // simply the order in which the values are needed): a chain of cold misses before the first
-// useful load can be issued.  The functions below ask for one word of each of the first lines of
-// the kernel-argument segment at once and wait once, so that the reads that follow hit the scalar
-// cache.  Reads only; the values are dropped.  Every word read must lie inside the arguments: a
-// function that touches n lines needs (n - 1) * 64 + 4 <= sizeof(arguments), which the callers
-// assert.  (All loads and the wait sit in one asm statement: the registers they write are not
+// useful load can be issued.  The function below asks for one word of each of the first lines of
+// the kernel-argument segment at once and waits once, so that the reads that follow hit the scalar
+// cache.  Reads only; the values are dropped.  Every word read must lie inside the arguments
+// (15 * 64 + 4 <= sizeof(arguments) and also + 68 <= sizeof(arguments)), which the caller asserts.  (All loads and the wait sit in one asm statement: the registers they write are not
 // handed out again before the data has arrived.)
 #pragma once
 
 #include <hip/hip_runtime.h>
 
 namespace vt {
-
-// lines 0..5 (bytes 0..383)
-__device__ __forceinline__ void warm_kernarg_6() {
-  typedef __attribute__((address_space(4))) const char* karg_t;
-  const karg_t base = (karg_t)__builtin_amdgcn_kernarg_segment_ptr();
-  const uint64_t p = (uint64_t)base;
-  uint32_t d0, d1, d2, d3, d4, d5;
-  asm volatile(
-      "s_load_dword %0, %6, 0x0\n\t"
-      "s_load_dword %1, %6, 0x40\n\t"
-      "s_load_dword %2, %6, 0x80\n\t"
-      "s_load_dword %3, %6, 0xc0\n\t"
-      "s_load_dword %4, %6, 0x100\n\t"
-      "s_load_dword %5, %6, 0x140\n\t"
-      "s_waitcnt lgkmcnt(0)"
-      : "=&s"(d0), "=&s"(d1), "=&s"(d2), "=&s"(d3), "=&s"(d4), "=&s"(d5)
-      : "s"(p)
-      : "memory");
-}
-
-// lines 0..13 (bytes 0..895)
-__device__ __forceinline__ void warm_kernarg_14() {
-  typedef __attribute__((address_space(4))) const char* karg_t;
-  const karg_t base = (karg_t)__builtin_amdgcn_kernarg_segment_ptr();
-  const uint64_t p = (uint64_t)base;
-  uint32_t d0, d1, d2, d3, d4, d5, d6, d7, d8, d9, d10, d11, d12, d13;
-  asm volatile(
-      "s_load_dword %0, %14, 0x0\n\t"
-      "s_load_dword %1, %14, 0x40\n\t"
-      "s_load_dword %2, %14, 0x80\n\t"
-      "s_load_dword %3, %14, 0xc0\n\t"
-      "s_load_dword %4, %14, 0x100\n\t"
-      "s_load_dword %5, %14, 0x140\n\t"
-      "s_load_dword %6, %14, 0x180\n\t"
-      "s_load_dword %7, %14, 0x1c0\n\t"
-      "s_load_dword %8, %14, 0x200\n\t"
-      "s_load_dword %9, %14, 0x240\n\t"
-      "s_load_dword %10, %14, 0x280\n\t"
-      "s_load_dword %11, %14, 0x2c0\n\t"
-      "s_load_dword %12, %14, 0x300\n\t"
-      "s_load_dword %13, %14, 0x340\n\t"
-      "s_waitcnt lgkmcnt(0)"
-      : "=&s"(d0), "=&s"(d1), "=&s"(d2), "=&s"(d3), "=&s"(d4), "=&s"(d5), "=&s"(d6), "=&s"(d7), "=&s"(d8), "=&s"(d9), "=&s"(d10), "=&s"(d11), "=&s"(d12), "=&s"(d13)
-      : "s"(p)
-      : "memory");
-}
 
 // lines 0..15 (bytes 0..1023) and the two lines from byte `also` (a multiple of 64)
 __device__ __forceinline__ void warm_kernarg_16_and_2(uint32_t also) {
