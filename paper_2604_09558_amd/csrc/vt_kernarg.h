@@ -5,8 +5,9 @@
 // useful load can be issued.  The function below asks for one word of each of the first lines of
 // the kernel-argument segment at once and waits once, so that the reads that follow hit the scalar
 // cache.  Reads only; the values are dropped.  Every word read must lie inside the arguments
-// (15 * 64 + 4 <= sizeof(arguments) and also + 68 <= sizeof(arguments)), which the caller asserts.  (All loads and the wait sit in one asm statement: the registers they write are not
-// handed out again before the data has arrived.)
+// (15 * 64 + 4 <= sizeof(arguments) and also + 68 <= sizeof(arguments)), which the caller asserts.
+// All loads and the wait sit in one asm statement: the registers they write are not handed out
+// again before the data has arrived.
 #pragma once
 
 #include <hip/hip_runtime.h>
