@@ -323,8 +323,10 @@ def choose_path(dw: DeviceWorkload, iters=20, warmup=3, unit_bytes=0, **kw):
 # ------------------------------------------------------------------------------------------
 class StrategyPipeline:
     """`chosen` maps tensor names to opportunities (vtog.Opportunity): those tensors are virtual,
-    in the read direction (the consumer reads through the map) or, for inputs of a Concat, in the
-    store direction (the input is written straight into the Concat's output).  Every other intermediate the consumer depends on is physical and is
+    in the read direction (the consumer reads through the map) or in the store direction: an input
+    of a Concat is written straight into its range of the Concat's output, the input of a Reshape,
+    Permute or Unsqueeze straight into that operator's output (through the inverse view).  Every
+    other intermediate the consumer depends on is physical and is
     produced by one copy kernel that reads through the descriptor of the eliminated operators
     above it; the consumer reads its operands through descriptors over the nearest physical
     tensors.  With `chosen` empty this is the fully materialized path, with every tensor chosen
@@ -359,13 +361,23 @@ class StrategyPipeline:
         # the output.  Such a Concat is executed input by input: each one goes through its own map
         # (over whatever physical tensors it is made of) straight into its range of the output.
         stored = {t: o for t, o in chosen.items() if o.direction == "store"}
+        bijective = ("reshape", "permute", "unsqueeze")
         for t, o in stored.items():
-            if stmts[o.op_index][1] != "concat":
-                raise vt.VtError(vt.ERR_UNSUPPORTED, "only store-direction choices of Concat inputs are lowered (tensor %r)" % t)
+            if stmts[o.op_index][1] != "concat" and stmts[o.op_index][1] not in bijective:
+                raise vt.VtError(vt.ERR_UNSUPPORTED, "store-direction choices are lowered for inputs of Concat, Reshape, Permute "
+                                                     "and Unsqueeze (tensor %r is stored into a %s)" % (t, stmts[o.op_index][1]))
         chosen = {t: o for t, o in chosen.items() if o.direction == "read"}
-        by_concat = {}
+        by_concat, by_bijective = {}, {}
         for t, o in stored.items():
-            by_concat.setdefault(o.op_index, set()).add(t)
+            if stmts[o.op_index][1] == "concat":
+                by_concat.setdefault(o.op_index, set()).add(t)
+            else:
+                by_bijective[o.op_index] = t
+
+        # what a stored tensor holds is addressed through its producing operator (it has no buffer
+        # of its own), also where one stored tensor is produced from another
+        through_stored = dict(chosen)
+        through_stored.update({t: read_opp[t] for t in stored if t in read_opp})
 
         def ensure(t):
             """make sure tensor t (a physical intermediate) has a buffer and a copy that fills it"""
@@ -377,9 +389,7 @@ class StrategyPipeline:
                 dim = p["dim"]
                 parts = []
                 for i in ins:
-                    via = dict(chosen)
-                    if i in stored and i in read_opp:
-                        via[i] = read_opp[i]       # its producing operator writes into the output: no buffer of its own
+                    via = through_stored if i in stored else dict(chosen)
                     chain, sources = vtog.read_chain(stmts, via, i)
                     for s in sources:
                         ensure(s)
@@ -395,6 +405,41 @@ class StrategyPipeline:
                     dst = self._build([(slot, "slice", (t,), {"dim": dim, "start": at, "stop": at + d.shape[dim], "step": 1})], [t], slot)
                     self.copies.append((produced[t], d, dst))
                     at += d.shape[dim]
+                return
+            if produced[t] in by_bijective:
+                # t = op(i) with i stored into t: what produces i is written through the inverse view
+                # of t (i seen as a Reshape / Permute of t), so i never has a buffer of its own and
+                # the operator between i and t is never executed
+                _, kind, ins, p = stmts[produced[t]]
+                i = ins[0]
+                chain, sources = vtog.read_chain(stmts, through_stored, i)
+                for s in sources:
+                    ensure(s)
+                src = self._build(chain, sources, i)
+                ishape = tuple(src.shape)
+                if kind == "permute":
+                    perm = tuple(p["perm"])
+                    tshape = tuple(ishape[j] for j in perm)
+                    inverse = {"perm": tuple(sorted(range(len(perm)), key=lambda a: perm[a]))}
+                    back = "permute"
+                else:
+                    n = 1
+                    for e in ishape:
+                        n *= e
+                    tshape = tuple(p["shape"]) if kind == "reshape" else ishape[:p["dim"]] + (1,) + ishape[p["dim"]:]
+                    if -1 in tshape:
+                        known = 1
+                        for e in tshape:
+                            known *= e if e != -1 else 1
+                        tshape = tuple(n // known if e == -1 else e for e in tshape)
+                    inverse = {"shape": ishape}
+                    back = "reshape"
+                self.shapes[t] = tshape
+                self.bufs[t] = torch.empty(tshape, dtype=TORCH_DTYPE[wl.dtype], device=dw.device)
+                self.bytes_written += self.bufs[t].numel() * self.bufs[t].element_size()
+                slot = "%s__as_%s" % (t, i)
+                dst = self._build([(slot, back, (t,), inverse)], [t], slot)
+                self.copies.append((produced[t], src, dst))
                 return
             forced = dict(chosen)
             forced[t] = read_opp[t]

@@ -153,3 +153,60 @@ def test_store_direction_choices_of_concat_inputs_are_lowered(gpu):
     p.run()
     torch.cuda.synchronize()
     assert np.max(np.abs(tio.to_host_f64(p.out) - run_workload(wl)["out"])) <= 2e-3
+
+
+BIJECTIVE_STORES = [
+    # workload, tensor stored into the output of a bijective operator, tolerance (None: bit-exact)
+    ("c1", lambda: workloads.c1_tiny_chain(seed=7, a=3, b=8, c=40, lo=2, hi=20, ny=7), ["t1"], None),
+    ("c3", lambda: workloads.c3_oproj_gemm(seed=7, B=2, H=3, S=100, D=64, N=264), ["o1"], 1e-2),
+    ("c4 permute", lambda: workloads.c4_window_ln_linear(seed=7, B=2, R=14, win=7, C=128, N=384), ["x1"], 1e-2),
+    ("c4 reshape", lambda: workloads.c4_window_ln_linear(seed=7, B=2, R=14, win=7, C=128, N=384), ["x2"], 1e-2),
+    ("c4 both", lambda: workloads.c4_window_ln_linear(seed=7, B=2, R=14, win=7, C=128, N=384), ["x1", "x2"], 1e-2),
+]
+
+
+@pytest.mark.parametrize("name,make,tensors,tol", BIJECTIVE_STORES, ids=[c[0] for c in BIJECTIVE_STORES])
+def test_store_direction_through_reshape_and_permute(gpu, name, make, tensors, tol):
+    """The input of a Reshape or Permute made a virtual tensor of the operator's output (store
+    direction, Sec. 4.4): what produces the input is written through the inverse view of the output,
+    the operator itself is never executed, and the consumer's result is the oracle's."""
+    vt, tio, pipelines, vtog, torch = gpu
+    wl = make()
+    ref = run_workload(wl)["out"]
+    g = vtog.build_vtog(list(wl.chain), tuple(wl.sources), ())
+    chosen = {t: next(o for o in g.by_tensor[t] if o.direction == "store") for t in tensors}
+    assert vtog.is_points_to_graph(g, chosen)
+    p = pipelines.StrategyPipeline(tio.DeviceWorkload(wl), chosen)
+    for t in tensors:
+        assert t not in p.bufs                                    # lives inside the operator's output
+    assert sum(isinstance(c[2], vt.Desc) for c in p.copies) >= 1  # written through a map
+    p.run()
+    torch.cuda.synchronize()
+    out = p.out if p.out is not None else p.consumer.out
+    if tol is None:
+        assert np.array_equal(out.cpu().numpy(), ref.astype(np.float32))
+    else:
+        got = tio.to_host_f64(out).reshape(ref.shape)
+        assert (np.abs(got - ref) <= tol + tol * np.abs(ref)).all()
+
+
+def test_store_direction_of_a_split_input_is_refused(gpu):
+    """An input of a Split stitched from the Split's outputs is a legal bundle of the opportunity
+    graph (Sec. 4.4) that this lowering does not execute: it says so instead of guessing."""
+    vt, tio, pipelines, vtog, torch = gpu
+    rng = np.random.default_rng(0)
+    src = {"X": rng.standard_normal((4, 6)).astype(np.float32), "Z": rng.standard_normal((2, 4)).astype(np.float32)}
+    chain = [("t0", "permute", ("X",), {"perm": (1, 0)}),
+             ("a", "split", ("t0",), {"dim": 0, "sizes": (2, 4), "output": 0})]
+    wl = workloads.Workload("split_store", "f32", src, chain, {"kind": "add_rowsum", "x": "a", "y": "Z"})
+    g = vtog.build_vtog(list(wl.chain), tuple(wl.sources), ())
+    stores = [o for o in g.by_tensor["t0"] if o.direction == "store"]
+    assert stores and wl.chain[stores[0].op_index][1] == "split"
+    with pytest.raises(vt.VtError):
+        pipelines.StrategyPipeline(tio.DeviceWorkload(wl), {"t0": stores[0]})
+    # the same chain with the read-direction choices runs
+    chosen = {t: next(o for o in g.by_tensor[t] if o.direction == "read") for t in ("t0", "a")}
+    p = pipelines.StrategyPipeline(tio.DeviceWorkload(wl), chosen)
+    p.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(p.out.cpu().numpy(), run_workload(wl)["out"].astype(np.float32))
