@@ -89,7 +89,13 @@ def build_vtog(statements, graph_inputs, graph_outputs, directions=("read", "sto
     for k, st in enumerate(statements):
         ins = [i for i in st[2] if isinstance(i, str)]
         outs = outputs_of(st)
-        arr[k].kind = KINDS.get(st[1], binding.OP_COMPUTE)
+        kind = KINDS.get(st[1], binding.OP_COMPUTE)
+        if st[1] == "split" and len(outs) < len(st[3].get("sizes", outs)):
+            # a statement that names one output of a Split (the executable chains' form) is a Slice as
+            # far as the graph goes: its input cannot be stitched from outputs that are not all there,
+            # so it gets the read-direction bundle only
+            kind = KINDS["slice"]
+        arr[k].kind = kind
         arr[k].n_in, arr[k].n_out = len(ins), len(outs)
         for j, i in enumerate(ins):
             arr[k].in_[j] = index[i]

@@ -190,22 +190,26 @@ def test_store_direction_through_reshape_and_permute(gpu, name, make, tensors, t
         assert (np.abs(got - ref) <= tol + tol * np.abs(ref)).all()
 
 
-def test_store_direction_of_a_split_input_is_refused(gpu):
-    """An input of a Split stitched from the Split's outputs is a legal bundle of the opportunity
-    graph (Sec. 4.4) that this lowering does not execute: it says so instead of guessing."""
+def test_one_output_of_a_split_gives_its_input_no_store_bundle(gpu):
+    """The executable chains name one output of a Split per statement.  The Split's input cannot be
+    stitched from outputs that are not all there, so the opportunity graph offers it no
+    store-direction bundle (a whole Split, all outputs in one statement, does: tests/test_vtog.py);
+    the read-direction choices run."""
     vt, tio, pipelines, vtog, torch = gpu
     rng = np.random.default_rng(0)
     src = {"X": rng.standard_normal((4, 6)).astype(np.float32), "Z": rng.standard_normal((2, 4)).astype(np.float32)}
     chain = [("t0", "permute", ("X",), {"perm": (1, 0)}),
              ("a", "split", ("t0",), {"dim": 0, "sizes": (2, 4), "output": 0})]
-    wl = workloads.Workload("split_store", "f32", src, chain, {"kind": "add_rowsum", "x": "a", "y": "Z"})
+    wl = workloads.Workload("split_read", "f32", src, chain, {"kind": "add_rowsum", "x": "a", "y": "Z"})
     g = vtog.build_vtog(list(wl.chain), tuple(wl.sources), ())
-    stores = [o for o in g.by_tensor["t0"] if o.direction == "store"]
-    assert stores and wl.chain[stores[0].op_index][1] == "split"
-    with pytest.raises(vt.VtError):
-        pipelines.StrategyPipeline(tio.DeviceWorkload(wl), {"t0": stores[0]})
-    # the same chain with the read-direction choices runs
-    chosen = {t: next(o for o in g.by_tensor[t] if o.direction == "read") for t in ("t0", "a")}
+    assert [o.direction for o in g.by_tensor["t0"]] == ["read"] and [o.direction for o in g.by_tensor["a"]] == ["read"]
+    whole = vtog.build_vtog([chain[0], (("a", "b"), "split", ("t0",), {"dim": 0, "sizes": (2, 4)})], ("X",), ())
+    stores = [o for o in whole.by_tensor["t0"] if o.direction == "store"]
+    assert [o.targets for o in stores] == [("a", "b")]
+    with pytest.raises(vt.VtError):          # a legal bundle that this lowering does not execute: it says so
+        pipelines.StrategyPipeline(tio.DeviceWorkload(wl), {"t0": stores[0]},
+                                   statements=[chain[0], (("a", "b"), "split", ("t0",), {"dim": 0, "sizes": (2, 4)})])
+    chosen = {t: g.by_tensor[t][0] for t in ("t0", "a")}
     p = pipelines.StrategyPipeline(tio.DeviceWorkload(wl), chosen)
     p.run()
     torch.cuda.synchronize()

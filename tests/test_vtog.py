@@ -247,3 +247,18 @@ def test_vtog_library_rejects_bad_graphs():
     assert L.vt_vtog_build(st, 1, 2, pinned, 3, C.byref(h)) == binding.ERR_INVALID_ARG
     assert b"outside the graph" in L.vt_last_error()
     assert L.vt_vtog_build(st, 1, 2, pinned, 0, C.byref(h)) == binding.ERR_INVALID_ARG
+
+
+def test_a_statement_naming_one_output_of_a_split_offers_no_store_bundle():
+    """The executable chains name one Split output per statement; the Split's input cannot be
+    stitched from outputs that are not all present, so it only gets the read-direction bundles.
+    A Split written as one statement with all its outputs keeps the store-direction bundle."""
+    head = ("t0", "permute", ("X",), {"perm": (1, 0)})
+    one = vtog.build_vtog([head, ("a", "split", ("t0",), {"dim": 0, "sizes": (2, 4), "output": 0})], ("X",), ())
+    assert [(o.direction, o.targets) for o in one.by_tensor["t0"]] == [("read", ("X",))]
+    assert [(o.direction, o.targets) for o in one.by_tensor["a"]] == [("read", ("t0",))]
+    both = vtog.build_vtog([head, ("a", "split", ("t0",), {"dim": 0, "sizes": (2, 4), "output": 0}),
+                            ("b", "split", ("t0",), {"dim": 0, "sizes": (2, 4), "output": 1})], ("X",), ())
+    assert all(o.direction == "read" for o in both.by_tensor["t0"])
+    whole = vtog.build_vtog([head, (("a", "b"), "split", ("t0",), {"dim": 0, "sizes": (2, 4)})], ("X",), ())
+    assert ("store", ("a", "b")) in [(o.direction, o.targets) for o in whole.by_tensor["t0"]]
