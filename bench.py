@@ -34,7 +34,7 @@ HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16/fp16 matrix peak
 
 ALL_CHAINS = ("c1", "c3", "c4", "c5", "rowsum_large", "qkv_store", "decode_segment", "paged", "moe_combine")
-DEFAULT_CHAINS = "c1,c3,c4,c5,rowsum_large,qkv_store,moe_combine"
+DEFAULT_CHAINS = "c1,c3,c4,c5,rowsum_large,qkv_store,moe_combine,paged,decode_segment"
 
 
 def algorithmic_bytes_c2(B, Hkv, G, S, D, n_splits, esz=2):
