@@ -131,6 +131,20 @@ int vt_desc_block(const vt_desc* d, int64_t cap_elems, int64_t* block_elems);
  * path).  Host only. */
 int vt_desc_as_strided(const vt_desc* d, int* is_strided, int64_t* stride, int64_t* offset);
 
+/* Block-wise form of a two-dimensional map (Sec. 4.2: the index computation is done once per block
+ * and simplified on the host): d virtual [R, C], read in aligned blocks of block_elems columns.
+ * If every piece of the map is affine in the row and in at most two levels of the block index,
+ * *n_segments receives the number of segments (at most 4) and segments[9*k .. 9*k+8] = row_lo,
+ * row_hi, blk_lo, blk_hi (the blocks [blk_lo, blk_hi) of the rows [row_lo, row_hi)), the address
+ * of the segment's first block, the distance in bytes to the next row, blk_stride, blk_group and
+ * group_stride: block blk_lo + j lies (j % blk_group) * blk_stride + (j / blk_group) *
+ * group_stride bytes from the first (blk_group = 0: j * blk_stride).  *n_segments = 0 if the map
+ * has another form (tables, more than one stage, digits that do not collapse) or if aligned blocks
+ * of that size are not contiguous ranges of a source (vt_desc_block).  `segments` has room for 36
+ * values (host memory).  The add + row-sum consumer reads its operands through these segments
+ * when both resolve, and through the evaluator otherwise. */
+int vt_desc_row_walk(const vt_desc* d, int64_t block_elems, int* n_segments, int64_t* segments);
+
 /* Piece p: its box [lo,hi) in virtual index space, its source number and its own run. */
 int vt_desc_piece(const vt_desc* d, int p, int64_t* lo, int64_t* hi, int* src_id, int64_t* run);
 /* CPU evaluation of the map at one virtual index (host logic; used by tests).  vindex holds

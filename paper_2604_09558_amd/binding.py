@@ -74,6 +74,7 @@ def lib():
         L.vt_classify.argtypes = [P, C.c_int64, C.POINTER(C.c_int), C.POINTER(C.c_int64)]
         L.vt_desc_block.argtypes = [P, C.c_int64, C.POINTER(C.c_int64)]
         L.vt_desc_as_strided.argtypes = [P, C.POINTER(C.c_int), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+        L.vt_desc_row_walk.argtypes = [P, C.c_int64, C.POINTER(C.c_int), C.POINTER(C.c_int64)]
         L.vt_eval_host.argtypes = [P, C.POINTER(C.c_int64), C.POINTER(C.c_int), C.POINTER(C.c_int64)]
         L.vt_eval_device_form.argtypes = [P, C.POINTER(C.c_int64), C.POINTER(C.c_int), C.POINTER(C.c_int64)]
         L.vt_desc_dump.argtypes = [P, C.c_char_p, C.c_size_t]
@@ -210,6 +211,15 @@ class Desc:
         if not flag.value:
             return None
         return tuple(st[i] for i in range(len(self.shape))), off.value
+
+    def row_walk(self, block_elems):
+        """Segments in which the block address of a [R, C] map is affine in the row and in at most two levels of
+        the block index: a list of (row_lo, row_hi, blk_lo, blk_hi, address, row_stride_bytes, blk_stride_bytes,
+        blk_group, group_stride_bytes); empty if the map has another form."""
+        n = C.c_int()
+        seg = (C.c_int64 * 36)()
+        _check(lib().vt_desc_row_walk(self.handle, block_elems, C.byref(n), seg))
+        return [tuple(seg[9 * k + i] for i in range(9)) for k in range(n.value)]
 
     def piece(self, p):
         lo, hi = (C.c_int64 * VT_MAX_DIMS)(), (C.c_int64 * VT_MAX_DIMS)()

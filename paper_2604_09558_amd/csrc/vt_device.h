@@ -64,6 +64,17 @@ __host__ __device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv& f) 
   return (uint32_t)(((uint64_t)n * f.magic) >> (31u + f.shift));
 }
 
+// Entry i of an index table.  On the device the tables live in device memory: the pointer comes
+// out of the descriptor, so the compiler would emit a generic access (one that also checks the
+// LDS and scratch apertures); naming the address space makes it a global load.
+__host__ __device__ __forceinline__ int32_t table_at(const int32_t* t, uint32_t i) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return reinterpret_cast<const __attribute__((address_space(1))) int32_t*>(reinterpret_cast<uintptr_t>(t))[i];
+#else
+  return t[i];
+#endif
+}
+
 // Element offset and source pointer of the element at (outer index o, inner linear index L).
 // Returns the piece index (always found for a well-formed descriptor).
 __host__ __device__ __forceinline__ int vtd_eval(const DevDesc& D, uint32_t o, uint32_t L, int64_t* off_out,
@@ -97,7 +108,7 @@ __host__ __device__ __forceinline__ int vtd_eval(const DevDesc& D, uint32_t o, u
         uint32_t q = fdiv(v, dg.radix);
         uint32_t r = v - q * dg.radix.d;
         v = q;
-        int64_t val = dg.table >= 0 ? (int64_t)D.tables[dg.table][dg.table_off + r] : (int64_t)r;
+        int64_t val = dg.table >= 0 ? (int64_t)table_at(D.tables[dg.table], dg.table_off + r) : (int64_t)r;
         acc += val * dg.stride;
       }
     }
@@ -110,7 +121,7 @@ __host__ __device__ __forceinline__ int vtd_eval(const DevDesc& D, uint32_t o, u
         uint32_t q = fdiv(v, dg.radix);
         uint32_t r = v - q * dg.radix.d;
         v = q;
-        int64_t val = dg.table >= 0 ? (int64_t)D.tables[dg.table][dg.table_off + r] : (int64_t)r;
+        int64_t val = dg.table >= 0 ? (int64_t)table_at(D.tables[dg.table], dg.table_off + r) : (int64_t)r;
         acc += val * dg.stride;
       }
     }
@@ -122,6 +133,38 @@ __host__ __device__ __forceinline__ int vtd_eval(const DevDesc& D, uint32_t o, u
 }
 
 #ifdef __HIPCC__
+// Loads and stores of 2, 4, 8 or 16 bytes at an address that a map produced.  Such an address
+// names device memory, which the compiler cannot see (it is an integer, or a pointer read out of
+// a descriptor): these helpers say so, and the access becomes a global one instead of a generic
+// one.  STREAM: the bytes are read once (a streaming load that does not displace other lines).
+template <int BYTES> struct RawVec;
+template <> struct RawVec<2> { typedef uint16_t type; };
+template <> struct RawVec<4> { typedef uint32_t type; };
+template <> struct RawVec<8> { typedef uint32_t type __attribute__((ext_vector_type(2))); };
+template <> struct RawVec<16> { typedef uint32_t type __attribute__((ext_vector_type(4))); };
+
+template <typename V, bool STREAM = false>
+__device__ __forceinline__ V ld_global(uint64_t addr) {
+  typedef typename RawVec<sizeof(V)>::type R;
+  const __attribute__((address_space(1))) R* p = reinterpret_cast<const __attribute__((address_space(1))) R*>(addr);
+  const R r = STREAM ? __builtin_nontemporal_load(p) : *p;
+  V v;
+  __builtin_memcpy(&v, &r, sizeof(V));
+  return v;
+}
+template <typename V, bool STREAM = false>
+__device__ __forceinline__ V ld_global(const void* p) { return ld_global<V, STREAM>(reinterpret_cast<uint64_t>(p)); }
+
+template <typename V>
+__device__ __forceinline__ void st_global(uint64_t addr, const V& v) {
+  typedef typename RawVec<sizeof(V)>::type R;
+  R r;
+  __builtin_memcpy(&r, &v, sizeof(V));
+  *reinterpret_cast<__attribute__((address_space(1))) R*>(addr) = r;
+}
+template <typename V>
+__device__ __forceinline__ void st_global(void* p, const V& v) { st_global<V>(reinterpret_cast<uint64_t>(p), v); }
+
 // The evaluator walks a map with per-lane indices (which piece, which digits): read from the
 // kernel arguments every step of that walk is a dependent read of memory.  The kernels that
 // evaluate per lane copy their maps to LDS first, with one coalesced read.
@@ -145,6 +188,29 @@ int vector_width(const vt_desc& d);
 // Largest power of two c <= cap such that aligned groups of c consecutive virtual elements are
 // one contiguous range of one source each (the block form of vector_width; no alignment claim).
 int64_t block_elems(const vt_desc& d, int64_t cap);
+
+// Where the host can resolve an operand's map into a few segments in which the block address is
+// affine in the row and in at most two levels of the block index, the kernel needs no evaluator:
+// a segment covers the blocks [blk_lo, blk_hi) of the rows [row_lo, row_hi), its first block
+// starts at `base`, one row further the address moves by row_stride bytes, and block blk_lo + j
+// lies (j % blk_group) * blk_stride + (j / blk_group) * group_stride bytes from the first
+// (blk_group = 0: one level, j * blk_stride).  n = 0: not resolved.
+constexpr int kRowSegs = 4;
+struct RowSeg {
+  uint64_t base;
+  int64_t row_stride, blk_stride, group_stride;
+  uint32_t row_lo, row_hi, blk_lo, blk_hi;
+  uint32_t blk_group, pad;
+};
+struct RowWalk {
+  RowSeg seg[kRowSegs];
+  int32_t n;
+};
+// Resolves the [R, C] operand d, read in aligned blocks of `be` columns, into such segments.
+// Every piece must be a single stage without tables whose row digits collapse to one stride and
+// whose column digits above the block collapse to one or two; the result is checked against the
+// evaluator at the corners and the centre of every segment.  False (w->n = 0) for any other map.
+bool resolve_row_walk(const vt_desc& d, int64_t be, RowWalk* w);
 
 // launch bookkeeping shared by the kernels' host wrappers
 int check_launch(const char* what);

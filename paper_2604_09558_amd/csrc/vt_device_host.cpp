@@ -209,7 +209,105 @@ extern "C" int vt_desc_block(const vt_desc* d, int64_t cap_elems, int64_t* block
   return VT_OK;
 }
 
+extern "C" int vt_desc_row_walk(const vt_desc* d, int64_t block_elems_in, int* n_segments, int64_t* segments) {
+  if (!d || !n_segments || !segments || block_elems_in < 1) return vt::fail(VT_ERR_INVALID_ARG, "vt_desc_row_walk: NULL argument or block < 1");
+  if (d->shape.size() != 2) return vt::fail(VT_ERR_SHAPE, "vt_desc_row_walk: the tensor must be [R, C]");
+  vt::RowWalk w;
+  vt::resolve_row_walk(*d, block_elems_in, &w);
+  *n_segments = w.n;
+  for (int k = 0; k < w.n; ++k) {
+    const vt::RowSeg& sg = w.seg[k];
+    int64_t* o = segments + 9 * k;
+    o[0] = sg.row_lo, o[1] = sg.row_hi, o[2] = sg.blk_lo, o[3] = sg.blk_hi;
+    o[4] = (int64_t)sg.base, o[5] = sg.row_stride, o[6] = sg.blk_stride, o[7] = sg.blk_group, o[8] = sg.group_stride;
+  }
+  return VT_OK;
+}
+
 namespace vt {
+
+// Terms of a digit group as a function of u, where the local coordinate is v = u * unit: every
+// digit becomes coef * ((u / div) % mod).  False if a digit cuts through `unit` unevenly or reads a table.
+struct AffTerm {
+  int64_t div, mod, coef;
+};
+static bool group_terms(const std::vector<Digit>& g, int64_t unit, std::vector<AffTerm>* terms) {
+  int64_t below = 1;                                  // product of the radices inner to the digit
+  for (int k = (int)g.size() - 1; k >= 0; --k) {
+    const Digit& dg = g[k];
+    if (dg.table >= 0) return false;
+    if (below % unit == 0) terms->push_back({below / unit, dg.radix, dg.stride});
+    else if (unit % below == 0) {
+      const int64_t m = unit / below;                 // the digit's value is (u * m) % radix
+      if (dg.radix % m == 0) terms->push_back({1, dg.radix / m, dg.stride * m});
+      else if (m % dg.radix != 0) return false;       // else: always zero
+    } else return false;
+    below *= dg.radix;
+  }
+  return true;
+}
+// Is the sum of the terms, on [0, extent), of the form (u % group) * s0 + (u / group) * s1?
+// One level (affine in u) gives group = 0.
+static bool terms_two_level(const std::vector<AffTerm>& terms, int64_t extent, int64_t* s0, int64_t* group, int64_t* s1) {
+  *s0 = *s1 = *group = 0;
+  bool have = false;
+  for (const AffTerm& t : terms) {
+    if (t.div >= extent || t.mod == 1) continue;      // never leaves zero
+    if (!have) {
+      if (t.div != 1) return false;                   // the values below this digit would be dropped
+      *s0 = t.coef;
+      have = true;
+    } else if (*group == 0) {
+      if (t.coef == *s0 * t.div) continue;
+      *group = t.div;                                 // the second level starts at this digit
+      *s1 = t.coef;
+    } else if (t.coef != *s1 * (t.div / *group) || t.div % *group) return false;
+  }
+  return true;
+}
+
+bool resolve_row_walk(const vt_desc& d, int64_t be, RowWalk* w) {
+  memset(w, 0, sizeof(*w));
+  if (d.shape.size() != 2 || d.pieces.size() > (size_t)kRowSegs || be < 1) return false;
+  if (block_elems(d, be) != be || d.shape[1] % be) return false;   // the blocks themselves must be contiguous ranges
+  const int esz = dtype_size(d.dtype);
+  int n = 0;
+  for (const Piece& p : d.pieces) {
+    if (!p.v.lower.empty() || p.v.groups.size() != 2) return false;
+    if (p.lo[1] % be || p.hi[1] % be) return false;
+    const int64_t rows = p.hi[0] - p.lo[0], blks = (p.hi[1] - p.lo[1]) / be;
+    if (rows < 1 || blks < 1) continue;
+    std::vector<AffTerm> tr, tb;
+    int64_t rs, r_group, r1, bs, b_group, b1;
+    if (!group_terms(p.v.groups[0], 1, &tr) || !terms_two_level(tr, rows, &rs, &r_group, &r1) || r_group != 0) return false;
+    if (!group_terms(p.v.groups[1], be, &tb) || !terms_two_level(tb, blks, &bs, &b_group, &b1)) return false;
+    const char* src = static_cast<const char*>(d.sources[p.src].ptr);
+    if (!src) return false;
+    RowSeg& sg = w->seg[n++];
+    const int64_t zero[2] = {0, 0};
+    sg.base = reinterpret_cast<uint64_t>(src) + (uint64_t)(eval_view(d, p.v, zero) * esz);
+    sg.row_stride = rs * esz;
+    sg.blk_stride = bs * esz;
+    sg.group_stride = b1 * esz;
+    sg.blk_group = (uint32_t)b_group;
+    sg.row_lo = (uint32_t)p.lo[0];
+    sg.row_hi = (uint32_t)p.hi[0];
+    sg.blk_lo = (uint32_t)(p.lo[1] / be);
+    sg.blk_hi = (uint32_t)(p.hi[1] / be);
+    // the evaluator has the last word: corners and centre of the segment, and the blocks around a group boundary
+    const int64_t rr[3] = {0, rows / 2, rows - 1};
+    const int64_t bb[5] = {0, blks / 2, blks - 1, std::min<int64_t>(blks - 1, b_group), std::min<int64_t>(blks - 1, std::max<int64_t>(0, b_group - 1))};
+    for (int64_t r : rr)
+      for (int64_t b : bb) {
+        const int64_t local[2] = {r, b * be};
+        const uint64_t want = reinterpret_cast<uint64_t>(src) + (uint64_t)(eval_view(d, p.v, local) * esz);
+        const int64_t hi = b_group ? b / b_group : 0, lo = b - hi * b_group;
+        if (want != sg.base + (uint64_t)(r * sg.row_stride + lo * sg.blk_stride + hi * sg.group_stride)) return false;
+      }
+  }
+  w->n = n;
+  return n > 0;
+}
 
 int check_launch(const char* what) {
   hipError_t e = hipGetLastError();

@@ -7,6 +7,7 @@
 
 #include "vt_device.h"
 #include "vt_numeric.h"
+#include "vt_profile.h"
 
 using namespace vt;
 
@@ -29,8 +30,7 @@ __global__ void __launch_bounds__(256) k_materialize(const DevDesc D, V* __restr
     int64_t off;
     const void* ptr;
     vtd_eval(M, o, vi * vec_elems, &off, &ptr);
-    const V* src = reinterpret_cast<const V*>(static_cast<const char*>(ptr) + off * M.elem_size);
-    dst[(size_t)o * inner_vecs + vi] = *src;
+    dst[(size_t)o * inner_vecs + vi] = ld_global<V>(static_cast<const char*>(ptr) + off * M.elem_size);
   }
 }
 
@@ -51,8 +51,8 @@ __global__ void __launch_bounds__(256) k_scatter(const DevDesc S, const DevDesc 
     const void *sp, *dp;
     vtd_eval(maps[0], o, vi * vec_elems, &so, &sp);
     vtd_eval(maps[1], o, vi * vec_elems, &dof, &dp);
-    *reinterpret_cast<V*>(static_cast<char*>(const_cast<void*>(dp)) + dof * maps[1].elem_size) =
-        *reinterpret_cast<const V*>(static_cast<const char*>(sp) + so * maps[0].elem_size);
+    st_global<V>(static_cast<char*>(const_cast<void*>(dp)) + dof * maps[1].elem_size,
+                 ld_global<V>(static_cast<const char*>(sp) + so * maps[0].elem_size));
   }
 }
 
@@ -65,6 +65,11 @@ __global__ void __launch_bounds__(256) k_scatter(const DevDesc S, const DevDesc 
 // index arithmetic is paid once per block and not once per vector.  SCATTER: the destination
 // goes through a map as well (store direction), otherwise it is dense.
 // ------------------------------------------------------------------------------------------
+// Every byte a copy moves is read once: streaming loads keep it from displacing other lines
+// (blocks of 256 bytes and less measured faster with ordinary loads).
+template <bool STREAM = true>
+__device__ __forceinline__ uint4 load_once(uint64_t addr) { return ld_global<uint4, STREAM>(addr); }
+
 __device__ __forceinline__ uint64_t shfl_u64(uint64_t v, int src_lane) {
   const uint32_t lo = __shfl((uint32_t)v, src_lane, 64), hi = __shfl((uint32_t)(v >> 32), src_lane, 64);
   return ((uint64_t)hi << 32) | lo;
@@ -123,12 +128,12 @@ __global__ void __launch_bounds__(256) k_copy_blocks(const DevDesc S, const DevD
     for (; j0 + 16 <= iters && (j0 + 16) * G <= n_here; j0 += 16) {
       uint4 v[16];
 #pragma unroll
-      for (int u = 0; u < 16; ++u) v[u] = *reinterpret_cast<const uint4*>(addr_of(src_addr, (j0 + u) * G + sub) + c16);
+      for (int u = 0; u < 16; ++u) v[u] = load_once<(BL >= 32)>(addr_of(src_addr, (j0 + u) * G + sub) + c16);
 #pragma unroll
       for (int u = 0; u < 16; ++u) {
         const uint32_t blk = (j0 + u) * G + sub;
         const uint64_t a = SCATTER ? addr_of(dst_addr, blk) + c16 : dense0 + (uint64_t)blk * (BL * 16);
-        *reinterpret_cast<uint4*>(a) = v[u];
+        st_global<uint4>(a, v[u]);
       }
     }
     for (; j0 < iters; j0 += 4) {                     // the remainder, four at a time, guarded
@@ -137,13 +142,13 @@ __global__ void __launch_bounds__(256) k_copy_blocks(const DevDesc S, const DevD
       for (int u = 0; u < 4; ++u) {
         const uint32_t blk = (j0 + u) * G + sub;
         const uint64_t a = addr_of(src_addr, min(blk, n_here - 1)) + c16;
-        if (blk < n_here) v[u] = *reinterpret_cast<const uint4*>(a);
+        if (blk < n_here) v[u] = load_once<(BL >= 32)>(a);
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const uint32_t blk = (j0 + u) * G + sub;
         const uint64_t a = SCATTER ? addr_of(dst_addr, min(blk, n_here - 1)) + c16 : dense0 + (uint64_t)blk * (BL * 16);
-        if (blk < n_here) *reinterpret_cast<uint4*>(a) = v[u];
+        if (blk < n_here) st_global<uint4>(a, v[u]);
       }
     }
   }
@@ -152,16 +157,19 @@ __global__ void __launch_bounds__(256) k_copy_blocks(const DevDesc S, const DevD
 // A map that is one contiguous range of one source (Def. 5 with minimal contiguous dimension 1:
 // a Reshape, a Slice or Split along the outermost dim, ...): a plain vector copy, no index work.
 __global__ void __launch_bounds__(256) k_copy_flat(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n_vec) {
-  const size_t stride = (size_t)gridDim.x * 256;
-  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  for (; i + 3 * stride < n_vec; i += 4 * stride) {
-    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+  // a workgroup moves consecutive 16 KB chunks: four loads of 4 KB in flight per wave, then their stores
+  const size_t chunks = n_vec / 1024;
+  for (size_t c = blockIdx.x; c < chunks; c += gridDim.x) {
+    const size_t i = c * 1024 + threadIdx.x;
+    const uint4 a = ld_global<uint4, true>(src + i), b = ld_global<uint4, true>(src + i + 256), e = ld_global<uint4, true>(src + i + 512),
+                d = ld_global<uint4, true>(src + i + 768);
     dst[i] = a;
-    dst[i + stride] = b;
-    dst[i + 2 * stride] = c;
-    dst[i + 3 * stride] = d;
+    dst[i + 256] = b;
+    dst[i + 512] = e;
+    dst[i + 768] = d;
   }
-  for (; i < n_vec; i += stride) dst[i] = src[i];
+  if (blockIdx.x == gridDim.x - 1)                    // the last, partial chunk
+    for (size_t i = chunks * 1024 + threadIdx.x; i < n_vec; i += 256) dst[i] = ld_global<uint4, true>(src + i);
 }
 
 // Picks the block size and launches k_copy_blocks; returns false if the maps allow no block of
@@ -302,7 +310,7 @@ __global__ void __launch_bounds__(256) k_add_rowsum(const DevDesc X, const DevDe
     const void *px, *py;
     vtd_eval(maps[0], 0, row * C + c, &ox, &px);
     vtd_eval(maps[1], 0, row * C + c, &oy, &py);
-    float t = static_cast<const float*>(px)[ox] + static_cast<const float*>(py)[oy];
+    float t = ld_global<float>(static_cast<const float*>(px) + ox) + ld_global<float>(static_cast<const float*>(py) + oy);
     p = p + t;
   }
 #pragma unroll
@@ -333,7 +341,7 @@ __device__ __forceinline__ void cursor_load(const DevDesc& X, uint32_t row, uint
 
 __device__ __forceinline__ float cursor_read(const BlockCursor& cur, uint32_t col, uint32_t blog) {
   const uint64_t a = shfl_u64(cur.addr, (int)((col >> blog) - cur.first));
-  return *reinterpret_cast<const float*>(a + (uint64_t)(col & ((1u << blog) - 1u)) * 4u);
+  return ld_global<float, true>(a + (uint64_t)(col & ((1u << blog) - 1u)) * 4u);   // read once: streaming
 }
 
 // The same for a window of 64 columns starting at the wave-uniform column c0 when blocks hold at
@@ -342,29 +350,60 @@ __device__ __forceinline__ float cursor_read(const BlockCursor& cur, uint32_t co
 __device__ __forceinline__ float cursor_read_window(const BlockCursor& cur, uint32_t c0, uint32_t lane, uint32_t blog) {
   const int owner = (int)((c0 >> blog) - cur.first);
   const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)cur.addr, owner), hi = __builtin_amdgcn_readlane((uint32_t)(cur.addr >> 32), owner);
-  const float* base = reinterpret_cast<const float*>(((uint64_t)hi << 32) | lo);
-  return base[(c0 & ((1u << blog) - 1u)) + lane];
+  const uint64_t base = ((uint64_t)hi << 32) | lo;
+  return ld_global<float, true>(base + (uint64_t)((c0 & ((1u << blog) - 1u)) + lane) * 4u);   // read once: streaming
 }
 
-template <bool WIDE>   // WIDE: both operands keep blocks of at least 64 columns
-__global__ void __launch_bounds__(256) k_add_rowsum_blocks(const DevDesc X, const DevDesc Y, float* __restrict__ out, uint32_t R,
-                                                           uint32_t C, uint32_t bx, uint32_t by) {
-  __shared__ DevDesc maps[2];
-  {
+__device__ __forceinline__ void cursor_walk(const RowWalk& W, uint32_t row, uint32_t C, uint32_t blog, uint32_t blk0, uint32_t lane,
+                                            BlockCursor& cur) {
+  const uint32_t nb = C >> blog;
+  const uint32_t b = min(blk0 + lane, nb - 1);
+  uint64_t a = 0;
+#pragma unroll
+  for (int k = 0; k < kRowSegs; ++k) {
+    const RowSeg& sg = W.seg[k];
+    if (k < W.n && row >= sg.row_lo && row < sg.row_hi && b >= sg.blk_lo && b < sg.blk_hi) {
+      const uint32_t j = b - sg.blk_lo, hi = sg.blk_group ? j / sg.blk_group : 0u, lo = j - hi * sg.blk_group;
+      a = sg.base + (uint64_t)((int64_t)(row - sg.row_lo) * sg.row_stride + (int64_t)lo * sg.blk_stride + (int64_t)hi * sg.group_stride);
+    }
+  }
+  cur.addr = a;
+  cur.first = blk0;
+}
+
+VT_PROF_DECLARE(add_rowsum)
+
+// WIDE: both operands keep blocks of at least 64 columns.  WALK: block addresses from the host's
+// segments (wx, wy) instead of the evaluator on X and Y.
+template <bool WIDE, bool WALK>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8))) k_add_rowsum_blocks(const RowWalk wx, const RowWalk wy, float* __restrict__ out, uint32_t R, uint32_t C,
+                                                           uint32_t bx, uint32_t by, const DevDesc X, const DevDesc Y) {
+  VT_PROF_BEGIN();
+  VT_PROF(0);
+  __shared__ DevDesc maps[2];                         // unused (and not allocated) with WALK
+  if (!WALK) {
     const DevDesc* const src[2] = {&X, &Y};
     stage_maps(maps, src);
   }
+  VT_PROF(1);
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t row = blockIdx.x * 4u + (threadIdx.x >> 6);
-  if (row >= R) return;
+  if (row >= R) return;                              // never the workgroup's first wave
   // columns after which the 64 cached blocks of an operand are used up
   const uint32_t span_x = 64u << bx, span_y = 64u << by;
   float p = 0.0f;
   BlockCursor cx, cy;
   for (uint32_t c0 = 0; c0 < C;) {
-    if (c0 % span_x == 0) cursor_load(maps[0], row, C, bx, c0 >> bx, lane, cx);
-    if (c0 % span_y == 0) cursor_load(maps[1], row, C, by, c0 >> by, lane, cy);
+    if (c0 % span_x == 0) {
+      if (WALK) cursor_walk(wx, row, C, bx, c0 >> bx, lane, cx);
+      else cursor_load(maps[0], row, C, bx, c0 >> bx, lane, cx);
+    }
+    if (c0 % span_y == 0) {
+      if (WALK) cursor_walk(wy, row, C, by, c0 >> by, lane, cy);
+      else cursor_load(maps[1], row, C, by, c0 >> by, lane, cy);
+    }
     const uint32_t end = min(C, min((c0 / span_x + 1) * span_x, (c0 / span_y + 1) * span_y));
+    VT_PROF_ONCE(2);
     // whole windows of 64 columns, eight at a time so that sixteen loads are in flight per lane
     for (; c0 + 512 <= end; c0 += 512) {
       float xv[8], yv[8];
@@ -375,6 +414,7 @@ __global__ void __launch_bounds__(256) k_add_rowsum_blocks(const DevDesc X, cons
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) p = p + (xv[u] + yv[u]);
+      VT_PROF_ONCE(3);
     }
     for (; c0 < end; c0 += 64) {
       const uint32_t col = min(c0 + lane, C - 1);     // every lane shuffles; lanes past the row add nothing
@@ -385,6 +425,8 @@ __global__ void __launch_bounds__(256) k_add_rowsum_blocks(const DevDesc X, cons
 #pragma unroll
   for (int s = 32; s >= 1; s >>= 1) p = p + __shfl_xor(p, s, 64);
   if (lane == 0) out[row] = p;
+  VT_PROF(4);
+  VT_PROF_FLUSH(add_rowsum, blockIdx.x);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -418,7 +460,7 @@ __global__ void __launch_bounds__(256) k_layernorm(const DevDesc X, T* __restric
       int64_t off;
       const void* ptr;
       vtd_eval(map[0], o, ri * C + j * VEC, &off, &ptr);
-      Vec<T, VEC> raw = *reinterpret_cast<const Vec<T, VEC>*>(static_cast<const T*>(ptr) + off);
+      Vec<T, VEC> raw = ld_global<Vec<T, VEC>>(static_cast<const T*>(ptr) + off);
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
         v[it][e] = to_float(raw.v[e]);
@@ -617,9 +659,19 @@ int vt_elementwise(int kind, const vt_desc* x, const vt_desc* y, float eps, void
       return l;
     };
     const uint32_t bx = block_log2(*x), by = block_log2(*y);
-    if (bx >= 6 && by >= 6) hipLaunchKernelGGL(k_add_rowsum_blocks<true>, dim3((R + 3) / 4), dim3(256), 0, st, X, Y, (float*)out, R, C, bx, by);
-    else if (bx >= 4 && by >= 4) hipLaunchKernelGGL(k_add_rowsum_blocks<false>, dim3((R + 3) / 4), dim3(256), 0, st, X, Y, (float*)out, R, C, bx, by);
-    else hipLaunchKernelGGL(k_add_rowsum, dim3((R + 3) / 4), dim3(256), 0, st, X, Y, (float*)out, R, C);
+    const dim3 grid((R + 3) / 4);
+    if (bx >= 4 && by >= 4) {
+      RowWalk wx, wy;
+      const bool walk = resolve_row_walk(*x, 1ll << bx, &wx) && resolve_row_walk(*y, 1ll << by, &wy);
+      const bool wide = bx >= 6 && by >= 6;
+#define VT_ROWSUM(WIDE, WALK) \
+  hipLaunchKernelGGL((k_add_rowsum_blocks<WIDE, WALK>), grid, dim3(256), 0, st, wx, wy, (float*)out, R, C, bx, by, X, Y)
+      if (wide && walk) VT_ROWSUM(true, true);
+      else if (wide) VT_ROWSUM(true, false);
+      else if (walk) VT_ROWSUM(false, true);
+      else VT_ROWSUM(false, false);
+#undef VT_ROWSUM
+    } else hipLaunchKernelGGL(k_add_rowsum, grid, dim3(256), 0, st, X, Y, (float*)out, R, C);
     return check_launch("vt_elementwise(add_rowsum)");
   }
   if (kind == VT_EW_LAYERNORM) {

@@ -528,3 +528,119 @@ def test_attention_plan_rejects_what_the_kernel_cannot_read():
         vt.vt_decode_attn_plan(q, kt, v)
     assert ei.value.code == vt.ERR_UNSUPPORTED
     assert vt.lib().vt_decode_attn_plan(None, None, None, 0, None, None, None, None) == vt.ERR_INVALID_ARG
+
+
+# ----------------------------------------------------------------------------------------
+# Row walk: the host's resolution of a [R, C] map into segments that are affine in (row, block)
+# ----------------------------------------------------------------------------------------
+FAKE_BASE = 1 << 40
+
+
+def fake_ptrs(wl):
+    """Distinct, far apart source addresses (never dereferenced on the host)."""
+    return {k: (v.shape, wl.dtype, FAKE_BASE + (i << 34)) for i, (k, v) in enumerate(wl.sources.items())}
+
+
+def check_row_walk(d, ptr_of_src, esz):
+    """Every block address the segments give equals the evaluator's, and the segments tile the
+    [R, C / block] domain exactly once.  Returns the number of segments (0: not resolved)."""
+    R, Cc = d.shape
+    be = d.block()
+    while Cc % be:
+        be //= 2
+    segs = d.row_walk(be)
+    if not segs:
+        return 0
+    covered = np.zeros((R, Cc // be), np.int32)
+    for row_lo, row_hi, blk_lo, blk_hi, base, rs, bs, group, gs in segs:
+        assert 0 <= row_lo < row_hi <= R and 0 <= blk_lo < blk_hi <= Cc // be
+        covered[row_lo:row_hi, blk_lo:blk_hi] += 1
+        for r in range(row_lo, row_hi):
+            for b in range(blk_lo, blk_hi):
+                src, off = d.eval_host((r, b * be))
+                j = b - blk_lo
+                hi = j // group if group else 0
+                assert base + (r - row_lo) * rs + (j - hi * group) * bs + hi * gs == ptr_of_src[src] + off * esz, (r, b, d.dump())
+    assert (covered == 1).all(), d.dump()
+    return len(segs)
+
+
+def test_row_walk_of_the_benchmark_chain():
+    wl = workloads.rowsum_chain_large()
+    specs = fake_ptrs(wl)
+    v = vt.build_chain(wl.chain, specs, "V")
+    segs = v.row_walk(128)
+    x, y = specs["X"][2], specs["Y"][2]
+    # X[a, row, :] is block a of the row: one row further 128 floats, one block further a whole [B, C0] slab
+    assert segs == [(0, 8192, 0, 32, x, 128 * 4, 8192 * 128 * 4, 0, 0), (0, 8192, 32, 40, y, 1024 * 4, 128 * 4, 0, 0)]
+    z = vt.build_chain(wl.chain, specs, "Z")
+    assert z.row_walk(1024) == [(0, 8192, 0, 5, specs["Z"][2], 5120 * 4, 1024 * 4, 0, 0)]
+    # half blocks: two of them share a run of X, then the address jumps to the next slab (two levels)
+    assert v.row_walk(64) == [(0, 8192, 0, 64, x, 128 * 4, 64 * 4, 2, 8192 * 128 * 4), (0, 8192, 64, 80, y, 1024 * 4, 64 * 4, 0, 0)]
+    # double blocks are not contiguous ranges of X; sizes that do not divide the row are refused
+    assert v.row_walk(256) == [] and v.row_walk(96) == []
+
+
+def test_row_walk_refuses_tables_and_stacked_stages():
+    rng = np.random.default_rng(0)
+    src = {"X": rng.normal(size=(12, 32)).astype(np.float32)}
+    idx = rng.permutation(12).astype(np.int32)
+    wl = workloads.Workload("g", "f32", src, [("R", "index_select", ("X",), {"dim": 0, "index": "I"})], {"kind": "none"}, {"I": idx})
+    d = vt.build_chain(wl.chain, fake_ptrs(wl), "R", wl.index_tables)
+    assert d.row_walk(32) == []
+    # a slice that is not aligned to the inner dims, then a reshape: a second stage
+    src = {"X": rng.normal(size=(6, 10)).astype(np.float32)}
+    chain = [("s", "slice", ("X",), {"dim": 1, "start": 1, "stop": 9, "step": 1}), ("R", "reshape", ("s",), {"shape": (12, 4)})]
+    wl = workloads.Workload("s", "f32", src, chain, {"kind": "none"})
+    d = vt.build_chain(wl.chain, fake_ptrs(wl), "R")
+    assert check_row_walk(d, {0: FAKE_BASE}, 4) in (0, 1)
+
+
+@pytest.mark.parametrize("seed", range(120))
+def test_row_walk_equals_the_evaluator_on_random_chains(seed):
+    wl = workloads.random_chain(seed, n_ops=4, max_extent=8)
+    specs = fake_ptrs(wl)
+    try:
+        d0 = vt.build_chain(wl.chain, specs, "R", wl.index_tables)
+    except vt.VtError:
+        pytest.skip("chain not representable")
+    shape = d0.shape
+    n = int(np.prod(shape))
+    # the result seen as [R, C] for every split of its dims into leading and trailing ones
+    resolved = 0
+    for cut in range(len(shape) + 1):
+        rows = int(np.prod(shape[:cut]))
+        chain = list(wl.chain) + [("R2", "reshape", ("R",), {"shape": (rows, n // rows)})]
+        try:
+            d = vt.build_chain(chain, specs, "R2", wl.index_tables)
+        except vt.VtError:
+            continue
+        ptr_of_src = {i: specs[name][2] for i, name in enumerate(d.source_names)}
+        resolved += check_row_walk(d, ptr_of_src, 2 if wl.dtype != "f32" else 4) > 0
+    # nothing to assert on `resolved` per seed: how often the form applies is counted below
+
+
+def test_row_walk_resolves_most_table_free_chains():
+    tried = ok = 0
+    for seed in range(120):
+        wl = workloads.random_chain(seed, n_ops=3, max_extent=8)
+        if wl.index_tables:
+            continue
+        specs = fake_ptrs(wl)
+        try:
+            d0 = vt.build_chain(wl.chain, specs, "R")
+        except vt.VtError:
+            continue
+        shape = d0.shape
+        if len(shape) < 2:
+            continue
+        rows = int(shape[0])
+        chain = list(wl.chain) + [("R2", "reshape", ("R",), {"shape": (rows, int(np.prod(shape)) // rows)})]
+        try:
+            d = vt.build_chain(chain, specs, "R2")
+        except vt.VtError:
+            continue
+        tried += 1
+        ok += len(d.row_walk(max(1, min(d.block(), 1)))) > 0
+    assert tried >= 40, tried
+    print("row walk resolved %d of %d table-free chains at block 1" % (ok, tried))

@@ -302,7 +302,34 @@ def test_add_rowsum_block_path_bit_exact(gpu, rows, xs, ny):
     dw = tio.DeviceWorkload(wl)
     v, z = dw.build("V"), dw.build("Z")
     assert v.block() >= 16
+    be = v.block()
+    while C % be:
+        be //= 2
+    assert v.row_walk(be) and z.row_walk(z.block(C & -C)), "these maps resolve on the host: the kernel takes block addresses from segments"
     out, check = guarded(torch, tio, (B,), "f32")
+    vt.vt_elementwise(vt.EW_ADD_ROWSUM, v, z, 0.0, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(out.cpu().numpy()), bits(ref["out"]))
+    check()
+
+
+@pytest.mark.parametrize("rows,cols,ny", [(37, 64, 16), (130, 1024, 256), (9, 4160, 64)])
+def test_add_rowsum_block_path_through_the_evaluator_bit_exact(gpu, rows, cols, ny):
+    """Rows gathered through an index table: the host cannot resolve the map into segments, and the
+    block addresses come from the evaluator (one evaluation per block)."""
+    vt, tio, torch = gpu
+    rng = np.random.default_rng(17)
+    C = cols + ny
+    src = {"X": rng.normal(size=(rows + 5, cols)).astype(np.float32), "Y": rng.normal(size=(rows, ny)).astype(np.float32),
+           "Z": rng.normal(size=(rows, C)).astype(np.float32)}
+    idx = rng.integers(0, rows + 5, size=rows).astype(np.int32)
+    chain = [("g", "index_select", ("X",), {"dim": 0, "index": "I"}), ("V", "concat", ("g", "Y"), {"dim": 1})]
+    wl = workloads.Workload("rowsum_gathered", "f32", src, chain, {"kind": "add_rowsum", "x": "V", "y": "Z"}, {"I": idx})
+    ref = run_workload(wl)
+    dw = tio.DeviceWorkload(wl)
+    v, z = dw.build("V"), dw.build("Z")
+    assert v.block() >= 16 and v.row_walk(min(v.block(), C & -C)) == []
+    out, check = guarded(torch, tio, (rows,), "f32")
     vt.vt_elementwise(vt.EW_ADD_ROWSUM, v, z, 0.0, out)
     torch.cuda.synchronize()
     assert np.array_equal(bits(out.cpu().numpy()), bits(ref["out"]))
