@@ -198,13 +198,16 @@ int64_t block_elems(const vt_desc& d, int64_t cap);
 constexpr int kRowSegs = 4;
 struct RowSeg {
   uint64_t base;
-  int64_t row_stride, blk_stride, group_stride;
+  int64_t row_stride;
+  uint32_t blk_stride, group_stride;   // a segment's blocks of one row span less than 4 GiB
   uint32_t row_lo, row_hi, blk_lo, blk_hi;
-  uint32_t blk_group, pad;
+  FastDiv blk_group;                   // d = 0: one level
+  uint32_t pad;
 };
 struct RowWalk {
   RowSeg seg[kRowSegs];
   int32_t n;
+  int32_t two_level;                   // some segment has a blk_group
 };
 // Resolves the [R, C] operand d, read in aligned blocks of `be` columns, into such segments.
 // Every piece must be a single stage without tables whose row digits collapse to one stride and

@@ -219,7 +219,7 @@ extern "C" int vt_desc_row_walk(const vt_desc* d, int64_t block_elems_in, int* n
     const vt::RowSeg& sg = w.seg[k];
     int64_t* o = segments + 9 * k;
     o[0] = sg.row_lo, o[1] = sg.row_hi, o[2] = sg.blk_lo, o[3] = sg.blk_hi;
-    o[4] = (int64_t)sg.base, o[5] = sg.row_stride, o[6] = sg.blk_stride, o[7] = sg.blk_group, o[8] = sg.group_stride;
+    o[4] = (int64_t)sg.base, o[5] = sg.row_stride, o[6] = sg.blk_stride, o[7] = sg.blk_group.d, o[8] = sg.group_stride;
   }
   return VT_OK;
 }
@@ -283,13 +283,20 @@ bool resolve_row_walk(const vt_desc& d, int64_t be, RowWalk* w) {
     if (!group_terms(p.v.groups[1], be, &tb) || !terms_two_level(tb, blks, &bs, &b_group, &b1)) return false;
     const char* src = static_cast<const char*>(d.sources[p.src].ptr);
     if (!src) return false;
+    // the kernel adds the block's distance from the row's first block as an unsigned 32-bit number
+    if (bs < 0 || b1 < 0) return false;
+    const int64_t span = b_group ? (b_group - 1) * bs + ((blks - 1) / b_group) * b1 : (blks - 1) * bs;
+    if (span * esz >= (1ll << 32) || blks >= (1ll << 31)) return false;
     RowSeg& sg = w->seg[n++];
     const int64_t zero[2] = {0, 0};
     sg.base = reinterpret_cast<uint64_t>(src) + (uint64_t)(eval_view(d, p.v, zero) * esz);
     sg.row_stride = rs * esz;
-    sg.blk_stride = bs * esz;
-    sg.group_stride = b1 * esz;
-    sg.blk_group = (uint32_t)b_group;
+    sg.blk_stride = (uint32_t)(bs * esz);
+    sg.group_stride = (uint32_t)(b1 * esz);
+    if (b_group) {
+      sg.blk_group = make_fastdiv((uint32_t)b_group);
+      w->two_level = 1;
+    }
     sg.row_lo = (uint32_t)p.lo[0];
     sg.row_hi = (uint32_t)p.hi[0];
     sg.blk_lo = (uint32_t)(p.lo[1] / be);
@@ -302,7 +309,7 @@ bool resolve_row_walk(const vt_desc& d, int64_t be, RowWalk* w) {
         const int64_t local[2] = {r, b * be};
         const uint64_t want = reinterpret_cast<uint64_t>(src) + (uint64_t)(eval_view(d, p.v, local) * esz);
         const int64_t hi = b_group ? b / b_group : 0, lo = b - hi * b_group;
-        if (want != sg.base + (uint64_t)(r * sg.row_stride + lo * sg.blk_stride + hi * sg.group_stride)) return false;
+        if (want != sg.base + (uint64_t)(r * sg.row_stride) + (uint64_t)((uint32_t)lo * sg.blk_stride + (uint32_t)hi * sg.group_stride)) return false;
       }
   }
   w->n = n;

@@ -45,4 +45,24 @@ __device__ __forceinline__ void warm_kernarg_16_and_2(uint32_t also) {
       : "memory");
 }
 
+// lines 0..7 (bytes 0..511): for kernels whose walked arguments fit there (7 * 64 + 4 <= sizeof(arguments))
+__device__ __forceinline__ void warm_kernarg_8() {
+  typedef __attribute__((address_space(4))) const char* karg_t;
+  const uint64_t p = (uint64_t)(karg_t)__builtin_amdgcn_kernarg_segment_ptr();
+  uint32_t d0, d1, d2, d3, d4, d5, d6, d7;
+  asm volatile(
+      "s_load_dword %0, %8, 0x0\n\t"
+      "s_load_dword %1, %8, 0x40\n\t"
+      "s_load_dword %2, %8, 0x80\n\t"
+      "s_load_dword %3, %8, 0xc0\n\t"
+      "s_load_dword %4, %8, 0x100\n\t"
+      "s_load_dword %5, %8, 0x140\n\t"
+      "s_load_dword %6, %8, 0x180\n\t"
+      "s_load_dword %7, %8, 0x1c0\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&s"(d0), "=&s"(d1), "=&s"(d2), "=&s"(d3), "=&s"(d4), "=&s"(d5), "=&s"(d6), "=&s"(d7)
+      : "s"(p)
+      : "memory");
+}
+
 }  // namespace vt

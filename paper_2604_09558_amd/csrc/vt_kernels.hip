@@ -6,6 +6,7 @@
 #include <cstdlib>
 
 #include "vt_device.h"
+#include "vt_kernarg.h"
 #include "vt_numeric.h"
 #include "vt_profile.h"
 
@@ -354,20 +355,47 @@ __device__ __forceinline__ float cursor_read_window(const BlockCursor& cur, uint
   return ld_global<float, true>(base + (uint64_t)((c0 & ((1u << blog) - 1u)) + lane) * 4u);   // read once: streaming
 }
 
-__device__ __forceinline__ void cursor_walk(const RowWalk& W, uint32_t row, uint32_t C, uint32_t blog, uint32_t blk0, uint32_t lane,
+typedef __attribute__((address_space(4))) const RowWalk* kernarg_walk_t;   // a walk inside the kernel-argument segment
+
+__device__ __forceinline__ void cursor_walk(kernarg_walk_t Wp, uint32_t row, uint32_t C, uint32_t blog, uint32_t blk0, uint32_t lane,
                                             BlockCursor& cur) {
+  // The segments are read here, where they are used, and not kept in registers over the kernel's
+  // main loop (the pointer is made opaque so that the reads cannot be moved out of this place).
+  asm volatile("" : "+s"(Wp));
   const uint32_t nb = C >> blog;
   const uint32_t b = min(blk0 + lane, nb - 1);
-  uint64_t a = 0;
+  // Few instructions matter here: every wave of the launch runs this before its first load.  A
+  // lane first picks the fields of the segment that holds its block (the tests on the row are
+  // uniform), then the address is computed once, the block's part in 32 bits.
+  uint64_t base = 0;
+  uint32_t j = 0, bs = 0, gs = 0;
+  FastDiv g = {0, 0, 0};
+  const int n = Wp->n, two_level = Wp->two_level;
 #pragma unroll
   for (int k = 0; k < kRowSegs; ++k) {
-    const RowSeg& sg = W.seg[k];
-    if (k < W.n && row >= sg.row_lo && row < sg.row_hi && b >= sg.blk_lo && b < sg.blk_hi) {
-      const uint32_t j = b - sg.blk_lo, hi = sg.blk_group ? j / sg.blk_group : 0u, lo = j - hi * sg.blk_group;
-      a = sg.base + (uint64_t)((int64_t)(row - sg.row_lo) * sg.row_stride + (int64_t)lo * sg.blk_stride + (int64_t)hi * sg.group_stride);
+    if (k < n) {
+      const __attribute__((address_space(4))) RowSeg* sg = &Wp->seg[k];
+      if (row >= sg->row_lo && row < sg->row_hi) {
+        const uint64_t row_base = sg->base + (uint64_t)((int64_t)(row - sg->row_lo) * sg->row_stride);
+        const bool in = b >= sg->blk_lo && b < sg->blk_hi;
+        base = in ? row_base : base;
+        j = in ? b - sg->blk_lo : j;
+        bs = in ? sg->blk_stride : bs;
+        if (two_level) {
+          gs = in ? sg->group_stride : gs;
+          g.d = in ? sg->blk_group.d : g.d;
+          g.magic = in ? sg->blk_group.magic : g.magic;
+          g.shift = in ? sg->blk_group.shift : g.shift;
+        }
+      }
     }
   }
-  cur.addr = a;
+  uint32_t off = j * bs;
+  if (two_level) {
+    const uint32_t hi = g.d ? fdiv(j, g) : 0u, lo = j - hi * g.d;
+    off = g.d ? lo * bs + hi * gs : off;
+  }
+  cur.addr = base + off;
   cur.first = blk0;
 }
 
@@ -376,10 +404,19 @@ VT_PROF_DECLARE(add_rowsum)
 // WIDE: both operands keep blocks of at least 64 columns.  WALK: block addresses from the host's
 // segments (wx, wy) instead of the evaluator on X and Y.
 template <bool WIDE, bool WALK>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8))) k_add_rowsum_blocks(const RowWalk wx, const RowWalk wy, float* __restrict__ out, uint32_t R, uint32_t C,
+__global__ void __launch_bounds__(256) k_add_rowsum_blocks(const RowWalk wx, const RowWalk wy, float* __restrict__ out, uint32_t R, uint32_t C,
                                                            uint32_t bx, uint32_t by, const DevDesc X, const DevDesc Y) {
   VT_PROF_BEGIN();
   VT_PROF(0);
+  if (WALK) {
+    // the segments and the scalars are read in several rounds, each a miss of the scalar cache:
+    // their eight lines are requested at once (0.4 us of 56 on the 335 MB chain)
+    static_assert(2 * sizeof(RowWalk) + sizeof(float*) + 4 * sizeof(uint32_t) <= 512, "the walked arguments lie in the first eight lines");
+    warm_kernarg_8();
+  }
+  // wx and wy are the first two arguments
+  const kernarg_walk_t kwalk = (kernarg_walk_t)__builtin_amdgcn_kernarg_segment_ptr();
+  (void)wx, (void)wy;
   __shared__ DevDesc maps[2];                         // unused (and not allocated) with WALK
   if (!WALK) {
     const DevDesc* const src[2] = {&X, &Y};
@@ -395,16 +432,17 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8))
   BlockCursor cx, cy;
   for (uint32_t c0 = 0; c0 < C;) {
     if (c0 % span_x == 0) {
-      if (WALK) cursor_walk(wx, row, C, bx, c0 >> bx, lane, cx);
+      if (WALK) cursor_walk(kwalk, row, C, bx, c0 >> bx, lane, cx);
       else cursor_load(maps[0], row, C, bx, c0 >> bx, lane, cx);
     }
     if (c0 % span_y == 0) {
-      if (WALK) cursor_walk(wy, row, C, by, c0 >> by, lane, cy);
+      if (WALK) cursor_walk(kwalk + 1, row, C, by, c0 >> by, lane, cy);
       else cursor_load(maps[1], row, C, by, c0 >> by, lane, cy);
     }
     const uint32_t end = min(C, min((c0 / span_x + 1) * span_x, (c0 / span_y + 1) * span_y));
     VT_PROF_ONCE(2);
     // whole windows of 64 columns, eight at a time so that sixteen loads are in flight per lane
+    // (thirty-two measured the same)
     for (; c0 + 512 <= end; c0 += 512) {
       float xv[8], yv[8];
 #pragma unroll
