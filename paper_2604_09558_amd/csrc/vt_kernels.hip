@@ -698,9 +698,12 @@ int vt_elementwise(int kind, const vt_desc* x, const vt_desc* y, float eps, void
     };
     const uint32_t bx = block_log2(*x), by = block_log2(*y);
     const dim3 grid((R + 3) / 4);
-    if (bx >= 4 && by >= 4) {
-      RowWalk wx, wy;
-      const bool walk = resolve_row_walk(*x, 1ll << bx, &wx) && resolve_row_walk(*y, 1ll << by, &wy);
+    // Block addresses from host-resolved segments whenever both maps have that form, whatever the
+    // block size (single elements included: a dozen instructions per address instead of the
+    // evaluator); else the evaluator once per block of at least 16 columns, else once per element.
+    RowWalk wx, wy;
+    const bool walk = resolve_row_walk(*x, 1ll << bx, &wx) && resolve_row_walk(*y, 1ll << by, &wy);
+    if (walk || (bx >= 4 && by >= 4)) {
       const bool wide = bx >= 6 && by >= 6;
 #define VT_ROWSUM(WIDE, WALK) \
   hipLaunchKernelGGL((k_add_rowsum_blocks<WIDE, WALK>), grid, dim3(256), 0, st, wx, wy, (float*)out, R, C, bx, by, X, Y)
