@@ -336,6 +336,53 @@ def test_add_rowsum_block_path_through_the_evaluator_bit_exact(gpu, rows, cols, 
     check()
 
 
+def test_add_rowsum_random_chains_bit_exact(gpu):
+    """Random chains seen as [R, C] for every split of their dims, added to a dense operand and
+    summed by rows: bit for bit the oracle's fixed-order sum, whether the kernel takes its block
+    addresses from host-resolved segments (one or two levels, several pieces, any block size) or
+    from the evaluator."""
+    vt, tio, torch = gpu
+    rng = np.random.default_rng(23)
+    walked = evaluated = 0
+    for seed in range(100):
+        wl = workloads.random_chain(seed, n_ops=4, max_extent=8)
+        dense = dm_ops.run_chain(wl.chain, wl.sources, wl.index_tables)["R"]
+        shape = dense.shape
+        n = int(np.prod(shape))
+        for cut in range(len(shape) + 1):
+            rows = int(np.prod(shape[:cut]))
+            cols = n // rows
+            z = rng.normal(size=(rows, cols)).astype(np.float32) * 8.0
+            src = dict(wl.sources)
+            src["Zr"] = z
+            chain = list(wl.chain) + [("R2", "reshape", ("R",), {"shape": (rows, cols)})]
+            wl2 = workloads.Workload("rowsum_random", "f32", src, chain, {"kind": "add_rowsum", "x": "R2", "y": "Zr"}, wl.index_tables)
+            dw = tio.DeviceWorkload(wl2)
+            try:
+                v, zd = dw.build("R2"), dw.build("Zr")
+            except vt.VtError as e:
+                assert e.code == vt.ERR_UNSUPPORTED
+                continue
+            be = v.block()
+            while cols % be:
+                be //= 2
+            ref = consumers.add_rowsum_f32(np.ascontiguousarray(dense.reshape(rows, cols)), z)
+            out, check = guarded(torch, tio, (rows,), "f32")
+            try:
+                vt.vt_elementwise(vt.EW_ADD_ROWSUM, v, zd, 0.0, out)
+            except vt.VtError as e:
+                assert e.code == vt.ERR_UNSUPPORTED, str(e)     # more pieces than the device form of a map holds
+                continue
+            torch.cuda.synchronize()
+            if v.row_walk(be):
+                walked += 1
+            else:
+                evaluated += 1
+            assert np.array_equal(bits(out.cpu().numpy()), bits(ref)), (seed, cut, v.dump())
+            check()
+    assert walked >= 100 and evaluated >= 100, (walked, evaluated)
+
+
 def test_add_rowsum_at_a_memory_bound_size_bit_exact(gpu):
     """The elementwise consumer at the size the benchmark times it (335 MB read), against the
     oracle's fixed-order sum, bit for bit, virtual and through the lean materialized path."""
