@@ -86,5 +86,24 @@ def build(verbose: bool = True, jobs: int = 4, profile: bool = False) -> str:
     return lib
 
 
+def build_ceilings(verbose: bool = True) -> str:
+    """Compile csrc/vt_ceilings.hip, a standalone program that measures what plain kernels with the
+    consumers' access patterns reach on the machine (no part of the library; nothing loads it)."""
+    exe = os.path.join(HERE, "vt_ceilings")
+    cmd = [hipcc(), "-O3", "-std=c++17"] + DEVICE[:5] + ["-o", exe, os.path.join(CSRC, "vt_ceilings.hip")]
+    if verbose:
+        print("[build]", " ".join(cmd), flush=True)
+    out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    text = "\n".join(l for l in out.stdout.splitlines() if "is not a recognized feature" not in l)
+    if text.strip() and verbose:
+        print(text)
+    if out.returncode != 0:
+        raise RuntimeError("hipcc failed on vt_ceilings.hip")
+    return exe
+
+
 if __name__ == "__main__":
-    build(profile="--profile" in sys.argv)
+    if "--ceilings" in sys.argv:
+        build_ceilings()
+    else:
+        build(profile="--profile" in sys.argv)
