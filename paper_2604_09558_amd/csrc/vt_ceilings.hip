@@ -125,13 +125,14 @@ int main() {
   CK(hipEventCreate(&e1));
   float* out = static_cast<float*>(dev_zero(1 << 20, 0));
   {
-    // 335 MB (the add + row-sum chain) and 134 MB (the bytes of the decode attention at 4096 keys)
-    const uint32_t shapes[2][2] = {{8192, 5120}, {8192, 2048}};
+    // 335 MB (the add + row-sum chain), 134 MB (the bytes of the decode attention at 4096 keys), and
+    // 50 MB (the projection's weights) read by 1228 and by 4912 waves
+    const uint32_t shapes[4][2] = {{8192, 5120}, {8192, 2048}, {1228, 5120}, {4912, 1280}};
     for (const auto& sh : shapes) {
       const uint32_t R = sh[0], C = sh[1];
       const size_t n = (size_t)R * C;
-      const int nb = 4;
-      float *X[nb], *Y[nb];
+      const int nb = n * 8 < (64u << 20) ? 12 : 4;     // small inputs: more copies, so that none stays in the last-level cache
+      float *X[12], *Y[12];
       for (int i = 0; i < nb; ++i) X[i] = static_cast<float*>(dev_zero(n * 4, 0)), Y[i] = static_cast<float*>(dev_zero(n * 4, 0));
       const double us = timed_us(60, [&](int i) { hipLaunchKernelGGL(k_read_rows, dim3(R / 4), dim3(256), 0, 0, X[i % nb], Y[i % nb], out, R, C); });
       char what[128];
