@@ -54,16 +54,22 @@ def build(verbose: bool = True, jobs: int = 4, profile: bool = False) -> str:
         cmd = [hipcc()] + COMMON + (["-DVT_PROFILE"] if profile else []) + (DEVICE if src.endswith(".hip") else []) + ["-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print("[build]", " ".join(cmd), flush=True)
-        procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+        # the compiler's remarks go to a file: a pipe that nobody reads while the build waits for
+        # another compiler would fill up and stall this one
+        log = open(obj + ".log", "w+")
+        procs.append((src, subprocess.Popen(cmd, stdout=log, stderr=subprocess.STDOUT, text=True), log))
         objs.append(obj)
-        while sum(p.poll() is None for _, p in procs) >= jobs:
-            for _, p in procs:
+        while sum(p.poll() is None for _, p, _ in procs) >= jobs:
+            for _, p, _ in procs:
                 if p.poll() is None:
                     p.wait()
                     break
     failed = False
-    for src, p in procs:
-        out, _ = p.communicate()
+    for src, p, log in procs:
+        p.wait()
+        log.seek(0)
+        out = log.read()
+        log.close()
         for kernel, scratch in scratch_report(out):
             if scratch and any(k in kernel for k in NO_SCRATCH):
                 print("[build] FAILED: %s uses %d bytes of scratch per lane (%s)" % (kernel, scratch, src), file=sys.stderr)

@@ -535,6 +535,120 @@ __global__ void __launch_bounds__(256) k_layernorm(const DevDesc X, T* __restric
   (void)outer;
 }
 
+// The same LayerNorm, same lane-to-element assignment and same order of operations (so the same
+// bits), for maps that keep every row one contiguous range of a source: the map is applied once
+// per ROW instead of once per vector.  A wave takes 32 consecutive rows; lane l evaluates the
+// address of row l (one evaluation serves 32 rows where the kernel above needs one per group of
+// 64 / lpr rows: the evaluator's several hundred instructions, not the memory, bound that kernel),
+// and the rows are then read in passes of 64 / lpr rows, their addresses handed round by shuffle,
+// eight vectors per lane in flight.  ITS = vectors per lane and row (1, 2 or 4).
+constexpr uint32_t kLnRowsPerWave = 32;   // (or one pass's rows, if that is more)
+
+template <typename T, int VEC, int ITS>
+__global__ void __launch_bounds__(256) k_layernorm_rows(const DevDesc X, T* __restrict__ out, uint32_t rows, uint32_t C,
+                                                        uint32_t lpr_log2, float eps, uint32_t rows_inner) {
+  __shared__ DevDesc map[1];
+  {
+    const DevDesc* const from[1] = {&X};
+    stage_maps(map, from);
+  }
+  constexpr int U = 8 / ITS;                            // passes in flight
+  const uint32_t lpr = 1u << lpr_log2;
+  const uint32_t rpw = 64u >> lpr_log2;                 // rows per pass
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t sub = lane & (lpr - 1u);
+  const uint32_t rw = max(kLnRowsPerWave, rpw);          // rows of this wave
+  const uint32_t row0 = (blockIdx.x * 4u + (threadIdx.x >> 6)) * rw;
+  if (row0 >= rows) return;
+  const uint32_t nvec = C / VEC;
+  uint64_t row_addr;
+  {
+    const uint32_t r = min(row0 + (lane & (rw - 1u)), rows - 1u);
+    const uint32_t o = r / rows_inner, ri = r - o * rows_inner;
+    int64_t off;
+    const void* ptr;
+    vtd_eval(map[0], o, ri * C, &off, &ptr);
+    row_addr = reinterpret_cast<uint64_t>(ptr) + (uint64_t)(off * (int64_t)sizeof(T));
+  }
+  const uint32_t passes = rw / rpw;
+  for (uint32_t p0 = 0; p0 < passes; p0 += U) {
+    Vec<T, VEC> raw[U][ITS];
+    bool live[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t rl = min((p0 + u) * rpw + (lane >> lpr_log2), rw - 1u);
+      live[u] = p0 + u < passes && row0 + rl < rows;
+      const uint64_t a = shfl_u64(row_addr, (int)rl);
+#pragma unroll
+      for (int it = 0; it < ITS; ++it) {
+        // unconditional (a lane without a vector of its own reads a valid one again and drops it:
+        // rows past the end were clamped to the last row above), so that all loads of the round
+        // are in flight together
+        const uint32_t j = min(sub + it * lpr, nvec - 1u);
+        raw[u][it] = ld_global<Vec<T, VEC>, true>(a + (uint64_t)j * (VEC * sizeof(T)));
+      }
+    }
+    // The U passes are independent: every step below is done for all of them before the next
+    // one, so that their shuffles are in flight together (per pass the operations and their
+    // order are those of k_layernorm).
+    float v[U][ITS][VEC];
+    float sum[U], sq[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      sum[u] = 0.0f;
+#pragma unroll
+      for (int it = 0; it < ITS; ++it) {
+        const bool mine = live[u] && sub + it * lpr < nvec;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          v[u][it][e] = mine ? to_float(raw[u][it].v[e]) : 0.0f;
+          if (mine) sum[u] += v[u][it][e];
+        }
+      }
+    }
+    for (uint32_t s = lpr >> 1; s >= 1; s >>= 1) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) sum[u] += __shfl_xor(sum[u], (int)s, 64);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float mean = sum[u] / (float)C;
+      sum[u] = mean;
+      sq[u] = 0.0f;
+#pragma unroll
+      for (int it = 0; it < ITS; ++it) {
+        if (sub + it * lpr < nvec) {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) {
+            float dlt = v[u][it][e] - mean;
+            sq[u] += dlt * dlt;
+          }
+        }
+      }
+    }
+    for (uint32_t s = lpr >> 1; s >= 1; s >>= 1) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) sq[u] += __shfl_xor(sq[u], (int)s, 64);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float mean = sum[u];
+      const float rstd = 1.0f / sqrtf(sq[u] / (float)C + eps);
+      const uint32_t row = row0 + (p0 + u) * rpw + (lane >> lpr_log2);
+#pragma unroll
+      for (int it = 0; it < ITS; ++it) {
+        const uint32_t j = sub + it * lpr;
+        if (live[u] && j < nvec) {
+          Vec<T, VEC> o;
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) o.v[e] = from_float<T>((v[u][it][e] - mean) * rstd);
+          *reinterpret_cast<Vec<T, VEC>*>(out + (size_t)row * C + (size_t)j * VEC) = o;
+        }
+      }
+    }
+  }
+}
+
 template <typename T>
 static int launch_layernorm_t(const vt_desc& d, const DevDesc& D, void* out, float eps, int64_t outer, int64_t inner,
                               hipStream_t stream) {
@@ -549,6 +663,24 @@ static int launch_layernorm_t(const vt_desc& d, const DevDesc& D, void* out, flo
   int64_t rows = outer * inner / C;
   if (rows >= (1ll << 31)) return fail(VT_ERR_UNSUPPORTED, "layernorm: too many rows");
   uint32_t rows_inner = (uint32_t)(inner / C);
+  // every row one contiguous range of a source: one evaluation of the map per row
+  bool rows_contiguous = d.run % C == 0;
+  for (const Piece& p : d.pieces) rows_contiguous = rows_contiguous && p.lo[n - 1] == 0 && p.hi[n - 1] == C;
+  if ((C & (C - 1)) == 0 && block_elems(d, C) == C) rows_contiguous = true;
+  if (rows_contiguous && vec * (int)sizeof(T) == 16) {   // full 16-byte vectors only: the other widths keep the kernel above
+    const int its = nvec <= (int64_t)(1 << lpr_log2) ? 1 : nvec <= (int64_t)(2 << lpr_log2) ? 2 : 4;
+    constexpr int V16 = 16 / (int)sizeof(T);
+    const int64_t rows_per_wg = 4 * (int64_t)std::max<uint32_t>(kLnRowsPerWave, 64u >> lpr_log2);
+    dim3 grid_rows((unsigned)((rows + rows_per_wg - 1) / rows_per_wg));
+#define LN_ROWS(I)                                                                                                            \
+  hipLaunchKernelGGL((k_layernorm_rows<T, V16, I>), grid_rows, dim3(256), 0, stream, D, (T*)out, (uint32_t)rows, (uint32_t)C, \
+                     lpr_log2, eps, rows_inner)
+    if (its == 1) LN_ROWS(1);
+    else if (its == 2) LN_ROWS(2);
+    else LN_ROWS(4);
+#undef LN_ROWS
+    return check_launch("vt_elementwise(layernorm)");
+  }
   uint32_t rpw = 64u >> lpr_log2;
   dim3 grid((unsigned)((rows + 4 * rpw - 1) / (4 * rpw)));
 #define LN_LAUNCH(V)                                                                                          \

@@ -172,27 +172,39 @@ def test_rowsum_order_pin_on_gpu(gpu):
     assert np.array_equal(out.cpu().numpy(), ref)
 
 
-@pytest.mark.parametrize("dtype,C", [("f16", 128), ("bf16", 96), ("f32", 200), ("f16", 1024), ("f16", 130)])
-def test_layernorm_virtual_rows(gpu, dtype, C):
+@pytest.mark.parametrize("dtype,C,R,cut", [
+    ("f16", 128, 6, 0), ("bf16", 96, 6, 0), ("f32", 200, 6, 0), ("f16", 1024, 6, 0), ("f16", 130, 6, 0),
+    # more than one wave's 64 rows and a ragged last wave (243 rows); two and four vectors per lane
+    ("f16", 128, 9, 0), ("bf16", 1024, 9, 0), ("f16", 2048, 9, 0), ("f32", 512, 9, 0), ("f32", 1024, 9, 0),
+    # the last dim sliced: rows are no longer whole contiguous ranges as far as the map's run says,
+    # or are contiguous but start off the vector grid
+    ("f16", 128, 9, 8), ("f32", 200, 9, 4), ("bf16", 96, 9, 3),
+])
+def test_layernorm_virtual_rows(gpu, dtype, C, R, cut):
+    """LayerNorm over window-partitioned rows: the per-row kernel (one evaluation of the map per
+    row, for maps that keep rows contiguous and 16-byte vectors) and the per-vector kernel."""
     vt, tio, torch = gpu
     rng = np.random.default_rng(7)
-    B, R, win = 2, 6, 3
+    B, win = 3 if R == 9 else 2, 3
     x = workloads.encode((rng.normal(size=(B, R, R, C)) * 2 + 0.5).astype(np.float32), dtype)
     nw = R // win
     chain = [("x1", "reshape", ("X",), {"shape": (B, nw, win, nw, win, C)}),
              ("x2", "permute", ("x1",), {"perm": (0, 1, 3, 2, 4, 5)}),
-             ("T", "reshape", ("x2",), {"shape": (B * nw * nw, win * win, C)})]
+             ("T0" if cut else "T", "reshape", ("x2",), {"shape": (B * nw * nw, win * win, C)})]
+    if cut:
+        chain.append(("T", "slice", ("T0",), {"dim": 2, "start": cut, "stop": C, "step": 1}))
     wl = workloads.Workload("ln", dtype, {"X": x}, chain, {"kind": "materialize", "x": "T"})
     dense = dm_ops.run_chain(chain, wl.sources)["T"]
     ref = consumers.layernorm(consumers.decode(dense, dtype), 1e-5)
     dw = tio.DeviceWorkload(wl)
     d = dw.build("T")
-    out = dw.empty(dense.shape)
+    out, check = guarded(torch, tio, dense.shape, dtype)
     vt.vt_elementwise(vt.EW_LAYERNORM, d, None, 1e-5, out)
     torch.cuda.synchronize()
     got = tio.to_host_f64(out)
     tol = {"f32": 2e-6, "f16": 2e-3, "bf16": 1.6e-2}[dtype]      # output rounding of values up to ~4
     assert np.max(np.abs(got - ref)) <= tol * max(1.0, np.max(np.abs(ref)))
+    check()
 
 
 # ------------------------------------------------------------------ block-wise paths
