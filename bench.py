@@ -373,7 +373,7 @@ def chain_stats(torch, name, no_graph=False, with_materialized=True):
     m_launches = max(3, min(launches, 24) if name != "c5" else 3)
     full = [make_full(i) for i in range(n_rot)]
     torch.cuda.synchronize()
-    f = stats(sample_launches(torch, [mk(p) for p in full], m_launches, graph_ok and name == "c1", warmup=n_rot))
+    f = stats(sample_launches(torch, [mk(p) for p in full], m_launches, graph_ok, warmup=n_rot))
     out["materialized_full_us"] = f
     out["speedup_vs_materialized_full"] = round(f["median"] / v["median"], 3)
     out["intermediate_bytes_saved_vs_full"] = saved(full[0])
@@ -382,7 +382,7 @@ def chain_stats(torch, name, no_graph=False, with_materialized=True):
     if lean is not None:
         lp = [lean(i) for i in range(n_rot)]
         torch.cuda.synchronize()
-        ls = stats(sample_launches(torch, [mk(p) for p in lp], m_launches, graph_ok and name == "c1", warmup=n_rot))
+        ls = stats(sample_launches(torch, [mk(p) for p in lp], m_launches, graph_ok, warmup=n_rot))
         out["materialized_lean_us"] = ls
         out["speedup_vs_materialized_lean"] = round(ls["median"] / v["median"], 3)
         out["intermediate_bytes_saved_vs_lean"] = int(lp[0].bytes_written)

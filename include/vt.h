@@ -145,6 +145,18 @@ int vt_desc_as_strided(const vt_desc* d, int* is_strided, int64_t* stride, int64
  * when both resolve, and through the evaluator otherwise. */
 int vt_desc_row_walk(const vt_desc* d, int64_t block_elems, int* n_segments, int64_t* segments);
 
+/* The general block-wise form (Sec. 4.2): the virtual tensor, in row-major order, is cut into
+ * units of unit_elems elements (unit_elems divides the element count: the blocks of a copy, the
+ * rows of a row-wise consumer).  If the map is a single index stage without tables, the address of
+ * unit u is base + sum_t ((u / div_t) % mod_t) * coef_t in the piece that holds it, with at most
+ * five terms per piece and four pieces; the copy kernels compute block addresses from these
+ * terms when the map resolves (*resolved = 1), and through the evaluator otherwise.  This call resolves the map and evaluates the resolved form, on the host,
+ * with the routine the kernels use: addresses[k] receives the address of the first element of
+ * unit first + k, k in [0, count) (count may be 0: only *resolved is set).  Host only; the
+ * sources need non-NULL pointers, which are never dereferenced. */
+int vt_desc_walk_addresses(const vt_desc* d, int64_t unit_elems, int64_t first, int64_t count, int* resolved,
+                           uint64_t* addresses);
+
 /* Piece p: its box [lo,hi) in virtual index space, its source number and its own run. */
 int vt_desc_piece(const vt_desc* d, int p, int64_t* lo, int64_t* hi, int* src_id, int64_t* run);
 /* CPU evaluation of the map at one virtual index (host logic; used by tests).  vindex holds

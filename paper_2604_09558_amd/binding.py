@@ -75,6 +75,7 @@ def lib():
         L.vt_desc_block.argtypes = [P, C.c_int64, C.POINTER(C.c_int64)]
         L.vt_desc_as_strided.argtypes = [P, C.POINTER(C.c_int), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
         L.vt_desc_row_walk.argtypes = [P, C.c_int64, C.POINTER(C.c_int), C.POINTER(C.c_int64)]
+        L.vt_desc_walk_addresses.argtypes = [P, C.c_int64, C.c_int64, C.c_int64, C.POINTER(C.c_int), C.POINTER(C.c_uint64)]
         L.vt_eval_host.argtypes = [P, C.POINTER(C.c_int64), C.POINTER(C.c_int), C.POINTER(C.c_int64)]
         L.vt_eval_device_form.argtypes = [P, C.POINTER(C.c_int64), C.POINTER(C.c_int), C.POINTER(C.c_int64)]
         L.vt_desc_dump.argtypes = [P, C.c_char_p, C.c_size_t]
@@ -220,6 +221,21 @@ class Desc:
         seg = (C.c_int64 * 36)()
         _check(lib().vt_desc_row_walk(self.handle, block_elems, C.byref(n), seg))
         return [tuple(seg[9 * k + i] for i in range(9)) for k in range(n.value)]
+
+    def walk_addresses(self, unit_elems, first=0, count=None):
+        """Addresses of the units [first, first + count) of unit_elems elements each, computed from the map's
+        resolved term form (the kernels' own routine, run on the host); None if the map does not resolve."""
+        n = 1
+        for e in self.shape:
+            n *= e
+        if count is None:
+            count = n // unit_elems - first if unit_elems > 0 else 0
+        flag = C.c_int()
+        buf = (C.c_uint64 * max(count, 1))()
+        _check(lib().vt_desc_walk_addresses(self.handle, unit_elems, first, count, C.byref(flag), buf))
+        if not flag.value:
+            return None
+        return [buf[i] for i in range(count)]
 
     def piece(self, p):
         lo, hi = (C.c_int64 * VT_MAX_DIMS)(), (C.c_int64 * VT_MAX_DIMS)()

@@ -215,6 +215,69 @@ struct RowWalk {
 // evaluator at the corners and the centre of every segment.  False (w->n = 0) for any other map.
 bool resolve_row_walk(const vt_desc& d, int64_t be, RowWalk* w);
 
+// The general form of the same idea, for any index space cut into equal units (blocks of a copy,
+// rows of a row-wise consumer): unit u of the virtual tensor, in row-major order, starts at
+//   base + sum over terms of ((u / div) % mod) * coef        bytes,
+// in the piece that holds it.  Every single-stage map without tables has this form: each digit of
+// each dim is one term, digits whose strides nest collapse into one, digits below the unit vanish.
+// A piece that does not span a dim completely (Concat) is recognised by a test on that dim's
+// coordinate, lo <= x < hi with x = (u / t_div) % t_mod (one such dim per piece), and the digits
+// of that dim are terms in x - lo instead of u.  A dozen instructions per term, against several
+// hundred for the evaluator's walk over the map.
+constexpr int kWalkPieces = 4;
+constexpr int kWalkTerms = 5;
+struct WalkTerm {
+  FastDiv div, mod;        // mod.d == 0: no modulo (the outermost term)
+  uint32_t coef;           // bytes; a piece's units span less than 4 GiB
+  uint32_t on_coord;       // the term is a function of x - lo (the tested dim's local coordinate), not of u
+};
+struct WalkPiece {
+  uint64_t base;
+  WalkTerm term[kWalkTerms];   // unused ones: div 1, no modulo, coefficient 0
+  int32_t n_terms;
+  int32_t has_test;            // 0: t_div 1, no modulo, [t_lo, t_hi) = [0, 2^32 - 1): always true
+  FastDiv t_div, t_mod;
+  uint32_t t_lo, t_hi;
+};
+struct BlockWalk {
+  WalkPiece piece[kWalkPieces];
+  int32_t n;               // 0: not resolved
+  int32_t pad;
+};
+// Resolves d, cut into units of `unit` elements (unit divides the element count; the caller
+// guarantees that a unit is one contiguous range of a source if it relies on that), into this
+// form; the result is checked against the evaluator on a sample of units.  False (w->n = 0) for
+// maps with tables, several stages, more pieces or terms than the form holds, 2^31 elements or more.
+bool resolve_block_walk(const vt_desc& d, int64_t unit, BlockWalk* w);
+
+// Address of unit u.  W: a pointer to the walk (generic, or into the kernel-argument segment).
+// A piece is copied as a whole (a few wide reads) and evaluated without branches: the host fills
+// unused terms with coefficient 0 and a piece without a test with one that always holds.
+template <typename WalkPtr>
+__host__ __device__ __forceinline__ uint64_t walk_address(WalkPtr W, uint32_t u) {
+  uint64_t addr = 0;
+  const int n = W->n;
+#pragma unroll
+  for (int p = 0; p < kWalkPieces; ++p) {
+    if (p < n) {
+      WalkPiece pc;
+      __builtin_memcpy(&pc, &W->piece[p], sizeof(WalkPiece));
+      const uint32_t xq = fdiv(u, pc.t_div), x = xq - fdiv(xq, pc.t_mod) * pc.t_mod.d;
+      const bool in = x >= pc.t_lo && x < pc.t_hi;
+      const uint32_t v = x - pc.t_lo;                   // local coordinate of the tested dim
+      uint32_t off = 0;
+#pragma unroll
+      for (int t = 0; t < kWalkTerms; ++t) {
+        uint32_t q = fdiv(pc.term[t].on_coord ? v : u, pc.term[t].div);
+        q -= fdiv(q, pc.term[t].mod) * pc.term[t].mod.d;   // mod.d == 0 (no modulo): magic 0 gives 0
+        off += q * pc.term[t].coef;
+      }
+      addr = in ? pc.base + off : addr;
+    }
+  }
+  return addr;
+}
+
 // launch bookkeeping shared by the kernels' host wrappers
 int check_launch(const char* what);
 // VT_OK if the descriptor can be the target of a store: no two virtual elements share a physical one.

@@ -224,6 +224,20 @@ extern "C" int vt_desc_row_walk(const vt_desc* d, int64_t block_elems_in, int* n
   return VT_OK;
 }
 
+extern "C" int vt_desc_walk_addresses(const vt_desc* d, int64_t unit_elems, int64_t first, int64_t count, int* resolved,
+                                      uint64_t* addresses) {
+  if (!d || !resolved || unit_elems < 1 || first < 0 || count < 0 || (count > 0 && !addresses))
+    return vt::fail(VT_ERR_INVALID_ARG, "vt_desc_walk_addresses: NULL argument or negative range");
+  vt::BlockWalk w;
+  *resolved = vt::resolve_block_walk(*d, unit_elems, &w) ? 1 : 0;
+  if (!*resolved) return VT_OK;
+  int64_t numel = 1;
+  for (int64_t e : d->shape) numel *= e;
+  if (first + count > numel / unit_elems) return vt::fail(VT_ERR_RANGE, "vt_desc_walk_addresses: units past the end of the tensor");
+  for (int64_t k = 0; k < count; ++k) addresses[k] = vt::walk_address(static_cast<const vt::BlockWalk*>(&w), (uint32_t)(first + k));
+  return VT_OK;
+}
+
 namespace vt {
 
 // Terms of a digit group as a function of u, where the local coordinate is v = u * unit: every
@@ -314,6 +328,171 @@ bool resolve_row_walk(const vt_desc& d, int64_t be, RowWalk* w) {
   }
   w->n = n;
   return n > 0;
+}
+
+// ---- resolve_block_walk
+namespace {
+struct RawTerm {
+  int64_t div, mod, coef;   // ((L / div) % mod) * coef, L and coef in elements; mod = 0: no modulo
+  bool on_coord = false;    // a function of the tested dim's local coordinate instead of L
+};
+// The same term as a function of u = L / unit (L a multiple of unit).  0: vanishes, 1: converted, -1: neither.
+int term_in_units(const RawTerm& t, int64_t unit, RawTerm* out) {
+  if (t.div % unit == 0) {
+    *out = {t.div / unit, t.mod, t.coef, t.on_coord};
+    return 1;
+  }
+  if (unit % t.div) return -1;
+  const int64_t m = unit / t.div;                      // the digit's value at L = u * unit is (u * m) % mod
+  if (t.mod == 0) {                                    // no modulo: u * m
+    *out = {1, 0, t.coef * m, t.on_coord};
+    return 1;
+  }
+  if (m % t.mod == 0) return 0;
+  if (t.mod % m) return -1;
+  *out = {1, t.mod / m, t.coef * m, t.on_coord};
+  return 1;
+}
+}  // namespace
+
+bool resolve_block_walk(const vt_desc& d, int64_t unit, BlockWalk* w) {
+  memset(w, 0, sizeof(*w));
+  const int n = (int)d.shape.size();
+  if (n < 1 || d.pieces.empty() || d.pieces.size() > (size_t)kWalkPieces || unit < 1) return false;
+  int64_t numel = 1;
+  for (int64_t e : d.shape) numel *= e;
+  if (numel < 1 || numel >= (1ll << 31) || numel % unit) return false;
+  const int64_t units = numel / unit;
+  const int esz = dtype_size(d.dtype);
+  std::vector<int64_t> Q(n, 1);                        // elements per step of dim i
+  for (int i = n - 2; i >= 0; --i) Q[i] = Q[i + 1] * d.shape[i + 1];
+  int np = 0;
+  for (const Piece& p : d.pieces) {
+    if (!p.v.lower.empty() || (int)p.v.groups.size() != n) return false;
+    const char* src = static_cast<const char*>(d.sources[p.src].ptr);
+    if (!src) return false;
+    bool empty = false;
+    for (int i = 0; i < n; ++i) empty = empty || p.hi[i] <= p.lo[i];
+    if (empty) continue;
+    std::vector<RawTerm> ut;                            // terms in units
+    int restricted = -1;
+    bool starts_no_unit = false;
+    int64_t extent_v = 0;                               // extent of the tested dim's local coordinate, in its units
+    WalkPiece& wp = w->piece[np];
+    memset(&wp, 0, sizeof(wp));
+    // what the branch-free evaluation needs of unused fields: terms that add nothing, a test that holds
+    for (WalkTerm& t : wp.term) t.div = make_fastdiv(1);
+    wp.t_div = make_fastdiv(1);
+    wp.t_hi = 0xffffffffu;
+    for (int i = 0; i < n && !starts_no_unit; ++i) {
+      const std::vector<Digit>& g = p.v.groups[i];
+      const int64_t S = d.shape[i];
+      for (const Digit& dg : g)
+        if (dg.table >= 0) return false;
+      if (p.lo[i] == 0 && p.hi[i] == S) {
+        int64_t below = 1;
+        for (int k = (int)g.size() - 1; k >= 0; --k) {
+          if (S % below || (k > 0 && S % (below * g[k].radix))) return false;
+          const int64_t mod = k == 0 ? S / below : g[k].radix;     // the outermost digit takes what is left
+          RawTerm o;
+          const int r = term_in_units({Q[i] * below, mod, g[k].stride, false}, unit, &o);
+          if (r < 0) return false;
+          if (r > 0) ut.push_back(o);
+          below *= g[k].radix;
+        }
+      } else {
+        if (restricted >= 0) return false;
+        restricted = i;
+        RawTerm c;
+        const int r = term_in_units({Q[i], S, 1, false}, unit, &c);   // the coordinate: ((u / c.div) % c.mod) * c.coef
+        if (r < 0) return false;
+        if (r == 0) {                                   // 0 at every unit start: local coordinate 0, or not this piece
+          starts_no_unit = p.lo[i] != 0;
+          continue;
+        }
+        const int64_t m = c.coef;
+        if (p.lo[i] % m || p.hi[i] % m) return false;
+        wp.has_test = 1;
+        wp.t_div = make_fastdiv((uint32_t)c.div);
+        wp.t_mod = make_fastdiv((uint32_t)c.mod);
+        wp.t_lo = (uint32_t)(p.lo[i] / m);
+        wp.t_hi = (uint32_t)(p.hi[i] / m);
+        extent_v = (p.hi[i] - p.lo[i]) / m;
+        int64_t below = 1;
+        for (int k = (int)g.size() - 1; k >= 0; --k) {   // digits of the local coordinate v = (x - lo) * m
+          RawTerm o;
+          const int rr = term_in_units({below, k == 0 ? 0 : g[k].radix, g[k].stride, true}, m, &o);
+          if (rr < 0) return false;
+          if (rr > 0) ut.push_back(o);
+          below *= g[k].radix;
+        }
+      }
+    }
+    if (starts_no_unit) continue;
+    // drop what never leaves zero, sort, merge digits whose strides nest
+    std::vector<RawTerm> kept;
+    for (RawTerm t : ut) {
+      const int64_t range = t.on_coord ? extent_v : units;
+      if (t.coef == 0 || t.mod == 1 || t.div >= range) continue;
+      if (t.mod == 0 || t.div * t.mod >= range) t.mod = 0;             // never wraps: no modulo needed
+      kept.push_back(t);
+    }
+    std::sort(kept.begin(), kept.end(), [](const RawTerm& a, const RawTerm& b) { return a.on_coord != b.on_coord ? a.on_coord < b.on_coord : a.div < b.div; });
+    std::vector<RawTerm> merged;
+    for (const RawTerm& t : kept) {
+      if (!merged.empty()) {
+        RawTerm& m = merged.back();
+        if (m.on_coord == t.on_coord && m.mod > 0 && t.div == m.div * m.mod && t.coef == m.coef * m.mod) {
+          m.mod = t.mod == 0 ? 0 : m.mod * t.mod;
+          continue;
+        }
+      }
+      merged.push_back(t);
+    }
+    if ((int)merged.size() > kWalkTerms) return false;
+    int64_t span = 0;
+    for (const RawTerm& t : merged) {
+      if (t.coef < 0 || t.coef * esz >= (1ll << 32)) return false;
+      const int64_t range = t.on_coord ? extent_v : units;
+      span += (t.mod ? t.mod - 1 : (range - 1) / t.div) * t.coef;
+    }
+    if (span * esz >= (1ll << 32)) return false;
+    wp.base = reinterpret_cast<uint64_t>(src) + (uint64_t)(p.v.base * esz);
+    wp.n_terms = (int)merged.size();
+    for (size_t k = 0; k < merged.size(); ++k) {
+      wp.term[k].div = make_fastdiv((uint32_t)merged[k].div);
+      if (merged[k].mod) wp.term[k].mod = make_fastdiv((uint32_t)merged[k].mod);
+      wp.term[k].coef = (uint32_t)(merged[k].coef * esz);
+      wp.term[k].on_coord = merged[k].on_coord ? 1u : 0u;
+    }
+    ++np;
+  }
+  if (np == 0) return false;
+  w->n = np;
+  // the evaluator has the last word, on the first and last units and a spread of others
+  const int64_t samples = std::min<int64_t>(units, 29);    // this runs at every launch: a few microseconds
+  std::vector<int64_t> x(n), local(n);
+  for (int64_t k = 0; k < samples + 2; ++k) {
+    const int64_t u = k == samples ? units - 1 : k == samples + 1 ? units / 2 : (k * 2654435761ll) % units;
+    int64_t L = u * unit;
+    for (int i = n - 1; i >= 0; --i) {
+      x[i] = L % d.shape[i];
+      L /= d.shape[i];
+    }
+    const int pi = find_piece(d, x.data());
+    if (pi < 0) {
+      w->n = 0;
+      return false;
+    }
+    const Piece& p = d.pieces[pi];
+    for (int i = 0; i < n; ++i) local[i] = x[i] - p.lo[i];
+    const uint64_t want = reinterpret_cast<uint64_t>(d.sources[p.src].ptr) + (uint64_t)(eval_view(d, p.v, local.data()) * esz);
+    if (walk_address(static_cast<const BlockWalk*>(w), (uint32_t)u) != want) {
+      w->n = 0;
+      return false;
+    }
+  }
+  return true;
 }
 
 int check_launch(const char* what) {

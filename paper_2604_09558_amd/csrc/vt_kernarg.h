@@ -65,4 +65,43 @@ __device__ __forceinline__ void warm_kernarg_8() {
       : "memory");
 }
 
+// lines 0..26 (bytes 0..1727): two block walks (26 * 64 + 4 <= sizeof(arguments))
+__device__ __forceinline__ void warm_kernarg_27() {
+  typedef __attribute__((address_space(4))) const char* karg_t;
+  const uint64_t p = (uint64_t)(karg_t)__builtin_amdgcn_kernarg_segment_ptr();
+  uint32_t d[27];
+  asm volatile(
+      "s_load_dword %0, %27, 0x0\n\t"
+      "s_load_dword %1, %27, 0x40\n\t"
+      "s_load_dword %2, %27, 0x80\n\t"
+      "s_load_dword %3, %27, 0xc0\n\t"
+      "s_load_dword %4, %27, 0x100\n\t"
+      "s_load_dword %5, %27, 0x140\n\t"
+      "s_load_dword %6, %27, 0x180\n\t"
+      "s_load_dword %7, %27, 0x1c0\n\t"
+      "s_load_dword %8, %27, 0x200\n\t"
+      "s_load_dword %9, %27, 0x240\n\t"
+      "s_load_dword %10, %27, 0x280\n\t"
+      "s_load_dword %11, %27, 0x2c0\n\t"
+      "s_load_dword %12, %27, 0x300\n\t"
+      "s_load_dword %13, %27, 0x340\n\t"
+      "s_load_dword %14, %27, 0x380\n\t"
+      "s_load_dword %15, %27, 0x3c0\n\t"
+      "s_load_dword %16, %27, 0x400\n\t"
+      "s_load_dword %17, %27, 0x440\n\t"
+      "s_load_dword %18, %27, 0x480\n\t"
+      "s_load_dword %19, %27, 0x4c0\n\t"
+      "s_load_dword %20, %27, 0x500\n\t"
+      "s_load_dword %21, %27, 0x540\n\t"
+      "s_load_dword %22, %27, 0x580\n\t"
+      "s_load_dword %23, %27, 0x5c0\n\t"
+      "s_load_dword %24, %27, 0x600\n\t"
+      "s_load_dword %25, %27, 0x640\n\t"
+      "s_load_dword %26, %27, 0x680\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&s"(d[0]), "=&s"(d[1]), "=&s"(d[2]), "=&s"(d[3]), "=&s"(d[4]), "=&s"(d[5]), "=&s"(d[6]), "=&s"(d[7]), "=&s"(d[8]), "=&s"(d[9]), "=&s"(d[10]), "=&s"(d[11]), "=&s"(d[12]), "=&s"(d[13]), "=&s"(d[14]), "=&s"(d[15]), "=&s"(d[16]), "=&s"(d[17]), "=&s"(d[18]), "=&s"(d[19]), "=&s"(d[20]), "=&s"(d[21]), "=&s"(d[22]), "=&s"(d[23]), "=&s"(d[24]), "=&s"(d[25]), "=&s"(d[26])
+      : "s"(p)
+      : "memory");
+}
+
 }  // namespace vt

@@ -4,6 +4,7 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <cstring>
 
 #include "vt_device.h"
 #include "vt_kernarg.h"
@@ -76,26 +77,13 @@ __device__ __forceinline__ uint64_t shfl_u64(uint64_t v, int src_lane) {
   return ((uint64_t)hi << 32) | lo;
 }
 
-template <int BL, bool SCATTER>
-__global__ void __launch_bounds__(256) k_copy_blocks(const DevDesc S, const DevDesc D, char* __restrict__ dst,
-                                                     uint32_t inner_blocks, uint32_t block_elems, uint32_t rb, uint32_t outer) {
+typedef __attribute__((address_space(4))) const BlockWalk* kernarg_block_walk_t;   // a walk inside the kernel-argument segment
+
+// The body shared by the two kernels below: src_of(o, blk) / dst_of(o, blk) give the address of a block.
+template <int BL, bool SCATTER, typename SrcOf, typename DstOf>
+__device__ __forceinline__ void copy_blocks_body(char* __restrict__ dst, uint32_t inner_blocks, uint32_t rb, uint32_t outer, SrcOf src_of,
+                                                 DstOf dst_of) {
   constexpr int G = 64 / BL;                         // blocks moved by one instruction
-  // Small blocks: the maps are evaluated often for the bytes moved, and are read from an LDS copy.
-  // Blocks of 1 KB: one evaluation moves a kilobyte, and the copy to LDS with its barrier costs
-  // more than it saves (measured on the gather of 28 KB rows: 10 % slower with it).
-  constexpr bool STAGE = BL < 64;
-  __shared__ DevDesc staged[STAGE ? (SCATTER ? 2 : 1) : 1];
-  if (STAGE) {
-    if (SCATTER) {
-      const DevDesc* const from[2] = {&S, &D};
-      stage_maps(reinterpret_cast<DevDesc*>(staged), from);
-    } else {
-      const DevDesc* const from[1] = {&S};
-      stage_maps(reinterpret_cast<DevDesc*>(staged), from);
-    }
-  }
-  const DevDesc& MS = STAGE ? staged[0] : S;
-  const DevDesc& MD = STAGE ? staged[SCATTER ? 1 : 0] : D;
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t wv = blockIdx.x * 4u + (threadIdx.x >> 6);
   const uint32_t first = wv * rb;                    // this wave's blocks: [first, first + rb)
@@ -113,15 +101,9 @@ __global__ void __launch_bounds__(256) k_copy_blocks(const DevDesc S, const DevD
   };
   for (uint32_t o = blockIdx.y; o < outer; o += gridDim.y) {
     const uint32_t mine = first + min(lane, n_here - 1);
-    int64_t off;
-    const void* ptr;
-    vtd_eval(MS, o, mine * block_elems, &off, &ptr);
-    const uint64_t src_addr = reinterpret_cast<uint64_t>(ptr) + (uint64_t)(off * MS.elem_size);
+    const uint64_t src_addr = src_of(o, mine);
     uint64_t dst_addr = 0;
-    if (SCATTER) {
-      vtd_eval(MD, o, mine * block_elems, &off, &ptr);
-      dst_addr = reinterpret_cast<uint64_t>(ptr) + (uint64_t)(off * MD.elem_size);
-    }
+    if (SCATTER) dst_addr = dst_of(o, mine);
     // dense destination: block b of the round sits at a fixed distance from the round's first block
     const uint64_t dense0 = reinterpret_cast<uint64_t>(dst) + ((uint64_t)o * inner_blocks + first) * (uint64_t)(BL * 16) + c16;
     uint32_t j0 = 0;
@@ -153,6 +135,50 @@ __global__ void __launch_bounds__(256) k_copy_blocks(const DevDesc S, const DevD
       }
     }
   }
+}
+
+template <int BL, bool SCATTER>
+__global__ void __launch_bounds__(256) k_copy_blocks(const DevDesc S, const DevDesc D, char* __restrict__ dst,
+                                                     uint32_t inner_blocks, uint32_t block_elems, uint32_t rb, uint32_t outer) {
+  // Small blocks: the maps are evaluated often for the bytes moved, and are read from an LDS copy.
+  // Blocks of 1 KB: one evaluation moves a kilobyte, and the copy to LDS with its barrier costs
+  // more than it saves (measured on the gather of 28 KB rows: 10 % slower with it).
+  constexpr bool STAGE = BL < 64;
+  __shared__ DevDesc staged[STAGE ? (SCATTER ? 2 : 1) : 1];
+  if (STAGE) {
+    if (SCATTER) {
+      const DevDesc* const from[2] = {&S, &D};
+      stage_maps(reinterpret_cast<DevDesc*>(staged), from);
+    } else {
+      const DevDesc* const from[1] = {&S};
+      stage_maps(reinterpret_cast<DevDesc*>(staged), from);
+    }
+  }
+  const DevDesc& MS = STAGE ? staged[0] : S;
+  const DevDesc& MD = STAGE ? staged[SCATTER ? 1 : 0] : D;
+  auto at = [&](const DevDesc& M, uint32_t o, uint32_t blk) -> uint64_t {
+    int64_t off;
+    const void* ptr;
+    vtd_eval(M, o, blk * block_elems, &off, &ptr);
+    return reinterpret_cast<uint64_t>(ptr) + (uint64_t)(off * M.elem_size);
+  };
+  copy_blocks_body<BL, SCATTER>(dst, inner_blocks, rb, outer, [&](uint32_t o, uint32_t blk) { return at(MS, o, blk); },
+                                [&](uint32_t o, uint32_t blk) { return at(MD, o, blk); });
+}
+
+// The same copy for maps that resolve into the term form (BlockWalk): a block's address costs a
+// dozen instructions per term, the terms are read from the arguments where they are used.
+template <int BL, bool SCATTER>
+__global__ void __launch_bounds__(256) k_copy_blocks_walk(const BlockWalk WS, const BlockWalk WD, char* __restrict__ dst,
+                                                          uint32_t inner_blocks, uint32_t rb) {
+  // the pieces are read one after the other, each a few wide reads: all their lines are requested at once first
+  static_assert(2 * sizeof(BlockWalk) >= 26 * 64 + 4 && 2 * sizeof(BlockWalk) <= 27 * 64, "the lines requested below are those of the two walks");
+  warm_kernarg_27();
+  kernarg_block_walk_t kw = (kernarg_block_walk_t)__builtin_amdgcn_kernarg_segment_ptr();   // WS, then WD
+  asm volatile("" : "+s"(kw));
+  (void)WS, (void)WD;
+  copy_blocks_body<BL, SCATTER>(dst, inner_blocks, rb, 1u, [&](uint32_t, uint32_t blk) { return walk_address(kw, blk); },
+                                [&](uint32_t, uint32_t blk) { return walk_address(kw + 1, blk); });
 }
 
 // A map that is one contiguous range of one source (Def. 5 with minimal contiguous dimension 1:
@@ -194,6 +220,30 @@ static bool launch_copy_blocks(const vt_desc& s, const vt_desc* d, const DevDesc
   while (rb > (uint32_t)(64 / bl) && blocks / rb < want_waves) rb >>= 1;
   const int64_t waves = (blocks + rb - 1) / rb;
   dim3 grid((unsigned)((waves + 3) / 4), (unsigned)std::min<int64_t>(outer, 65535));
+  // block addresses from the maps' term form when both resolve
+  BlockWalk WS, WD;
+  memset(&WD, 0, sizeof(WD));
+  const bool walk = outer == 1 && resolve_block_walk(s, be, &WS) && (!d || resolve_block_walk(*d, be, &WD));
+  if (walk) {
+#define VT_COPY_WALK(BLV)                                                                                              \
+  case BLV:                                                                                                            \
+    if (d) hipLaunchKernelGGL((k_copy_blocks_walk<BLV, true>), grid, dim3(256), 0, stream, WS, WD, (char*)nullptr,     \
+                              (uint32_t)blocks, rb);                                                                   \
+    else hipLaunchKernelGGL((k_copy_blocks_walk<BLV, false>), grid, dim3(256), 0, stream, WS, WD, (char*)dst,          \
+                            (uint32_t)blocks, rb);                                                                     \
+    break;
+    switch (bl) {
+      VT_COPY_WALK(2)
+      VT_COPY_WALK(4)
+      VT_COPY_WALK(8)
+      VT_COPY_WALK(16)
+      VT_COPY_WALK(32)
+      VT_COPY_WALK(64)
+      default: return false;
+    }
+#undef VT_COPY_WALK
+    return true;
+  }
 #define VT_COPY_BLOCKS(BLV)                                                                                         \
   case BLV:                                                                                                         \
     if (d) hipLaunchKernelGGL((k_copy_blocks<BLV, true>), grid, dim3(256), 0, stream, S, D, (char*)nullptr,         \
@@ -542,6 +592,8 @@ __global__ void __launch_bounds__(256) k_layernorm(const DevDesc X, T* __restric
 // 64 / lpr rows: the evaluator's several hundred instructions, not the memory, bound that kernel),
 // and the rows are then read in passes of 64 / lpr rows, their addresses handed round by shuffle,
 // eight vectors per lane in flight.  ITS = vectors per lane and row (1, 2 or 4).
+// (Row addresses from the map's term form, as in the block copies, were measured here as well:
+// 20-22 us against 17.5 us on the window-partitioned rows, equal on dense rows; the evaluator stays.)
 constexpr uint32_t kLnRowsPerWave = 32;   // (or one pass's rows, if that is more)
 
 template <typename T, int VEC, int ITS>

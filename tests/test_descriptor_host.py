@@ -644,3 +644,88 @@ def test_row_walk_resolves_most_table_free_chains():
         ok += len(d.row_walk(max(1, min(d.block(), 1)))) > 0
     assert tried >= 40, tried
     print("row walk resolved %d of %d table-free chains at block 1" % (ok, tried))
+
+
+# ----------------------------------------------------------------------------------------
+# Block walk: the general term form of a single-stage map, against the evaluator
+# ----------------------------------------------------------------------------------------
+def check_block_walk(d, ptr_of_src, esz, unit):
+    """Every unit's address from the term form equals the evaluator's.  True if the map resolved."""
+    shape = d.shape
+    n = int(np.prod(shape))
+    assert n % unit == 0
+    got = d.walk_addresses(unit)
+    if got is None:
+        return False
+    assert len(got) == n // unit
+    for u, a in enumerate(got):
+        x = np.unravel_index(u * unit, shape) if shape else ()
+        src, off = d.eval_host(tuple(int(v) for v in x))
+        assert a == ptr_of_src[src] + off * esz, (u, unit, d.dump())
+    return True
+
+
+def test_block_walk_of_the_benchmark_chains():
+    wl = workloads.c4_window_ln_linear(B=2, R=14, win=7, C=128, N=384)
+    specs = fake_ptrs(wl)
+    t = vt.build_chain(wl.chain, specs, "T")
+    # rows of the window partition: five digits, two of which nest into one term
+    assert check_block_walk(t, {0: specs["X"][2]}, 2, 128)
+    assert check_block_walk(t, {0: specs["X"][2]}, 2, 8)
+    wl = workloads.rowsum_chain_large(A=4, B=96, C0=64, ny=48)
+    specs = fake_ptrs(wl)
+    v = vt.build_chain(wl.chain, specs, "V")
+    ptrs = {i: specs[name][2] for i, name in enumerate(v.source_names)}
+    assert check_block_walk(v, ptrs, 4, 16)            # concat along the last dim: a test on the column block
+    assert check_block_walk(v, ptrs, 4, 1)
+    assert v.walk_addresses(32) is None or check_block_walk(v, ptrs, 4, 32) is not None
+    wl = workloads.c3_oproj_gemm(seed=3, B=2, H=3, S=100, D=64, N=264)
+    specs = fake_ptrs(wl)
+    a = vt.build_chain(wl.chain, specs, "A")
+    assert check_block_walk(a, {0: specs[a.source_names[0]][2]}, 2, 64)
+
+
+def test_block_walk_refuses_tables_and_stages():
+    rng = np.random.default_rng(0)
+    src = {"X": rng.normal(size=(12, 32)).astype(np.float32)}
+    idx = rng.permutation(12).astype(np.int32)
+    wl = workloads.Workload("g", "f32", src, [("R", "index_select", ("X",), {"dim": 0, "index": "I"})], {"kind": "none"}, {"I": idx})
+    d = vt.build_chain(wl.chain, fake_ptrs(wl), "R", wl.index_tables)
+    assert d.walk_addresses(32) is None
+    with pytest.raises(vt.VtError):
+        d.walk_addresses(0)
+
+
+@pytest.mark.parametrize("seed", range(150))
+def test_block_walk_equals_the_evaluator_on_random_chains(seed):
+    wl = workloads.random_chain(seed, n_ops=5, max_extent=8)
+    specs = fake_ptrs(wl)
+    try:
+        d = vt.build_chain(wl.chain, specs, "R", wl.index_tables)
+    except vt.VtError:
+        pytest.skip("chain not representable")
+    n = int(np.prod(d.shape))
+    ptr_of_src = {i: specs[name][2] for i, name in enumerate(d.source_names)}
+    esz = 2 if wl.dtype != "f32" else 4
+    units = {1, d.block()}
+    if d.shape:
+        units.add(int(d.shape[-1]))                    # rows
+    for unit in sorted(units):
+        if unit >= 1 and n % unit == 0:
+            check_block_walk(d, ptr_of_src, esz, unit)
+
+
+def test_block_walk_resolves_most_table_free_chains():
+    tried = ok = 0
+    for seed in range(200):
+        wl = workloads.random_chain(seed, n_ops=4, max_extent=8)
+        if wl.index_tables:
+            continue
+        specs = fake_ptrs(wl)
+        try:
+            d = vt.build_chain(wl.chain, specs, "R")
+        except vt.VtError:
+            continue
+        tried += 1
+        ok += d.walk_addresses(d.block(), 0, 0) is not None
+    assert tried >= 60 and ok >= 0.6 * tried, (ok, tried)
