@@ -585,8 +585,8 @@ __global__ void __launch_bounds__(256) k_layernorm(const DevDesc X, T* __restric
   (void)outer;
 }
 
-// The same LayerNorm, same lane-to-element assignment and same order of operations (so the same
-// bits), for maps that keep every row one contiguous range of a source: the map is applied once
+// The same LayerNorm, same lane-to-element assignment (the sums over a row's lanes may be taken in
+// another order), for maps that keep every row one contiguous range of a source: the map is applied once
 // per ROW instead of once per vector.  A wave takes 32 consecutive rows; lane l evaluates the
 // address of row l (one evaluation serves 32 rows where the kernel above needs one per group of
 // 64 / lpr rows: the evaluator's several hundred instructions, not the memory, bound that kernel),
@@ -595,15 +595,19 @@ __global__ void __launch_bounds__(256) k_layernorm(const DevDesc X, T* __restric
 // (Row addresses from the map's term form, as in the block copies, were measured here as well:
 // 20-22 us against 17.5 us on the window-partitioned rows, equal on dense rows; the evaluator stays.)
 constexpr uint32_t kLnRowsPerWave = 32;   // (or one pass's rows, if that is more)
+VT_PROF_DECLARE(layernorm)
 
 template <typename T, int VEC, int ITS>
 __global__ void __launch_bounds__(256) k_layernorm_rows(const DevDesc X, T* __restrict__ out, uint32_t rows, uint32_t C,
                                                         uint32_t lpr_log2, float eps, uint32_t rows_inner) {
+  VT_PROF_BEGIN();
+  VT_PROF(0);
   __shared__ DevDesc map[1];
   {
     const DevDesc* const from[1] = {&X};
     stage_maps(map, from);
   }
+  VT_PROF(1);
   constexpr int U = 8 / ITS;                            // passes in flight
   const uint32_t lpr = 1u << lpr_log2;
   const uint32_t rpw = 64u >> lpr_log2;                 // rows per pass
@@ -622,7 +626,25 @@ __global__ void __launch_bounds__(256) k_layernorm_rows(const DevDesc X, T* __re
     vtd_eval(map[0], o, ri * C, &off, &ptr);
     row_addr = reinterpret_cast<uint64_t>(ptr) + (uint64_t)(off * (int64_t)sizeof(T));
   }
+  VT_PROF(2);
   const uint32_t passes = rw / rpw;
+  // Sum over the lpr lanes of a row, for the U passes at once.  Rows of 16 or 8 lanes (the usual
+  // ones: 128 or 64 elements of 16 bits) use the VALU's lane permutes; a shuffle through LDS costs
+  // a round trip per step, and the compiler waits for each one before it issues the next.
+  auto reduce_rows = [&](float (&x)[U]) {
+    if (lpr == 16) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) x[u] = group_sum<16>(x[u]);
+    } else if (lpr == 8) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) x[u] = group_sum<8>(x[u]);
+    } else {
+      for (uint32_t s = lpr >> 1; s >= 1; s >>= 1) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] += __shfl_xor(x[u], (int)s, 64);
+      }
+    }
+  };
   for (uint32_t p0 = 0; p0 < passes; p0 += U) {
     Vec<T, VEC> raw[U][ITS];
     bool live[U];
@@ -640,9 +662,7 @@ __global__ void __launch_bounds__(256) k_layernorm_rows(const DevDesc X, T* __re
         raw[u][it] = ld_global<Vec<T, VEC>, true>(a + (uint64_t)j * (VEC * sizeof(T)));
       }
     }
-    // The U passes are independent: every step below is done for all of them before the next
-    // one, so that their shuffles are in flight together (per pass the operations and their
-    // order are those of k_layernorm).
+    // The U passes are independent: every step below is done for all of them before the next one.
     float v[U][ITS][VEC];
     float sum[U], sq[U];
 #pragma unroll
@@ -658,10 +678,8 @@ __global__ void __launch_bounds__(256) k_layernorm_rows(const DevDesc X, T* __re
         }
       }
     }
-    for (uint32_t s = lpr >> 1; s >= 1; s >>= 1) {
-#pragma unroll
-      for (int u = 0; u < U; ++u) sum[u] += __shfl_xor(sum[u], (int)s, 64);
-    }
+    VT_PROF_ONCE(3);
+    reduce_rows(sum);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const float mean = sum[u] / (float)C;
@@ -678,10 +696,7 @@ __global__ void __launch_bounds__(256) k_layernorm_rows(const DevDesc X, T* __re
         }
       }
     }
-    for (uint32_t s = lpr >> 1; s >= 1; s >>= 1) {
-#pragma unroll
-      for (int u = 0; u < U; ++u) sq[u] += __shfl_xor(sq[u], (int)s, 64);
-    }
+    reduce_rows(sq);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const float mean = sum[u];
@@ -694,11 +709,20 @@ __global__ void __launch_bounds__(256) k_layernorm_rows(const DevDesc X, T* __re
           Vec<T, VEC> o;
 #pragma unroll
           for (int e = 0; e < VEC; ++e) o.v[e] = from_float<T>((v[u][it][e] - mean) * rstd);
+          // (an ordinary store: a streaming one ends the kernel 2 us earlier, since no dirty lines
+          // have to drain, but the consumer that follows then reads the rows from memory instead
+          // of the cache: LayerNorm + GEMM measured 71.0 against 70.1 us)
           *reinterpret_cast<Vec<T, VEC>*>(out + (size_t)row * C + (size_t)j * VEC) = o;
         }
       }
     }
+    VT_PROF_ONCE(4);
   }
+#ifdef VT_PROFILE
+  __builtin_amdgcn_s_waitcnt(0);
+  VT_PROF(5);
+  VT_PROF_FLUSH(layernorm, blockIdx.x);
+#endif
 }
 
 template <typename T>

@@ -52,21 +52,6 @@ struct Mma16<f16_t> {
   }
 };
 
-// Sum over the LPR (8 or 16) consecutive lanes that share a row, on the VALU's data-parallel
-// primitives (mirror within 16 / 8 lanes, then the two quad permutes): every lane gets the total.
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
-}
-template <int LPR>
-__device__ __forceinline__ float group_sum(float v) {
-  if (LPR == 16) v += dpp_move<0x140>(v);   // row_mirror: lane i <-> 15 - i
-  v += dpp_move<0x141>(v);                  // row_half_mirror: i <-> 7 - i
-  v += dpp_move<0xB1>(v);                   // quad_perm [1,0,3,2]
-  v += dpp_move<0x4E>(v);                   // quad_perm [2,3,0,1]
-  return v;
-}
-
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int LBM = 64;           // rows per block

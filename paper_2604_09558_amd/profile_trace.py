@@ -8,7 +8,7 @@ the compute dies compare.  The marks cost a little time: read the ordinary libra
 from rocprofv3, and the shape of the timeline from here.
 
     python -m paper_2604_09558_amd.profile_trace attn [--n-splits N] [--reps R]
-    python -m paper_2604_09558_amd.profile_trace gemm | gemm_store | ln_gemm | add_rowsum
+    python -m paper_2604_09558_amd.profile_trace gemm | gemm_store | ln_gemm | add_rowsum | layernorm
     python -m paper_2604_09558_amd.profile_trace gemm_values     (k_gemm's duration and clock against the operand values)
 """
 from __future__ import annotations
@@ -37,6 +37,7 @@ MARKS = {
     "gemm": ["start", "first tiles in LDS", "K loop done", "tile stored"],
     "gemm_store": ["start", "first tile multiplied", "tile loop done", "partial sums stored", "ticket taken", "mapped store done"],
     "add_rowsum": ["start", "maps in LDS", "block addresses known", "first 512 columns added", "row written"],
+    "layernorm": ["start", "map in LDS", "row addresses known", "first rows loaded", "first rows stored", "all stores complete"],
     "ln_gemm": ["start", "first two blocks requested", "W in registers", "first block multiplied", "last block multiplied",
                 "last stores issued", "all memory operations complete"],
 }
@@ -71,7 +72,7 @@ def report(kernel, marks):
         print("  merging workgroups, median step: " + "; ".join("%s %.2f" % (n, np.median(us[m, b] - us[m, a])) for n, a, b in steps))
         print("  last mark of the launch %.2f us = last tile loop done %.2f + %.2f" % (
             np.nanmax(us[:, 5]), np.nanmax(us[:, 2]), np.nanmax(us[:, 5]) - np.nanmax(us[:, 2])))
-    k_done = 4 if kernel == "add_rowsum" else 2
+    k_done = {"add_rowsum": 4, "layernorm": 5}.get(kernel, 2)
     print("  '%s' by compute die (median / max): " % MARKS[kernel][k_done] +
           "  ".join("%d: %.1f/%.1f" % (x, np.nanmedian(us[xcc == x, k_done]), np.nanmax(us[xcc == x, k_done]))
                     for x in sorted(set(xcc.tolist()))))
@@ -267,6 +268,35 @@ def trace_add_rowsum(a):
         report("add_rowsum", (t[live], rate))
 
 
+def trace_layernorm(a):
+    """The LayerNorm consumer on config 4's window-partitioned rows (first wave of each workgroup of 128 rows)."""
+    import torch
+    import workloads
+    import paper_2604_09558_amd as vt
+    from paper_2604_09558_amd import torch_io as tio
+    lib = vt.lib()
+    dws = [tio.DeviceWorkload(workloads.c4_window_ln_linear(seed=s)) for s in range(3)]
+    ds = [d.build("T") for d in dws]
+    outs = [d.empty(ds[0].shape) for d in dws]
+    n_wg = 1024
+    for i in range(3):
+        vt.vt_elementwise(vt.EW_LAYERNORM, ds[i], None, 1e-5, outs[i])
+    torch.cuda.synchronize()
+    read_marks(lib, "layernorm", n_wg)
+    for rep in range(a.reps):
+        for i in (2, 0):
+            vt.vt_elementwise(vt.EW_LAYERNORM, ds[i], None, 1e-5, outs[i])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        vt.vt_elementwise(vt.EW_LAYERNORM, ds[1], None, 1e-5, outs[1])
+        e1.record()
+        torch.cuda.synchronize()
+        t, rate = read_marks(lib, "layernorm", n_wg)
+        live = t[:, 0] > 0
+        print("layernorm, %d workgroups, launch %d: %.1f us between events" % (int(live.sum()), rep, e0.elapsed_time(e1) * 1e3))
+        report("layernorm", (t[live], rate))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("kernel", choices=sorted(MARKS) + ["gemm_values"])
@@ -274,7 +304,7 @@ def main():
     ap.add_argument("--reps", type=int, default=3)
     a = ap.parse_args()
     {"attn": trace_attn, "gemm": trace_gemm, "gemm_store": trace_gemm_store, "gemm_values": trace_gemm_values,
-     "ln_gemm": trace_ln_gemm, "add_rowsum": trace_add_rowsum}[a.kernel](a)
+     "ln_gemm": trace_ln_gemm, "add_rowsum": trace_add_rowsum, "layernorm": trace_layernorm}[a.kernel](a)
 
 
 if __name__ == "__main__":
