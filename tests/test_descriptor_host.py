@@ -729,3 +729,25 @@ def test_block_walk_resolves_most_table_free_chains():
         tried += 1
         ok += d.walk_addresses(d.block(), 0, 0) is not None
     assert tried >= 60 and ok >= 0.6 * tried, (ok, tried)
+
+
+def test_block_address_probes_check_their_arguments():
+    wl = workloads.c1_tiny_chain()
+    d = vt.build_chain(wl.chain, fake_ptrs(wl), "V")
+    n = int(np.prod(d.shape))
+    assert len(d.walk_addresses(1, n - 3, 3)) == 3
+    with pytest.raises(vt.VtError) as e:
+        d.walk_addresses(1, n - 3, 4)                   # one unit past the end
+    assert e.value.code == vt.ERR_RANGE
+    with pytest.raises(vt.VtError):
+        d.walk_addresses(1, -1, 1)
+    assert d.walk_addresses(5) is None                  # 5 does not divide 8 * 21
+    # sources without pointers: nothing to resolve against
+    bare = vt.build_chain(wl.chain, specs_of(wl), "V")
+    assert bare.walk_addresses(1, 0, 0) is None and bare.row_walk(1) == []
+    with pytest.raises(vt.VtError):
+        d.row_walk(0)
+    three_d = vt.build_chain([], {"S": ((2, 3, 4), "f32", FAKE_BASE)}, "S")
+    with pytest.raises(vt.VtError) as e:
+        three_d.row_walk(4)
+    assert e.value.code == vt.ERR_SHAPE
