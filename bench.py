@@ -218,7 +218,7 @@ CHAIN_PLAN = {
     "c3": (3, 30, False),
     "c4": (6, 240, True),
     "c5": (1, 6, False),
-    "rowsum_large": (2, 60, False),
+    "rowsum_large": (2, 60, True),
     "qkv_store": (6, 240, True),
     "decode_segment": (4, 120, True),
     "paged": (4, 200, True),
@@ -269,7 +269,7 @@ CHAIN_PLAN = {
     "c3": (3, 30, False),
     "c4": (6, 240, True),
     "c5": (1, 6, False),
-    "rowsum_large": (2, 60, False),
+    "rowsum_large": (2, 60, True),
     "qkv_store": (6, 240, True),
     "decode_segment": (4, 120, True),
     "paged": (4, 200, True),
