@@ -60,6 +60,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--n-splits", type=int, default=0, help="context splits of the attention kernel (0 = library's choice)")
     ap.add_argument("--context", type=int, default=4096, help="context length (the benchmark's is 4096; others are for tuning)")
+    ap.add_argument("--copy-rates", action="store_true",
+                    help="only time the copy kernels of the materialized paths on 128 MiB (and torch's device copy) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 128 MiB -> 128 MiB copy kernel 20 times (reference point for HBM byte counters)")
     ap.add_argument("--chains", default=DEFAULT_CHAINS,
@@ -432,6 +434,34 @@ def main():
             vt.vt_materialize(descs[k % 4], dst)
         torch.cuda.synchronize()
         print(json.dumps({"calibration": "vt_materialize copies 134217728 B -> 134217728 B", "launches": 20}))
+        return
+    if a.copy_rates:
+        # the copy kernels of the materialized paths on 128 MiB, beside the runtime's device copy
+        n = 128 << 20
+        srcs = [torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda:0") for _ in range(4)]
+        dsts = [torch.empty(n, dtype=torch.uint8, device="cuda:0") for _ in range(4)]
+
+        def rate(fn, reps=40):
+            for i in range(8):
+                fn(i)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(reps):
+                fn(i)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) / reps * 1e3
+            return {"us": round(us, 1), "TB/s": round(2 * n / us / 1e6, 2)}
+
+        out = {}
+        flat = [vt.build_chain([], {"S": ((n // 4,), "f32", t.data_ptr())}, "S") for t in srcs]
+        out["contiguous map (k_copy_flat)"] = rate(lambda i: vt.vt_materialize(flat[i % 4], dsts[i % 4]))
+        out["torch copy_"] = rate(lambda i: dsts[i % 4].copy_(srcs[i % 4]))
+        for name, shape in (("permute in 256-byte blocks", (4096, 128, 64)), ("permute in 1 KB blocks", (1024, 128, 256))):
+            ds = [vt.build_chain([("P", "permute", ("S",), {"perm": (1, 0, 2)})], {"S": (shape, "f32", t.data_ptr())}, "P") for t in srcs]
+            out[name] = rate(lambda i: vt.vt_materialize(ds[i % 4], dsts[i % 4]))
+        print(json.dumps({"copy_rates_128MiB": out}))
         return
     chains = [] if a.chains in ("", "none") else a.chains.split(",")
     for c in chains:
