@@ -225,7 +225,8 @@ bool resolve_row_walk(const vt_desc& d, int64_t be, RowWalk* w);
 // each dim is one term, digits whose strides nest collapse into one, digits below the unit vanish.
 // A piece that does not span a dim completely (Concat) is recognised by a test on that dim's
 // coordinate, lo <= x < hi with x = (u / t_div) % t_mod (one such dim per piece), and the digits
-// of that dim are terms in x - lo instead of u.  A dozen instructions per term, against several
+// of that dim are terms in x - lo instead of u (a piece that is a range of the outermost dim is a
+// range of the units, and all its digits are terms in the unit's index within that range).  A dozen instructions per term, against several
 // hundred for the evaluator's walk over the map.
 constexpr int kWalkPieces = 4;
 constexpr int kWalkTerms = 5;

@@ -374,6 +374,7 @@ bool resolve_block_walk(const vt_desc& d, int64_t unit, BlockWalk* w) {
     bool empty = false;
     for (int i = 0; i < n; ++i) empty = empty || p.hi[i] <= p.lo[i];
     if (empty) continue;
+    std::vector<RawTerm> raw;                           // terms of L (or of the index within the piece's range), in elements
     std::vector<RawTerm> ut;                            // terms in units
     int restricted = -1;
     bool starts_no_unit = false;
@@ -384,20 +385,35 @@ bool resolve_block_walk(const vt_desc& d, int64_t unit, BlockWalk* w) {
     for (WalkTerm& t : wp.term) t.div = make_fastdiv(1);
     wp.t_div = make_fastdiv(1);
     wp.t_hi = 0xffffffffu;
+    // A piece that is a range of the OUTERMOST dim only (Concat along dim 0) is a tensor of its
+    // own: a range [lo, hi) of the units, and every digit a function of the unit's index in it.
+    bool own_range = p.lo[0] != 0 || p.hi[0] != d.shape[0];
+    for (int i = 1; i < n; ++i) own_range = own_range && p.lo[i] == 0 && p.hi[i] == d.shape[i];
+    if (own_range) {
+      if ((p.lo[0] * Q[0]) % unit || (p.hi[0] * Q[0]) % unit) return false;
+      wp.has_test = 1;                                  // t_div 1, no modulo: the coordinate is u itself
+      wp.t_lo = (uint32_t)(p.lo[0] * Q[0] / unit);
+      wp.t_hi = (uint32_t)(p.hi[0] * Q[0] / unit);
+      extent_v = (p.hi[0] - p.lo[0]) * Q[0] / unit;
+      restricted = 0;
+    }
     for (int i = 0; i < n && !starts_no_unit; ++i) {
       const std::vector<Digit>& g = p.v.groups[i];
       const int64_t S = d.shape[i];
       for (const Digit& dg : g)
         if (dg.table >= 0) return false;
-      if (p.lo[i] == 0 && p.hi[i] == S) {
+      if (own_range && i == 0) {
+        int64_t below = 1;
+        for (int k = (int)g.size() - 1; k >= 0; --k) {   // digits of the index within the range, divided by Q[0]
+          raw.push_back({Q[0] * below, k == 0 ? 0 : g[k].radix, g[k].stride, true});
+          below *= g[k].radix;
+        }
+      } else if (own_range || (p.lo[i] == 0 && p.hi[i] == S)) {
         int64_t below = 1;
         for (int k = (int)g.size() - 1; k >= 0; --k) {
           if (S % below || (k > 0 && S % (below * g[k].radix))) return false;
           const int64_t mod = k == 0 ? S / below : g[k].radix;     // the outermost digit takes what is left
-          RawTerm o;
-          const int r = term_in_units({Q[i] * below, mod, g[k].stride, false}, unit, &o);
-          if (r < 0) return false;
-          if (r > 0) ut.push_back(o);
+          raw.push_back({Q[i] * below, mod, g[k].stride, own_range});
           below *= g[k].radix;
         }
       } else {
@@ -429,6 +445,29 @@ bool resolve_block_walk(const vt_desc& d, int64_t unit, BlockWalk* w) {
       }
     }
     if (starts_no_unit) continue;
+    {
+      // digits whose strides nest are one digit: merged in elements first, so that a unit may cut
+      // through them (rows of 40 elements in units of 64, when the rows follow each other in the source)
+      std::sort(raw.begin(), raw.end(), [](const RawTerm& a, const RawTerm& b) { return a.div < b.div; });
+      std::vector<RawTerm> nested;
+      for (const RawTerm& t : raw) {
+        if (t.coef == 0 || t.mod == 1) continue;
+        if (!nested.empty()) {
+          RawTerm& m = nested.back();
+          if (m.mod > 0 && t.div == m.div * m.mod && t.coef == m.coef * m.mod) {
+            m.mod = t.mod == 0 ? 0 : m.mod * t.mod;
+            continue;
+          }
+        }
+        nested.push_back(t);
+      }
+      for (const RawTerm& t : nested) {
+        RawTerm o;
+        const int r = term_in_units(t, unit, &o);
+        if (r < 0) return false;
+        if (r > 0) ut.push_back(o);
+      }
+    }
     // drop what never leaves zero, sort, merge digits whose strides nest
     std::vector<RawTerm> kept;
     for (RawTerm t : ut) {

@@ -238,6 +238,18 @@ BLOCK_CASES = [
     ("window", {"X": (2, 14, 14, 64)}, [("a", "reshape", ("X",), {"shape": (2, 2, 7, 2, 7, 64)}), ("b", "permute", ("a",), {"perm": (0, 1, 3, 2, 4, 5)}),
                                         ("R", "reshape", ("b",), {"shape": (8, 49, 64)})]),
     ("tiny", {"X": (2, 3, 16)}, [("R", "permute", ("X",), {"perm": (1, 0, 2)})]),
+    # pieces that do not span a middle dim, behind a permute: the term form tests that dim's
+    # coordinate and takes its digits from the local coordinate
+    ("concat_mid_permuted", {"X": (3, 20, 5, 32), "Y": (3, 13, 5, 32)},
+     [("c", "concat", ("X", "Y"), {"dim": 1}), ("R", "permute", ("c",), {"perm": (2, 0, 1, 3)})]),
+    ("three_pieces", {"X": (41, 32), "Y": (41, 96), "W": (41, 64)},
+     [("c", "concat", ("X", "Y"), {"dim": 1}), ("R", "concat", ("c", "W"), {"dim": 1})]),
+    ("sliced_heads_concat", {"X": (2, 4, 60, 64), "Y": (2, 4, 7, 64)},
+     [("s", "slice", ("X",), {"dim": 2, "start": 3, "stop": 51, "step": 1}), ("c", "concat", ("s", "Y"), {"dim": 2}),
+      ("p", "permute", ("c",), {"perm": (0, 2, 1, 3)}), ("R", "reshape", ("p",), {"shape": (110, 256)})]),
+    ("split_reshaped", {"X": (6, 8, 96)},
+     [("s", "split", ("X",), {"dim": 2, "sizes": (32, 64), "output": 1}), ("p", "permute", ("s",), {"perm": (1, 0, 2)}),
+      ("R", "reshape", ("p",), {"shape": (8, 384)})]),
 ]
 
 
@@ -253,6 +265,12 @@ def test_materialize_block_paths_bit_exact_with_canaries(gpu, name, shapes, chai
     dw = tio.DeviceWorkload(wl)
     d = dw.build("R")
     assert d.block(512) * dense.dtype.itemsize >= 32, "case meant for the block path"
+    # which of the two sources of block addresses the launch uses: the term form for every case
+    # without an index table, the evaluator for the one with
+    be = d.block(1024 // dense.dtype.itemsize)
+    while dense.size % be:
+        be //= 2
+    assert (d.walk_addresses(be, 0, 0) is not None) == (name != "rows_2048"), name
     out, check = guarded(torch, tio, dense.shape, dtype)
     vt.vt_materialize(d, out)
     torch.cuda.synchronize()
