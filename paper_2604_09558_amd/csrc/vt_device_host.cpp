@@ -389,8 +389,8 @@ bool resolve_block_walk(const vt_desc& d, int64_t unit, BlockWalk* w) {
     // own: a range [lo, hi) of the units, and every digit a function of the unit's index in it.
     bool own_range = p.lo[0] != 0 || p.hi[0] != d.shape[0];
     for (int i = 1; i < n; ++i) own_range = own_range && p.lo[i] == 0 && p.hi[i] == d.shape[i];
+    if ((p.lo[0] * Q[0]) % unit || (p.hi[0] * Q[0]) % unit) own_range = false;   // a unit across the range's end: the general form
     if (own_range) {
-      if ((p.lo[0] * Q[0]) % unit || (p.hi[0] * Q[0]) % unit) return false;
       wp.has_test = 1;                                  // t_div 1, no modulo: the coordinate is u itself
       wp.t_lo = (uint32_t)(p.lo[0] * Q[0] / unit);
       wp.t_hi = (uint32_t)(p.hi[0] * Q[0] / unit);
