@@ -292,6 +292,110 @@ static int launch_scatter(const vt_desc& s, const vt_desc& d, hipStream_t stream
   return check_launch("vt_scatter");
 }
 
+// ------------------------------------------------------------------------------------------
+// Transposing copy.  A map whose source runs along another virtual dim than the innermost one
+// (a Transpose of the last dims: contiguous runs of one element, the case block-wise I/O cannot
+// help) is copied in 64 x 64 tiles through LDS: a tile is read along the source's contiguous
+// direction and written along the destination's, both coalesced.  The two directions and the
+// remaining ones come from the map's term form (one piece, no test, the terms being exactly the
+// digits of the virtual index): term 0 is the destination's innermost digit, `s` the digit whose
+// coefficient is one element.
+// ------------------------------------------------------------------------------------------
+constexpr int kTrTile = 64;
+struct TransposeParams {
+  uint64_t src;             // address of virtual element 0
+  char* dst;
+  uint32_t md, ms;          // extents of the destination-contiguous and the source-contiguous digit
+  uint32_t coef_d;          // bytes between consecutive values of the destination-contiguous digit in the source
+  uint32_t div_s;           // virtual elements between consecutive values of the source-contiguous digit
+  int32_t n_other;
+  uint32_t o_mod[kWalkTerms], o_coef[kWalkTerms], o_div[kWalkTerms];   // the other digits: extent, source bytes, virtual elements
+  uint32_t batch;           // product of the other digits' extents
+};
+
+template <typename T>
+__global__ void __launch_bounds__(256) k_copy_transpose(const TransposeParams P) {
+  __shared__ T tile[kTrTile][kTrTile + 1];
+  const uint32_t lane = threadIdx.x & 63u, quarter = threadIdx.x >> 6;
+  const uint32_t d0 = blockIdx.x * kTrTile, s0 = blockIdx.y * kTrTile;
+  for (uint32_t bz = blockIdx.z; bz < P.batch; bz += gridDim.z) {
+    uint64_t rest_src = 0, rest_u = 0;
+    uint32_t b = bz;
+    for (int k = 0; k < P.n_other; ++k) {
+      const uint32_t q = b / P.o_mod[k], i = b - q * P.o_mod[k];
+      b = q;
+      rest_src += (uint64_t)i * P.o_coef[k];
+      rest_u += (uint64_t)i * P.o_div[k];
+    }
+    // read: lanes along the source's contiguous digit
+#pragma unroll
+    for (int r = 0; r < kTrTile / 4; ++r) {
+      const uint32_t id = r * 4 + quarter, is = lane;
+      if (d0 + id < P.md && s0 + is < P.ms)
+        tile[id][is] = ld_global<T, true>(P.src + rest_src + (uint64_t)(d0 + id) * P.coef_d + (uint64_t)(s0 + is) * sizeof(T));
+    }
+    __syncthreads();
+    // write: lanes along the destination's contiguous digit
+#pragma unroll
+    for (int r = 0; r < kTrTile / 4; ++r) {
+      const uint32_t is = r * 4 + quarter, id = lane;
+      if (d0 + id < P.md && s0 + is < P.ms)
+        reinterpret_cast<T*>(P.dst)[rest_u + (uint64_t)(s0 + is) * P.div_s + (d0 + id)] = tile[id][is];
+    }
+    __syncthreads();
+  }
+}
+
+// Launches k_copy_transpose if the map has the form described above; false otherwise.
+static bool launch_transpose(const vt_desc& d, void* dst, hipStream_t stream) {
+  const int esz = dtype_size(d.dtype);
+  BlockWalk W;
+  if (!resolve_block_walk(d, 1, &W) || W.n != 1 || W.piece[0].has_test) return false;
+  const WalkPiece& pc = W.piece[0];
+  int64_t numel = 1;
+  for (int64_t e : d.shape) numel *= e;
+  const int nt = pc.n_terms;
+  if (nt < 2) return false;
+  // the terms must be the digits of the virtual index: div 1, then each the product of those before
+  int64_t mods[kWalkTerms];
+  int64_t expect = 1;
+  for (int t = 0; t < nt; ++t) {
+    if (pc.term[t].on_coord || (int64_t)pc.term[t].div.d != expect) return false;
+    mods[t] = pc.term[t].mod.d ? (int64_t)pc.term[t].mod.d : numel / expect;
+    expect *= mods[t];
+  }
+  if (expect != numel) return false;
+  if (pc.term[0].coef == (uint32_t)esz) return false;    // the source runs along the innermost digit: not a transpose
+  int ts = -1;
+  for (int t = 1; t < nt; ++t)
+    if (pc.term[t].coef == (uint32_t)esz) ts = t;
+  if (ts < 0 || mods[0] < 16 || mods[ts] < 16) return false;   // short digits: tiles would be mostly empty
+  TransposeParams P;
+  memset(&P, 0, sizeof(P));
+  P.src = pc.base;
+  P.dst = static_cast<char*>(dst);
+  P.md = (uint32_t)mods[0];
+  P.ms = (uint32_t)mods[ts];
+  P.coef_d = pc.term[0].coef;
+  P.div_s = pc.term[ts].div.d;
+  int64_t batch = 1;
+  for (int t = 1; t < nt; ++t) {
+    if (t == ts) continue;
+    P.o_mod[P.n_other] = (uint32_t)mods[t];
+    P.o_coef[P.n_other] = pc.term[t].coef;
+    P.o_div[P.n_other] = pc.term[t].div.d;
+    ++P.n_other;
+    batch *= mods[t];
+  }
+  P.batch = (uint32_t)batch;
+  const int64_t td = (mods[0] + kTrTile - 1) / kTrTile, tsn = (mods[ts] + kTrTile - 1) / kTrTile;
+  if (tsn > 65535) return false;
+  dim3 grid((unsigned)td, (unsigned)tsn, (unsigned)std::min<int64_t>(batch, 65535));
+  if (esz == 4) hipLaunchKernelGGL(k_copy_transpose<uint32_t>, grid, dim3(256), 0, stream, P);
+  else hipLaunchKernelGGL(k_copy_transpose<uint16_t>, grid, dim3(256), 0, stream, P);
+  return true;
+}
+
 static int launch_materialize(const vt_desc& d, void* dst, hipStream_t stream) {
   DevDesc D;
   int64_t outer, inner;
@@ -316,6 +420,7 @@ static int launch_materialize(const vt_desc& d, void* dst, hipStream_t stream) {
     }
   }
   if (launch_copy_blocks(d, nullptr, D, D, dst, outer, inner, stream)) return check_launch("vt_materialize");
+  if (outer == 1 && launch_transpose(d, dst, stream)) return check_launch("vt_materialize");
   int vec = vector_width(d);
   if ((uintptr_t)dst % 16) vec = 1;
   int esz = dtype_size(d.dtype);

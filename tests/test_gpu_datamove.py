@@ -278,6 +278,44 @@ def test_materialize_block_paths_bit_exact_with_canaries(gpu, name, shapes, chai
     check()
 
 
+TRANSPOSE_CASES = [
+    # source shape, perm: the source's contiguous dim is not the result's innermost one
+    ((100, 130), (1, 0)),                      # plain 2-D transpose, ragged tiles
+    ((64, 64), (1, 0)),                        # exactly one tile
+    ((3, 70, 96), (0, 2, 1)),                  # batched
+    ((5, 33, 7, 40), (3, 1, 2, 0)),            # the two directions far apart, two other digits
+    ((2, 200, 3, 17), (0, 3, 2, 1)),           # 17 >= 16: still tiled
+    ((6, 9, 50), (2, 0, 1)),                   # digits of the source's other dims merge (6 x 9 contiguous rows)
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape,perm", TRANSPOSE_CASES)
+def test_materialize_transposes_bit_exact_with_canaries(gpu, shape, perm, dtype):
+    """Permutes that move the source's contiguous dim away from the innermost place: the tiled
+    transposing copy (and, for the chains that do not fit its form, the per-vector kernel)."""
+    vt, tio, torch = gpu
+    rng = np.random.default_rng(31)
+    src = {"X": workloads.encode(rng.normal(size=shape).astype(np.float32), dtype)}
+    chain = [("R", "permute", ("X",), {"perm": perm})]
+    wl = workloads.Workload("transpose", dtype, src, chain, {"kind": "materialize", "x": "R"})
+    dense = dm_ops.run_chain(chain, wl.sources)["R"]
+    dw = tio.DeviceWorkload(wl)
+    d = dw.build("R")
+    assert d.block(512) * dense.dtype.itemsize < 32, "case meant for maps without blocks"
+    out, check = guarded(torch, tio, dense.shape, dtype)
+    vt.vt_materialize(d, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(tio.to_host_bits(out)), bits(dense)), d.dump()
+    check()
+    # the same through the one-operator copy of the materialized paths
+    out2, check2 = guarded(torch, tio, dense.shape, dtype)
+    vt.vt_copy_op("permute", [(shape, dtype, dw.tensors["X"].data_ptr())], {"perm": perm}, out2)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(tio.to_host_bits(out2)), bits(dense))
+    check2()
+
+
 def test_scatter_block_path_round_trip_with_canaries(gpu):
     """Store direction on the block path: a dense tensor written through the permuted map, every
     other byte of the target left alone, then read back through the same map."""
