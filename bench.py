@@ -461,6 +461,11 @@ def main():
         for name, shape in (("permute in 256-byte blocks", (4096, 128, 64)), ("permute in 1 KB blocks", (1024, 128, 256))):
             ds = [vt.build_chain([("P", "permute", ("S",), {"perm": (1, 0, 2)})], {"S": (shape, "f32", t.data_ptr())}, "P") for t in srcs]
             out[name] = rate(lambda i: vt.vt_materialize(ds[i % 4], dsts[i % 4]))
+        tr = [vt.build_chain([("P", "permute", ("S",), {"perm": (1, 0)})], {"S": ((4096, 8192), "f32", t.data_ptr())}, "P") for t in srcs]
+        out["transpose [4096, 8192] fp32 (k_copy_transpose)"] = rate(lambda i: vt.vt_materialize(tr[i % 4], dsts[i % 4]), reps=10)
+        views = [t.view(torch.float32).view(4096, 8192).t() for t in srcs]
+        outs = [t.view(torch.float32).view(8192, 4096) for t in dsts]
+        out["torch copy_ of the transposed view"] = rate(lambda i: outs[i % 4].copy_(views[i % 4]), reps=10)
         print(json.dumps({"copy_rates_128MiB": out}))
         return
     chains = [] if a.chains in ("", "none") else a.chains.split(",")
