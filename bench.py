@@ -236,57 +236,6 @@ def hbm_roofline(alg_bytes, us, kernel):
 
 def mfma_roofline(flops, us, kernel):
     tf = flops / (us * 1e-6) / 1e12
-    return {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None, "kernel": kernel}
-
-
-# chains whose full oracle pass takes seconds on the host (config 5 and the combine take tens of
-# seconds and are timed by the parity tests only)
-ORACLE_TIMED = ("c1", "c3", "c4", "rowsum_large", "qkv_store")
-
-
-def oracle_seconds(name):
-    """Wall time and cores of one full oracle pass of a chain (every operator materialized, then
-    the consumer, float64 unless the paper fixes the precision), inputs generated beforehand."""
-    import psutil
-    import workloads
-    from oracle.run import run_workload
-    wl = workloads.CONFIGS[name](seed=0)
-    proc = psutil.Process()
-    c0 = proc.cpu_times()
-    t0 = time.perf_counter()
-    run_workload(wl)
-    dt = time.perf_counter() - t0
-    c1 = proc.cpu_times()
-    cpu = (c1.user - c0.user) + (c1.system - c0.system)
-    return {"seconds": round(dt, 4), "cores": max(1, int(round(cpu / dt))), "kind": "oracle", "sample": "one full pass"}
-
-
-# ------------------------------------------------------------------------------------------
-# the chains besides the headline
-# ------------------------------------------------------------------------------------------
-# name -> (input copies the virtual path rotates over, launches to sample, HIP graph?)
-CHAIN_PLAN = {
-    "c1": (1, 256, True),
-    "c3": (3, 30, False),
-    "c4": (6, 240, True),
-    "c5": (1, 6, False),
-    "rowsum_large": (2, 60, True),
-    "qkv_store": (6, 240, True),
-    "decode_segment": (4, 120, True),
-    "paged": (4, 200, True),
-    "moe_combine": (1, 40, False),
-}
-
-
-def hbm_roofline(alg_bytes, us, kernel):
-    gbs = alg_bytes / (us * 1e-6) / 1e9
-    return {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
-            "traffic": None, "kernel": kernel}
-
-
-def mfma_roofline(flops, us, kernel):
-    tf = flops / (us * 1e-6) / 1e12
     r = {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
          "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None, "kernel": kernel}
     try:
@@ -363,6 +312,8 @@ def chain_stats(torch, name, no_graph=False, with_materialized=True):
     out["roofline"] = roof(v["median"])
     if "algorithmic_bytes" not in out["roofline"] and out["roofline"]["bound"] == "hbm":
         out["roofline"]["algorithmic_bytes"] = int(alg)
+    if name in CHAIN_TRAFFIC_SOURCE:
+        out["roofline"]["traffic"] = counter_traffic("chains_hbm_traffic.txt", CHAIN_TRAFFIC_SOURCE[name], key=name)
     if name == "c4":
         u = stats(sample_launches(torch, [mk(pipelines.Gemm(dw, fused=False)) for dw in dws], launches // 2, graph_ok))
         out["virtual_unfused_us"] = u
@@ -392,21 +343,28 @@ def chain_stats(torch, name, no_graph=False, with_materialized=True):
     return out
 
 
-def counter_traffic(profile_name, source_name):
+def counter_traffic(profile_name, source_name, key=None):
     """HBM bytes per launch from the committed rocprofv3 counter summary, or None when the summary
-    was made for another version of the kernel's source (it records the source's SHA-256)."""
+    was made for another version of the kernel's source (it records the source's SHA-256).  A
+    summary that covers several kernels labels its lines: `traffic_bytes_per_launch[key]: N`."""
     tpath = os.path.join(ROOT, "profiles", profile_name)
     spath = os.path.join(ROOT, "paper_2604_09558_amd", "csrc", source_name)
     if not (os.path.exists(tpath) and os.path.exists(spath)):
         return None
     digest = hashlib.sha256(open(spath, "rb").read()).hexdigest()
+    tag = "" if key is None else "[%s]" % key
     traffic, same = None, False
     for line in open(tpath):
-        if line.startswith("traffic_bytes_per_launch:"):
+        if line.startswith("traffic_bytes_per_launch%s:" % tag):
             traffic = int(float(line.split(":")[1]))
-        if line.startswith("source_sha256:"):
+        if line.startswith("source_sha256%s:" % tag):
             same = line.split(":")[1].strip() == digest
     return traffic if same else None
+
+
+# chain -> source file of its dominant kernel, for the chains whose HBM counters are committed
+CHAIN_TRAFFIC_SOURCE = {"c4": "vt_ln_gemm.hip", "qkv_store": "vt_gemm_store.hip", "moe_combine": "vt_kernels.hip",
+                        "rowsum_large": "vt_kernels.hip"}
 
 
 def main():
