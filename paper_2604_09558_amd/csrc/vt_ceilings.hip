@@ -10,6 +10,8 @@
 //            streaming loads and stores (the mixture-of-experts combine's shape)
 //   wread    a [K, N] bf16 matrix read once in the pattern of the skinny projection (a workgroup
 //            owns 128 columns of a K slice, a load instruction reads 4 rows x 256 bytes)
+//   mix      one fp16 [100352, 128] array read and three times its bytes written (whole 768-byte
+//            output rows, streaming stores): the fused LayerNorm + linear layer's traffic
 //   copy     the runtime's device-to-device copy
 // Every launch rotates over input copies larger than the last-level cache; times are HIP events
 // over back-to-back launches, the gap between launches included.
@@ -92,6 +94,27 @@ __global__ void __launch_bounds__(256) k_wread(const char* __restrict__ W, float
   if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345678u) out[threadIdx.x] = 1.f;   // false for the inputs used; keeps the loads
 }
 
+// a wave copies rows: 16 lanes read a row's 256 bytes, 48 lanes write one 768-byte output row
+__global__ void __launch_bounds__(256) k_mix(const u32x4* __restrict__ X, u32x4* __restrict__ O, uint32_t R, int streaming) {
+  const uint32_t lane = threadIdx.x & 63u, wave = (blockIdx.x * 256u + threadIdx.x) >> 6, n_waves = gridDim.x * 4u;
+  for (uint32_t r0 = wave * 4u; r0 < R; r0 += n_waves * 4u) {      // R is a multiple of 4
+    const u32x4 v = __builtin_nontemporal_load(X + (size_t)r0 * 16 + lane);            // rows r0 .. r0+3
+    u32x4 o[3];
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      // output unit 64 j + lane of the 192 units of rows r0 .. r0+3 (48 per row): any of the row's inputs will do
+      const uint32_t u = 64u * j + lane, src_lane = (u / 48u) * 16u + (u % 48u) % 16u;
+      for (int e = 0; e < 4; ++e) o[j][e] = (uint32_t)__shfl((int)v[e], (int)src_lane, 64) + j;
+    }
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      u32x4* dst = O + (size_t)r0 * 48 + 64u * j + lane;
+      if (streaming) __builtin_nontemporal_store(o[j], dst);
+      else *dst = o[j];
+    }
+  }
+}
+
 static hipEvent_t e0, e1;
 
 template <typename F>
@@ -168,6 +191,23 @@ int main() {
     const double us = timed_us(64, [&](int i) { hipLaunchKernelGGL(k_wread, dim3(4, N / 128), dim3(256), 0, 0, W[i % nb], out, K / 4, row_bytes); });
     report("wread: bf16 [4096, 6144] read once by 192 workgroups (128 columns x 1024 rows each), 50 MB", (double)K * row_bytes, us);
     for (int i = 0; i < nb; ++i) CK(hipFree(W[i]));
+  }
+  {
+    const uint32_t R = 100352, nb = 6;                 // 6 x 103 MB: more than the last-level cache
+    u32x4 *X[nb], *O[nb];
+    for (uint32_t i = 0; i < nb; ++i) X[i] = static_cast<u32x4*>(dev_zero((size_t)R * 256, 1)), O[i] = static_cast<u32x4*>(dev_zero((size_t)R * 768, 0));
+    for (int streaming = 0; streaming < 2; ++streaming)
+      for (int grid : {512, 2048}) {
+        const double us = timed_us(60, [&](int i) { hipLaunchKernelGGL(k_mix, dim3(grid), dim3(256), 0, 0, X[i % nb], O[i % nb], R, streaming); });
+        char what[128];
+        snprintf(what, sizeof(what), "mix: fp16 [100352, 128] read, [100352, 384] written, %s stores, %d workgroups, 103 MB", streaming ? "streaming" : "ordinary",
+                 grid);
+        report(what, (double)R * 1024, us);
+      }
+    for (uint32_t i = 0; i < nb; ++i) {
+      CK(hipFree(X[i]));
+      CK(hipFree(O[i]));
+    }
   }
   {
     const size_t n = 128u << 20;
