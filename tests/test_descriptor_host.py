@@ -111,8 +111,11 @@ def check_runs(d):
                 broke = True
         # maximal among runs that are products of trailing refined digits: some block
         # boundary must really break, unless the run already covers the piece
-        # (an index table may be consecutive by accident: the analysis never looks at its entries)
-        assert broke or run == size or ",T" in d.dump(), (p, run, d.dump())
+        # (an index table may be consecutive by accident: the analysis never looks at its entries;
+        # below a stacked stage it reasons from the alignment of the piece's base against the lower
+        # digits, not from the piece's extent, so a piece that happens to end before the lower
+        # digit wraps may be contiguous beyond its run: sound, not maximal)
+        assert broke or run == size or ",T" in d.dump() or "| base=" in d.dump(), (p, run, d.dump())
     assert info["run"] == min(runs)
 
 

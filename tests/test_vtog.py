@@ -1,6 +1,5 @@
 """Opportunity graph (Alg. 1) and greedy points-to graph construction (Alg. 2): the paper's
 worked examples, and the greedy result against exhaustive search on small graphs."""
-import itertools
 
 import numpy as np
 import pytest
