@@ -91,6 +91,7 @@ def capture(torch, fns):
 
 
 GRAPH_CAP = 512     # launches per HIP graph in the timed region
+GRAPH_MIN = 32      # launches per HIP graph of the per-chain samples
 
 
 def time_steps(torch, step_fns, steps, warmup, use_graph):
@@ -138,14 +139,16 @@ def time_steps(torch, step_fns, steps, warmup, use_graph):
 
 def sample_launches(torch, fns, launches, use_graph, warmup=2):
     """Microseconds per launch of fns (rotating), as a list of samples.  Graph mode: a graph holds
-    every fn at least once and at least 8 launches; a sample is one replay's event time divided
-    by its launches.  Eager mode: one event before every launch, a sample is the time between
-    neighbours (for kernels much longer than a launch from Python)."""
+    every fn the same number of times and at least GRAPH_MIN launches (a replay costs several
+    microseconds between its events, which 8 launches per graph showed as more than 1 us per
+    launch); a sample is one replay's event time divided by its launches.  Eager mode: one event
+    before every launch, a sample is the time between neighbours (for kernels much longer than a
+    launch from Python)."""
     stream = torch.cuda.current_stream()
     if use_graph:
-        per = len(fns) * max(1, -(-8 // len(fns)))
+        per = len(fns) * max(1, -(-GRAPH_MIN // len(fns)))
         g = capture(torch, (fns * per)[:per])
-        n = max(3, -(-launches // per))
+        n = max(5, -(-launches // per))
         for _ in range(warmup):
             g.replay()
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
@@ -218,12 +221,12 @@ def oracle_seconds(name):
 CHAIN_PLAN = {
     "c1": (1, 256, True),
     "c3": (3, 30, False),
-    "c4": (6, 240, True),
+    "c4": (6, 360, True),
     "c5": (1, 6, False),
-    "rowsum_large": (2, 60, True),
-    "qkv_store": (6, 240, True),
-    "decode_segment": (4, 120, True),
-    "paged": (4, 200, True),
+    "rowsum_large": (2, 256, True),
+    "qkv_store": (6, 360, True),
+    "decode_segment": (4, 256, True),
+    "paged": (4, 320, True),
     "moe_combine": (1, 40, False),
 }
 
