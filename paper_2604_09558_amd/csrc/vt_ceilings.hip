@@ -13,12 +13,18 @@
 //   mix      one fp16 [100352, 128] array read and three times its bytes written (whole 768-byte
 //            output rows, streaming stores): the fused LayerNorm + linear layer's traffic
 //   copy     the runtime's device-to-device copy
+//   mfma     the GEMM consumer's matrix instruction (32x32x16, bf16) in a loop without any memory
+//            access: 4 x 4 register blocks per wave as in the GEMM's tile, one wave per SIMD, with
+//            operands that are all zero and with normally distributed ones; the shader clock is
+//            read beside the wall clock inside the loop
 // Every launch rotates over input copies larger than the last-level cache; times are HIP events
 // over back-to-back launches, the gap between launches included.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
 
 #define CK(x)                                                                      \
   do {                                                                             \
@@ -115,6 +121,38 @@ __global__ void __launch_bounds__(256) k_mix(const u32x4* __restrict__ X, u32x4*
   }
 }
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// operands: 4 + 4 register sets per lane read once from `ops` ([8][256 threads] 16-byte units per
+// workgroup-independent table), then `iters` rounds of the 16 products a[i] x b[j]
+__global__ void __launch_bounds__(256) k_mfma(const u32x4* __restrict__ ops, float* __restrict__ out, unsigned long long* __restrict__ clocks, int iters) {
+  bf16x8 a[4], b[4];
+  for (int i = 0; i < 4; ++i) {
+    a[i] = __builtin_bit_cast(bf16x8, ops[i * 256 + threadIdx.x]);
+    b[i] = __builtin_bit_cast(bf16x8, ops[(4 + i) * 256 + threadIdx.x]);
+  }
+  f32x16 acc[16];
+  for (int i = 0; i < 16; ++i)
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+  const unsigned long long c0 = clock64(), w0 = wall_clock64();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i * 4 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i * 4 + j], 0, 0, 0);
+  }
+  const unsigned long long c1 = clock64(), w1 = wall_clock64();
+  float sum = 0.f;
+  for (int i = 0; i < 16; ++i)
+    for (int e = 0; e < 16; ++e) sum += acc[i][e];
+  out[blockIdx.x * 256 + threadIdx.x] = sum;
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    clocks[0] = c1 - c0;
+    clocks[1] = w1 - w0;
+  }
+}
+
 static hipEvent_t e0, e1;
 
 template <typename F>
@@ -207,6 +245,42 @@ int main() {
     for (uint32_t i = 0; i < nb; ++i) {
       CK(hipFree(X[i]));
       CK(hipFree(O[i]));
+    }
+  }
+  {
+    // 16 products of 32768 multiply-adds-as-2-flops per round and wave, 4 waves per workgroup, 256 workgroups
+    const int iters = 2048, grid = 256;
+    const double flops = (double)grid * 4 * iters * 16 * 32768.0;
+    u32x4* ops = static_cast<u32x4*>(dev_zero(8 * 256 * 16, 0));
+    unsigned long long* clocks = static_cast<unsigned long long*>(dev_zero(16, 0));
+    float* sums = static_cast<float*>(dev_zero((size_t)grid * 256 * 4, 0));
+    int wall_khz = 100000;
+    CK(hipDeviceGetAttribute(&wall_khz, hipDeviceAttributeWallClockRate, 0));
+    for (int normal = 0; normal < 2; ++normal) {
+      if (normal) {
+        // bf16 values of a standard normal distribution (Box-Muller over a fixed linear congruential sequence)
+        unsigned short* h = static_cast<unsigned short*>(malloc(8 * 256 * 16));
+        unsigned long long st = 12345;
+        auto uni = [&]() {
+          st = st * 6364136223846793005ull + 1442695040888963407ull;
+          return ((st >> 11) + 1) * (1.0 / 9007199254740993.0);
+        };
+        for (int i = 0; i < 8 * 256 * 8; ++i) {
+          const float v = (float)(sqrt(-2.0 * log(uni())) * cos(6.283185307179586 * uni()));
+          unsigned u;
+          memcpy(&u, &v, 4);
+          h[i] = (unsigned short)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+        }
+        CK(hipMemcpy(ops, h, 8 * 256 * 16, hipMemcpyHostToDevice));
+        free(h);
+      }
+      const double us = timed_us(40, [&](int) { hipLaunchKernelGGL(k_mfma, dim3(grid), dim3(256), 0, 0, ops, sums, clocks, iters); });
+      unsigned long long c[2];
+      CK(hipMemcpy(c, clocks, 16, hipMemcpyDeviceToHost));
+      printf("mfma: 32x32x16 bf16, no memory access, %s operands: %8.2f us  %7.1f TFLOP/s  %4.1f %% of 2.5 PFLOP/s  shader clock %.2f GHz\n",
+             normal ? "normally distributed" : "zero                ", us, flops / us / 1e6, flops / us / 1e6 / 2500.0 * 100.0,
+             (double)c[0] / ((double)c[1] / (wall_khz * 1e3)) / 1e9);
+      fflush(stdout);
     }
   }
   {
