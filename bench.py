@@ -367,7 +367,7 @@ def counter_traffic(profile_name, source_name, key=None):
 
 # chain -> source file of its dominant kernel, for the chains whose HBM counters are committed
 CHAIN_TRAFFIC_SOURCE = {"c4": "vt_ln_gemm.hip", "qkv_store": "vt_gemm_store.hip", "moe_combine": "vt_kernels.hip",
-                        "rowsum_large": "vt_kernels.hip"}
+                        "rowsum_large": "vt_kernels.hip", "c3": "vt_gemm.hip", "c5": "vt_gemm.hip", "paged": "vt_attn.hip"}
 
 
 def main():

@@ -31,19 +31,22 @@ def test_counter_traffic_is_tied_to_the_kernel_source():
 
 def test_chain_traffic_entries_are_keyed_and_tied_to_their_sources():
     """The chains' counter summary holds one labelled entry per chain; each is reported only for the
-    source file whose hash it records, and none of them shows re-reads (traffic within 5 % above the
-    algorithmic bytes the summary states beside it)."""
+    source file whose hash it records, and none of the memory-bound ones shows re-reads (traffic
+    within 5 % above the algorithmic bytes the summary states beside it)."""
     sys.path.insert(0, ROOT)
     import re
     import bench
     text = open(os.path.join(ROOT, "profiles", "chains_hbm_traffic.txt")).read()
     alg = [int(m) for m in re.findall(r"algorithmic (\d+) B", text)]
-    assert len(alg) == len(bench.CHAIN_TRAFFIC_SOURCE) == 4
+    assert len(alg) == len(bench.CHAIN_TRAFFIC_SOURCE) == 7
     for (key, src), a in zip(bench.CHAIN_TRAFFIC_SOURCE.items(), alg):
         t = bench.counter_traffic("chains_hbm_traffic.txt", src, key=key)
         if t is None:       # the kernel's source changed after the counters were read: bench reports null
             continue
-        assert a <= t <= 1.05 * a, (key, t, a)
-        assert bench.counter_traffic("chains_hbm_traffic.txt", "vt_attn.hip", key=key) is None
+        if key in ("c3", "c5"):     # the GEMM's panels are read once per compute die and round (not HBM-bound)
+            assert a <= t, (key, t, a)
+        else:
+            assert a <= t <= 1.05 * a, (key, t, a)
+        assert bench.counter_traffic("chains_hbm_traffic.txt", "vt_build.cpp", key=key) is None      # another source: stale
     assert bench.counter_traffic("chains_hbm_traffic.txt", "vt_kernels.hip", key="no_such_chain") is None
     assert bench.counter_traffic("chains_hbm_traffic.txt", "vt_kernels.hip") is None      # unlabelled lines: none in this file
