@@ -280,16 +280,19 @@ __global__ void k_zero_store_ws(uint32_t* p, size_t n) {
   if (i < n) p[i] = 0u;
 }
 
-// Slices of K per block: a power of two (equal slices), about 192 workgroups in all (measured
-// best on the 4096 x 6144 projection: fewer leave compute units idle, more lengthen the merge),
-// at least one tile per wave.
+// Slices of K per block: as many as keep every workgroup on a compute unit of its own (one unit
+// draws only about 40 GB/s from memory, so the matrix has to be spread over all of them, and a
+// second workgroup on a unit would finish last; measured on the 4096 x 6144 projection, 48 column
+// blocks: 4 slices 14.75 us, 5: 14.5, 6: 16.7, 7: 16.6, 8: 15.9), at least one tile per wave, at
+// most 64.  The slices are whole tiles and need not be equal.
 int choose_k_splits(int64_t blocks, int64_t K) {
+  static const int n_cu = [] {
+    int dev = 0, n = 256;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 256;
+    return n > 0 ? n : 256;
+  }();
   const int64_t max_splits = std::max<int64_t>(1, K / (kTileK * kWaves));
-  const int target = 192;
-  const int64_t want = std::min<int64_t>(std::min(std::max<int64_t>(1, (target + blocks - 1) / blocks), max_splits), 64);
-  int ns = 1;
-  while (ns * 2 <= want) ns *= 2;
-  return ns;
+  return (int)std::min<int64_t>(std::min(std::max<int64_t>(1, n_cu / blocks), max_splits), 64);
 }
 
 size_t ticket_area(int64_t blocks) { return (size_t)((blocks * 4 + 255) / 256 * 256); }
