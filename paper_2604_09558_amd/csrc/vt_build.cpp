@@ -628,6 +628,13 @@ static void finalize_piece(const vt_desc& d, Piece& p) {
     if (p.hi[i] - p.lo[i] != d.shape[i]) open = false;  // the piece is narrower than the tensor here
   }
   g = gcd64(g, p.v.base);
+  // A piece that is one run as a whole sits at cur .. cur + run - 1 of the next stage's index space;
+  // while that range stays inside one dense run of the stage below, it remains one range (its
+  // extent decides, not the alignment of its start).
+  int64_t piece_size = 1;
+  for (int i = 0; i < n; ++i) piece_size *= p.hi[i] - p.lo[i];
+  bool whole = run == piece_size && p.v.base >= 0;
+  int64_t cur = p.v.base;
   for (const Stage& s : p.v.lower) {
     int64_t r2 = 1, e2 = 1, g2 = 0;
     bool op2 = true;
@@ -641,6 +648,20 @@ static void finalize_piece(const vt_desc& d, Piece& p) {
         g2 = gcd64(g2, dg.stride);
       }
     }
+    if (whole && cur % r2 + run <= r2) {
+      int64_t x = cur;
+      cur = s.base;
+      for (int k = (int)s.digits.size() - 1; k >= 0; --k) {
+        int64_t dig = x % s.digits[k].radix;
+        x /= s.digits[k].radix;
+        if (s.digits[k].table >= 0) dig = d.tables[s.digits[k].table].host[s.digits[k].table_off + dig];
+        cur += dig * s.digits[k].stride;
+      }
+      g = cur;                     // the one offset at which the range starts below
+      whole = cur >= 0;
+      continue;
+    }
+    whole = false;
     // blocks of c consecutive indices are contiguous below iff c | run, c | r2 and c divides
     // every offset at which a run of the stage above can start
     int64_t c = gcd64(run, r2);

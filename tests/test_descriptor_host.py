@@ -412,6 +412,26 @@ def test_stacked_stage_case():
     check_desc_against_dense(d, dense, wl)
 
 
+def test_a_piece_inside_one_dense_run_of_the_stage_below_keeps_its_run():
+    """expand -> reshape -> split leaves a stacked stage; the two elements kept are neighbours in the
+    source (elements 0 and 1 of the first row of three), although neither the start's alignment
+    nor the lower digit's radix (3) is a multiple of the run (2): the extent decides."""
+    chain = [("v0", "expand", ("S0",), {"shape": (3, 2, 3)}),
+             ("v1", "reshape", ("v0",), {"shape": (1, 18)}),
+             ("v2", "split", ("v1",), {"dim": 1, "sizes": (2, 16), "output": 0}),
+             ("R", "reshape", ("v2",), {"shape": (1, 2)})]
+    d = vt.build_chain(chain, {"S0": ((3, 1, 3), "f32")}, "R")
+    assert d.info()["run"] == 2
+    assert d.eval_host((0, 0)) == (0, 0) and d.eval_host((0, 1)) == (0, 1)
+    check_runs(d)
+    # one element further and the piece crosses into the broadcast copy of the row: no run of 4
+    chain[2] = ("v2", "split", ("v1",), {"dim": 1, "sizes": (4, 14), "output": 0})
+    chain[3] = ("R", "reshape", ("v2",), {"shape": (1, 4)})
+    d = vt.build_chain(chain, {"S0": ((3, 1, 3), "f32")}, "R")
+    assert d.info()["run"] == 1
+    check_runs(d)
+
+
 def test_error_paths():
     src = {"X": ((4, 6), "f32"), "Y": ((4, 5), "f32"), "H": ((4, 6), "f16")}
 
