@@ -463,6 +463,9 @@ def main():
         alg = algorithmic_bytes_c2(B, Hkv, G, S, D, n_splits)
         wall_ms, ev_ms = time_steps(torch, [mk(p) for p in virt], a.steps, a.warmup, not a.no_graph)
         per_replay = stats(sample_launches(torch, [mk(p) for p in virt], 400, not a.no_graph))
+        # the same kernel on ONE input copy, which the 256 MB Infinity Cache then serves: reported
+        # beside the rotating-copies figure, never used for `value` or the roofline
+        warm = stats(sample_launches(torch, [mk(virt[0])], 400, not a.no_graph))
         value = alg / (wall_ms * 1e-3) / 1e9
         achieved = alg / (ev_ms * 1e-3) / 1e9
         out.update({
@@ -475,6 +478,7 @@ def main():
                        "input_copies_rotated": a.copies, "launch": "eager" if a.no_graph else "hip graph replay"},
             "virtual_us": round(wall_ms * 1e3, 2),
             "virtual_us_per_replay": per_replay,
+            "virtual_us_one_copy_cached": warm,
             "hbm_pct_of_peak": round(100.0 * value / HBM_PEAK_GBS, 1),
             "algorithmic_bytes": alg,
             "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
