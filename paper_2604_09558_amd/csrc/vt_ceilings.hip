@@ -269,8 +269,12 @@ int main() {
     const size_t row_bytes = (size_t)N * 2;
     char* W[nb];
     for (int i = 0; i < nb; ++i) W[i] = static_cast<char*>(dev_zero((size_t)K * row_bytes, 1));
-    const double us = timed_us(64, [&](int i) { hipLaunchKernelGGL(k_wread, dim3(4, N / 128), dim3(256), 0, 0, W[i % nb], out, K / 4, row_bytes); });
-    report("wread: bf16 [4096, 6144] read once by 192 workgroups (128 columns x 1024 rows each), 50 MB", (double)K * row_bytes, us);
+    for (int slices : {4, 2, 1}) {      // fewer workgroups: what one compute unit can draw
+      const double us = timed_us(64, [&](int i) { hipLaunchKernelGGL(k_wread, dim3(slices, N / 128), dim3(256), 0, 0, W[i % nb], out, K / slices, row_bytes); });
+      char what[128];
+      snprintf(what, sizeof(what), "wread: bf16 [4096, 6144] read once by %d workgroups (128 columns x %d rows each), 50 MB", slices * N / 128, K / slices);
+      report(what, (double)K * row_bytes, us);
+    }
     for (int i = 0; i < nb; ++i) CK(hipFree(W[i]));
   }
   {
